@@ -1,0 +1,409 @@
+"""CPU oracle for pdADMM-G / pdADMM-G-Q (arXiv 2105.09837). TEST INFRASTRUCTURE ONLY.
+
+Plain numpy, fp64 arithmetic on fp32-representable inputs, written from the paper:
+Section 3.1 (Problems 1-2, the augmentation X_k = H psi_k(A)), Section 3.2 (augmented
+Lagrangian L_rho, Algorithm 1), Section 3.3 (Problem 3, the set Delta), Section 5.1
+(renormalised adjacency, Psi = {I, A~, A~^2, A~^3}, ReLU, cross-entropy) and Appendix A/B
+(the sub-problem solutions). Every phi is evaluated literally (W p + b is recomputed each
+time); there is no blocking, fusion, caching or algebraic shortcut.
+
+Only tests, the smoke check and the benchmark's cpu_baseline leg may import this module.
+It shares no code with the HIP library and does not import it.
+
+Storage convention: the paper's n x |V| matrices are held node-major, i.e. as numpy
+arrays of shape [|V|, n] (the transpose); W_l is [n_l, n_{l-1}] as in the paper, so
+W_l p_l + b_l is `p @ W.T + b`.
+
+Readings of points the paper leaves open (all are conventions, "parity unpinned" by the
+paper itself; the tests pin them only through the mathematical properties they imply):
+  * backtracking schedule for tau_l / theta_l (Appendix A gives only the acceptance
+    condition): start each iteration at previous/eta, multiply by eta until accepted;
+  * b-update: b_l is one vector broadcast over all nodes, so the exact minimiser of phi
+    over b_l is b - mean_over_nodes(W p + b - z); the printed step "gradient / nu" equals
+    that only if the curvature nu*|V| is used, which is the reading taken;
+  * choice between the two ReLU candidates of the z-update: the one with the smaller
+    value of the z-subproblem objective, ties to the non-positive candidate;
+  * FISTA for z_L: fixed number of steps, step 1/(nu + 1/2), start at z_L^k, risk = sum
+    (not mean) of cross-entropy over labelled nodes; unlabelled nodes take z = W p + b;
+  * Delta is a uniform grid (lo, hi, levels); the nearest-level decision is taken in fp32
+    (the precision of the stored p), ties to the even index.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+from typing import List, Optional, Tuple
+
+import numpy as np
+
+F32 = np.float32
+F64 = np.float64
+
+
+# --------------------------------------------------------------------------------------
+# Graph preprocessing (Section 5.1) and augmentation (Section 3.1)
+# --------------------------------------------------------------------------------------
+def normalize_adj(rowptr: np.ndarray, colidx: np.ndarray):
+    """A~ = (D+I)^(-1/2) (A+I) (D+I)^(-1/2), D_ii = sum_j A_ij (Section 5.1).
+
+    Input: CSR pattern of the symmetric binary A without self-loops. Output: CSR of A~ with
+    the diagonal inserted, columns ascending, values computed in fp64 as
+    1/sqrt((d_i+1)(d_j+1)) and rounded once to fp32."""
+    n = rowptr.size - 1
+    deg = np.diff(rowptr).astype(np.int64)
+    out_rowptr = np.zeros(n + 1, dtype=np.int64)
+    out_rowptr[1:] = np.cumsum(deg + 1)
+    out_col = np.empty(out_rowptr[-1], dtype=np.int32)
+    out_val = np.empty(out_rowptr[-1], dtype=F32)
+    for i in range(n):
+        cols = colidx[rowptr[i]:rowptr[i + 1]].astype(np.int64)
+        cols = np.sort(np.concatenate([cols, [i]]))
+        w = 1.0 / np.sqrt(((deg[i] + 1) * (deg[cols] + 1)).astype(F64))
+        out_col[out_rowptr[i]:out_rowptr[i + 1]] = cols
+        out_val[out_rowptr[i]:out_rowptr[i + 1]] = w.astype(F32)
+    return out_rowptr.astype(np.int32), out_col, out_val
+
+
+def augment(rowptr, colidx, vals, X, hops: int) -> np.ndarray:
+    """X_aug = [X | A~X | ... | A~^hops X] along the feature axis (Sections 3.1, 5.1).
+
+    fp32 result with a fully specified rounding order so that it can be compared bit for
+    bit: every product val*x is rounded to fp32, then added to an fp32 accumulator that
+    starts at +0, strictly in the CSR (ascending column) order of the row."""
+    X = np.ascontiguousarray(X, dtype=F32)
+    n, d = X.shape
+    out = np.empty((n, (hops + 1) * d), dtype=F32)
+    out[:, :d] = X
+    deg = np.diff(rowptr)
+    order = np.argsort(-deg, kind="stable")       # rows sorted by decreasing length
+    sorted_deg = deg[order]
+    prev = X
+    for k in range(1, hops + 1):
+        acc = np.zeros((n, d), dtype=F32)
+        for pos in range(int(deg.max()) if n else 0):
+            cnt = int(np.searchsorted(-sorted_deg, -pos, side="left"))  # rows with deg > pos
+            rows = order[:cnt]
+            e = rowptr[rows] + pos
+            prod = vals[e].astype(F32)[:, None] * prev[colidx[e]]      # fp32 multiply
+            acc[rows] = acc[rows] + prod                                # fp32 add
+        out[:, k * d:(k + 1) * d] = acc
+        prev = acc
+    return out
+
+
+def augment_definition_dense(rowptr, colidx, X, hops: int) -> np.ndarray:
+    """The same quantity straight from its definition, dense fp64 (small graphs only):
+    builds A, D, A~ as dense matrices and multiplies matrix powers (Section 5.1)."""
+    n = rowptr.size - 1
+    A = np.zeros((n, n))
+    for i in range(n):
+        A[i, colidx[rowptr[i]:rowptr[i + 1]]] = 1.0
+    dinv = np.diag(1.0 / np.sqrt(A.sum(axis=1) + 1.0))
+    At = dinv @ (A + np.eye(n)) @ dinv
+    Xd = X.astype(F64)
+    return np.concatenate([np.linalg.matrix_power(At, k) @ Xd for k in range(hops + 1)], axis=1)
+
+
+# --------------------------------------------------------------------------------------
+# Projection onto Delta (Section 3.3, Appendix B)
+# --------------------------------------------------------------------------------------
+@dataclass(frozen=True)
+class Grid:
+    """Uniform Delta = {lo + i*step : i = 0..levels-1}; all members are fp32 numbers."""
+    lo: float
+    hi: float
+    levels: int
+
+    @property
+    def step32(self) -> np.float32:
+        return F32((F32(self.hi) - F32(self.lo)) / F32(self.levels - 1))
+
+    def members(self) -> np.ndarray:
+        i = np.arange(self.levels, dtype=F32)
+        return (F32(self.lo) + (i * self.step32).astype(F32)).astype(F32)
+
+
+def quantize(v, grid: Grid) -> Tuple[np.ndarray, np.ndarray]:
+    """argmin_{delta in Delta} |delta - v| elementwise (Appendix B), decision in fp32:
+    t = (v - lo)/step, index = round-half-even(t) clamped to [0, levels-1],
+    delta = lo + index*step (product rounded, then sum rounded). NaN maps to index 0."""
+    v32 = np.asarray(v).astype(F32)
+    lo = F32(grid.lo)
+    step = grid.step32
+    with np.errstate(invalid="ignore", over="ignore"):
+        t = ((v32 - lo).astype(F32) / step).astype(F32)
+        r = np.rint(t)
+    r = np.where(np.isnan(r), 0.0, r)
+    idx = np.clip(r, 0, grid.levels - 1).astype(np.int32)
+    val = (lo + (idx.astype(F32) * step).astype(F32)).astype(F32)
+    return idx, val
+
+
+# --------------------------------------------------------------------------------------
+# State and the pieces of L_rho (Section 3.2)
+# --------------------------------------------------------------------------------------
+def relu(x):
+    return np.maximum(x, 0.0)
+
+
+@dataclass
+class State:
+    """All variables of Problem 2 plus the duals and the backtracking parameters.
+    Python index i holds the paper's layer l = i + 1. p[0] = X is fixed."""
+    W: List[np.ndarray]
+    b: List[np.ndarray]
+    z: List[np.ndarray]
+    p: List[np.ndarray]            # p[0..L-1]  <-> p_1..p_L
+    q: List[np.ndarray]            # q[0..L-2]  <-> q_1..q_{L-1}
+    u: List[np.ndarray]            # u[0..L-2]
+    y: np.ndarray                  # class ids, [N]
+    mask: Optional[np.ndarray]     # labelled nodes (bool [N]) or None = all
+    rho: float
+    nu: float
+    grid: Optional[Grid] = None    # pdADMM-G-Q when set
+    tau: List[float] = field(default_factory=list)     # tau[i] for p[i], i >= 1
+    theta: List[float] = field(default_factory=list)
+    eta: float = 2.0
+    bt_max_trials: int = 64
+    fista_iters: int = 20
+    p_trials: List[int] = field(default_factory=list)
+    w_trials: List[int] = field(default_factory=list)
+
+    @property
+    def L(self) -> int:
+        return len(self.W)
+
+    def copy(self) -> "State":
+        c = lambda xs: [np.array(x, copy=True) for x in xs]
+        return State(c(self.W), c(self.b), c(self.z), c(self.p), c(self.q), c(self.u), self.y,
+                     self.mask, self.rho, self.nu, self.grid, list(self.tau), list(self.theta),
+                     self.eta, self.bt_max_trials, self.fista_iters, list(self.p_trials),
+                     list(self.w_trials))
+
+
+def init_forward(X_aug, W0, b0, y, rho, nu, grid: Optional[Grid] = None, mask=None,
+                 tau0: float = 1.0, theta0: float = 1.0, **kw) -> State:
+    """Forward-consistent start: z_l = W_l p_l + b_l, q_l = f(z_l), p_{l+1} = q_l (projected
+    onto Delta for -Q), u_l = 0. (The paper only says 'initialise'; its theorems hold from
+    any start.)"""
+    L = len(W0)
+    W = [np.asarray(w, dtype=F64) for w in W0]
+    b = [np.asarray(v, dtype=F64) for v in b0]
+    p = [np.asarray(X_aug, dtype=F64)]
+    z, q, u = [], [], []
+    for i in range(L):
+        zi = p[i] @ W[i].T + b[i]
+        z.append(zi)
+        if i < L - 1:
+            qi = relu(zi)
+            q.append(qi)
+            nxt = qi
+            if grid is not None:
+                nxt = quantize(qi, grid)[1].astype(F64)
+            p.append(np.array(nxt, dtype=F64, copy=True))
+            u.append(np.zeros_like(qi))
+    return State(W, b, z, p, q, u, np.asarray(y), mask, float(rho), float(nu), grid,
+                 [tau0] * L, [theta0] * L, p_trials=[0] * L, w_trials=[0] * L, **kw)
+
+
+def phi(st: State, i: int, p=None, W=None, b=None) -> float:
+    """phi for layer l = i+1 (Section 3.2): (nu/2)||z - W p - b||^2, plus for l >= 2
+    <u_{l-1}, p - q_{l-1}> + (rho/2)||p - q_{l-1}||^2."""
+    p = st.p[i] if p is None else p
+    W = st.W[i] if W is None else W
+    b = st.b[i] if b is None else b
+    res = st.z[i] - (p @ W.T + b)
+    val = 0.5 * st.nu * float(np.sum(res * res))
+    if i >= 1:
+        dpq = p - st.q[i - 1]
+        val += float(np.sum(st.u[i - 1] * dpq)) + 0.5 * st.rho * float(np.sum(dpq * dpq))
+    return val
+
+
+def grad_p(st: State, i: int) -> np.ndarray:
+    """Gradient of phi in p_l (l = i+1 >= 2): nu W^T (W p + b - z) + u_{l-1} + rho (p - q_{l-1})."""
+    r = st.p[i] @ st.W[i].T + st.b[i] - st.z[i]
+    return st.nu * (r @ st.W[i]) + st.u[i - 1] + st.rho * (st.p[i] - st.q[i - 1])
+
+
+def grad_W(st: State, i: int) -> np.ndarray:
+    """Gradient of phi in W_l: nu (W p + b - z) p^T."""
+    r = st.p[i] @ st.W[i].T + st.b[i] - st.z[i]
+    return st.nu * (r.T @ st.p[i])
+
+
+def grad_b(st: State, i: int) -> np.ndarray:
+    """Gradient of phi in b_l: nu * sum over nodes of (W p + b - z)."""
+    r = st.p[i] @ st.W[i].T + st.b[i] - st.z[i]
+    return st.nu * r.sum(axis=0)
+
+
+class BacktrackingError(RuntimeError):
+    pass
+
+
+# --------------------------------------------------------------------------------------
+# Sub-problem updates (Appendix A, B)
+# --------------------------------------------------------------------------------------
+def update_p(st: State, i: int) -> None:
+    """p_l <- argmin U_l(p; tau) (+ indicator of Delta for -Q), tau raised until
+    phi(p_new) <= U_l(p_new; tau) (Appendix A 'update p', Appendix B)."""
+    g = grad_p(st, i)
+    if not np.any(g):
+        st.p_trials[i] = 0
+        return
+    p_old = st.p[i]
+    phi0 = phi(st, i)
+    t = st.tau[i] / st.eta
+    for trial in range(1, st.bt_max_trials + 1):
+        cand = p_old - g / t
+        if st.grid is not None:
+            cand = quantize(cand, st.grid)[1].astype(F64)
+        d = cand - p_old
+        upper = phi0 + float(np.sum(g * d)) + 0.5 * t * float(np.sum(d * d))
+        if phi(st, i, p=cand) <= upper:
+            st.tau[i] = t
+            st.p[i] = cand
+            st.p_trials[i] = trial
+            return
+        t *= st.eta
+    raise BacktrackingError(f"p-update of layer {i + 1}: no tau accepted")
+
+
+def update_W(st: State, i: int) -> None:
+    """W_l <- W_l - grad_W phi / theta, theta raised until phi(W_new) <= V_l(W_new; theta)."""
+    G = grad_W(st, i)
+    if not np.any(G):
+        st.w_trials[i] = 0
+        return
+    W_old = st.W[i]
+    phi0 = phi(st, i)
+    t = st.theta[i] / st.eta
+    for trial in range(1, st.bt_max_trials + 1):
+        cand = W_old - G / t
+        D = cand - W_old
+        upper = phi0 + float(np.sum(G * D)) + 0.5 * t * float(np.sum(D * D))
+        if phi(st, i, W=cand) <= upper:
+            st.theta[i] = t
+            st.W[i] = cand
+            st.w_trials[i] = trial
+            return
+        t *= st.eta
+    raise BacktrackingError(f"W-update of layer {i + 1}: no theta accepted")
+
+
+def update_b(st: State, i: int) -> None:
+    """b_l <- b_l - grad_b phi / (nu |V|): the exact minimiser over a broadcast bias."""
+    n_nodes = st.p[i].shape[0]
+    st.b[i] = st.b[i] - grad_b(st, i) / (st.nu * n_nodes)
+
+
+def z_subproblem_value(z, a, q, z_old):
+    """(z-a)^2 + (q - f(z))^2 + (z - z_old)^2: the z-subproblem for l < L without nu/2."""
+    return (z - a) ** 2 + (q - relu(z)) ** 2 + (z - z_old) ** 2
+
+
+def update_z_hidden(st: State, i: int) -> None:
+    """Closed-form ReLU z-update for l < L (Appendix A 'update z'): two candidates,
+    min((a+z_old)/2, 0) and max((a+q+z_old)/3, 0); keep the better one, ties to the first."""
+    a = st.p[i] @ st.W[i].T + st.b[i]
+    z_old, q = st.z[i], st.q[i]
+    z_neg = np.minimum((a + z_old) / 2.0, 0.0)
+    z_pos = np.maximum((a + q + z_old) / 3.0, 0.0)
+    h_neg = z_subproblem_value(z_neg, a, q, z_old)
+    h_pos = z_subproblem_value(z_pos, a, q, z_old)
+    st.z[i] = np.where(h_pos < h_neg, z_pos, z_neg)
+
+
+def log_softmax(z):
+    m = z.max(axis=1, keepdims=True)
+    e = z - m
+    return e - np.log(np.exp(e).sum(axis=1, keepdims=True))
+
+
+def risk(z_last, y, mask=None) -> float:
+    """R(z_L; y): cross-entropy summed over labelled nodes."""
+    ls = log_softmax(z_last)
+    per = -ls[np.arange(z_last.shape[0]), y]
+    if mask is not None:
+        per = per[mask]
+    return float(per.sum())
+
+
+def fista_z_last(z_start, a, y, nu, iters, mask=None):
+    """FISTA (Beck & Teboulle 2009) on R(z; y) + (nu/2)||z - a||^2, step 1/(nu + 1/2)."""
+    n, c = a.shape
+    onehot = np.zeros((n, c))
+    onehot[np.arange(n), y] = 1.0
+    lab = np.ones((n, 1)) if mask is None else mask.astype(F64)[:, None]
+    lip = nu + 0.5
+    x = z_start.copy()
+    w = z_start.copy()
+    t = 1.0
+    for _ in range(iters):
+        grad = lab * (np.exp(log_softmax(w)) - onehot) + nu * (w - a)
+        x_new = w - grad / lip
+        t_new = (1.0 + np.sqrt(1.0 + 4.0 * t * t)) / 2.0
+        w = x_new + ((t - 1.0) / t_new) * (x_new - x)
+        x, t = x_new, t_new
+    if mask is not None:
+        x = np.where(mask[:, None], x, a)       # exact minimiser where there is no risk term
+    return x
+
+
+def update_z_last(st: State) -> None:
+    i = st.L - 1
+    a = st.p[i] @ st.W[i].T + st.b[i]
+    st.z[i] = fista_z_last(st.z[i], a, st.y, st.nu, st.fista_iters, st.mask)
+
+
+def update_q(st: State, i: int) -> None:
+    """q_l <- (rho p_{l+1} + u_l + nu f(z_l)) / (rho + nu)."""
+    st.q[i] = (st.rho * st.p[i + 1] + st.u[i] + st.nu * relu(st.z[i])) / (st.rho + st.nu)
+
+
+def update_u(st: State, i: int) -> None:
+    """u_l <- u_l + rho (p_{l+1} - q_l)."""
+    st.u[i] = st.u[i] + st.rho * (st.p[i + 1] - st.q[i])
+
+
+def iterate(st: State, n_iters: int = 1) -> None:
+    """Algorithm 1: phases p, W, b, z, q, (residual), u; each phase over all layers."""
+    L = st.L
+    for _ in range(n_iters):
+        for i in range(1, L):
+            update_p(st, i)
+        for i in range(L):
+            update_W(st, i)
+        for i in range(L):
+            update_b(st, i)
+        for i in range(L - 1):
+            update_z_hidden(st, i)
+        update_z_last(st)
+        for i in range(L - 1):
+            update_q(st, i)
+        for i in range(L - 1):
+            update_u(st, i)
+
+
+# --------------------------------------------------------------------------------------
+# Objective and residual (Section 3.2, Algorithm 1)
+# --------------------------------------------------------------------------------------
+def objective(st: State) -> dict:
+    """Terms of L_rho: risk, (nu/2) sum ||z - W p - b||^2, (nu/2) sum ||q - f(z)||^2,
+    sum <u, p_{l+1} - q_l>, (rho/2) sum ||p_{l+1} - q_l||^2; F = first three; L_rho = all."""
+    L = st.L
+    lin = sum(float(np.sum((st.z[i] - st.p[i] @ st.W[i].T - st.b[i]) ** 2)) for i in range(L))
+    act = sum(float(np.sum((st.q[i] - relu(st.z[i])) ** 2)) for i in range(L - 1))
+    dl = sum(float(np.sum(st.u[i] * (st.p[i + 1] - st.q[i]))) for i in range(L - 1))
+    dq = sum(float(np.sum((st.p[i + 1] - st.q[i]) ** 2)) for i in range(L - 1))
+    out = dict(risk=risk(st.z[L - 1], st.y, st.mask), lin_pen=0.5 * st.nu * lin,
+               act_pen=0.5 * st.nu * act, dual_lin=dl, dual_quad=0.5 * st.rho * dq)
+    out["F"] = out["risk"] + out["lin_pen"] + out["act_pen"]
+    out["L_rho"] = out["F"] + out["dual_lin"] + out["dual_quad"]
+    return out
+
+
+def residual(st: State):
+    """sqrt(sum_l ||p_{l+1} - q_l||_F^2) and the per-layer norms."""
+    per = np.array([np.sqrt(float(np.sum((st.p[i + 1] - st.q[i]) ** 2))) for i in range(st.L - 1)])
+    return float(np.sqrt(np.sum(per ** 2))), per

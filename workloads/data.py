@@ -1,0 +1,80 @@
+"""Seeded features, labels, starting weights and perturbation noise.
+
+The perturbation turns a forward-consistent state (which is a fixed point of most of the
+ADMM updates) into a generic one: it only scales noise by the root-mean-square of an
+array and adds it. Nothing here evaluates the model or any ADMM update.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+from .configs import Workload
+
+# stream ids (added to the workload's seed base)
+S_GRAPH, S_FEAT, S_LABEL, S_WEIGHT, S_NOISE = 0, 1, 2, 3, 4
+
+
+def stream_rng(w: Workload, stream: int) -> np.random.Generator:
+    return np.random.Generator(np.random.PCG64(w.seed(stream)))
+
+
+def make_features(w: Workload) -> np.ndarray:
+    rng = stream_rng(w, S_FEAT)
+    if w.feat_kind == "bernoulli01":
+        return (rng.random((w.n_nodes, w.feat_dim)) < 0.01).astype(np.float32)
+    if w.feat_kind == "normal":
+        return rng.standard_normal((w.n_nodes, w.feat_dim), dtype=np.float32)
+    raise ValueError(w.feat_kind)
+
+
+def make_labels(w: Workload) -> np.ndarray:
+    return stream_rng(w, S_LABEL).integers(0, w.n_classes, size=w.n_nodes).astype(np.int32)
+
+
+def make_weights(w: Workload):
+    """W_l ~ N(0, 2 / n_{l-1}) as fp32 [n_l, n_{l-1}], b_l = 0; l = 1..L."""
+    rng = stream_rng(w, S_WEIGHT)
+    dims = w.dims
+    Ws, bs = [], []
+    for l in range(1, len(dims)):
+        std = np.float32(np.sqrt(2.0 / dims[l - 1]))
+        Ws.append(rng.standard_normal((dims[l], dims[l - 1]), dtype=np.float32) * std)
+        bs.append(np.zeros(dims[l], dtype=np.float32))
+    return Ws, bs
+
+
+def noise_like(rng: np.random.Generator, shape) -> np.ndarray:
+    return rng.standard_normal(shape, dtype=np.float32)
+
+
+def _rms(a: np.ndarray) -> np.float32:
+    return np.float32(np.sqrt(np.mean(np.square(a, dtype=np.float64))))
+
+
+def perturb_state(w: Workload, z, q, quantizer=None, scale: float = 0.1):
+    """Given forward-consistent z_1..z_L and q_1..q_{L-1} (node-major fp32 arrays), return
+    perturbed (z, q, p_2..p_L, u_1..u_{L-1}):
+        z_l += s*rms(z_l)*n1,  q_l += s*rms(q_l)*n2,  p_{l+1} = q_l + s*rms(q_l)*n3,
+        u_l = s*nu*rms(q_l)*n4,
+    with n* ~ N(0,1) from the workload's noise stream. `quantizer`, when given, is applied to
+    every p (it is the caller's projection onto the grid; this module does not define it)."""
+    rng = stream_rng(w, S_NOISE)
+    L = len(z)
+    s = np.float32(scale)
+    z_out, q_out, p_out, u_out = [], [], [], []
+    for l in range(L):
+        zl = z[l].astype(np.float32, copy=True)
+        zl += s * _rms(zl) * noise_like(rng, zl.shape)
+        z_out.append(zl)
+        if l < L - 1:
+            r = _rms(q[l])
+            ql = q[l].astype(np.float32, copy=True)
+            ql += s * r * noise_like(rng, ql.shape)
+            pl = ql + s * r * noise_like(rng, ql.shape)
+            if quantizer is not None:
+                pl = quantizer(pl)
+            ul = (s * np.float32(w.nu) * r) * noise_like(rng, ql.shape)
+            q_out.append(ql)
+            p_out.append(pl.astype(np.float32, copy=False))
+            u_out.append(ul.astype(np.float32, copy=False))
+    return z_out, q_out, p_out, u_out
