@@ -1,0 +1,190 @@
+/*
+ * pdadmm.h - C ABI of the MI355X (gfx950) implementation of one pdADMM-G / pdADMM-G-Q
+ * iteration over all layers of a graph-augmented MLP (arXiv 2105.09837).
+ *
+ * Conventions
+ *  - "DEVICE" pointers are HIP device memory owned by the caller; "HOST" pointers are
+ *    ordinary host memory. The library never allocates or frees device memory: all state
+ *    lives in the caller's workspace (pdadmm_workspace_bytes / pdadmm_init).
+ *  - The paper's n x |V| matrices are stored node-major, row-major [|V|, n] fp32 (the same
+ *    bytes as the paper's matrix in column-major). W_l is row-major [n_l, n_{l-1}].
+ *  - Layers are numbered 1..L as in the paper. p_1 = X (the augmented features) is fixed.
+ *  - Every call returns a pdadmm_status; pdadmm_last_error(ctx) gives a text for the last
+ *    failure on that context. Nothing throws or aborts across this boundary. A context is
+ *    not thread-safe. After PDADMM_EHIP the context must be destroyed.
+ *  - Kernels are enqueued on the stream given at init / in the call (a hipStream_t passed
+ *    as void*; NULL = the default stream). pdadmm_iterate is asynchronous for pdADMM-G;
+ *    for pdADMM-G-Q it waits for one 4-byte-per-layer flag copy per backtracking round.
+ */
+#ifndef PDADMM_H
+#define PDADMM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct pdadmm_ctx pdadmm_ctx;
+
+typedef enum {
+  PDADMM_OK = 0,
+  PDADMM_EINVAL = 1,      /* bad argument (NULL, size, range, alignment) */
+  PDADMM_ENOMEM = 2,      /* workspace smaller than pdadmm_workspace_bytes() */
+  PDADMM_EHIP = 3,        /* a HIP runtime call failed */
+  PDADMM_EBACKTRACK = 4,  /* bt_max_trials exceeded in a p- or W-update */
+  PDADMM_ENONFINITE = 5   /* a norm that drives a step size became NaN/Inf */
+} pdadmm_status;
+
+/* Problem 2 / Problem 3 of the paper plus the conventions the paper leaves open. */
+typedef struct {
+  int32_t n_nodes;         /* |V| */
+  int32_t n_layers;        /* L >= 1 */
+  const int32_t* dims;     /* HOST, dims[0..L] = n_0..n_L (read during the call only) */
+  float rho, nu;           /* penalties of L_rho (Section 3.2), both > 0 */
+  int32_t quantize;        /* 0: pdADMM-G; 1: pdADMM-G-Q, p_l (l >= 2) restricted to Delta */
+  float q_lo, q_hi;        /* Delta = { q_lo + i*(q_hi-q_lo)/(q_levels-1) }, i = 0..q_levels-1 */
+  int32_t q_levels;        /* 2..256 */
+  int32_t fista_iters;     /* fixed number of FISTA steps for z_L (Appendix A); e.g. 20 */
+  float bt_eta;            /* backtracking growth factor (> 1), e.g. 2 */
+  float tau0, theta0;      /* initial tau_l, theta_l, e.g. 1 */
+  int32_t bt_max_trials;   /* cap per update, e.g. 64 */
+  int32_t refresh_every;   /* recompute W_l p_l + b_l - z_l from scratch every k iterations; 0 = never */
+} pdadmm_config;
+
+/* Terms of the augmented Lagrangian L_rho (Section 3.2). */
+typedef struct {
+  double risk;       /* R(z_L; y): cross-entropy summed over labelled nodes */
+  double lin_pen;    /* (nu/2) sum_l ||z_l - W_l p_l - b_l||^2 */
+  double act_pen;    /* (nu/2) sum_{l<L} ||q_l - f(z_l)||^2 */
+  double dual_lin;   /* sum_{l<L} <u_l, p_{l+1} - q_l> */
+  double dual_quad;  /* (rho/2) sum_{l<L} ||p_{l+1} - q_l||^2 */
+  double F;          /* risk + lin_pen + act_pen (objective of Problem 2) */
+  double L_rho;      /* F + dual_lin + dual_quad */
+} pdadmm_objective_terms;
+
+/* Variables addressable by pdadmm_get_var / pdadmm_set_var. */
+enum {
+  PDADMM_VAR_P = 0,      /* p_l, l = 1..L (l = 1 is read-only), [N, n_{l-1}] */
+  PDADMM_VAR_W = 1,      /* W_l, [n_l, n_{l-1}] */
+  PDADMM_VAR_B = 2,      /* b_l, [n_l] */
+  PDADMM_VAR_Z = 3,      /* z_l, [N, n_l] */
+  PDADMM_VAR_Q = 4,      /* q_l, l = 1..L-1, [N, n_l] */
+  PDADMM_VAR_U = 5,      /* u_l, l = 1..L-1, [N, n_l] */
+  PDADMM_VAR_TAU = 6,    /* tau_l, l = 2..L: one HOST double */
+  PDADMM_VAR_THETA = 7,  /* theta_l, l = 1..L: one HOST double */
+  PDADMM_VAR_PIDX = 8,   /* get only, -Q: indices of p_l in Delta, uint8 [N, n_{l-1}], l = 2..L */
+  /* read-only internals, for diagnostics */
+  PDADMM_VAR_RESID = 9,  /* carried W_l p_l + b_l - z_l, [N, n_l] */
+  PDADMM_VAR_GRAD_P = 10,/* last gradient of phi in p_l, [N, n_{l-1}], l = 2..L */
+  PDADMM_VAR_GRAD_W = 11 /* last gradient of phi in W_l, [n_l, n_{l-1}] */
+};
+
+/* Phases of Algorithm 1 as this library groups them (pdadmm_step_phase). */
+enum { PDADMM_PHASE_P = 0, PDADMM_PHASE_W = 1, PDADMM_PHASE_BZQU = 2 };
+
+/*
+ * Renormalised adjacency (Section 5.1): A~ = (D+I)^(-1/2) (A+I) (D+I)^(-1/2), D_ii = sum_j A_ij.
+ * In : HOST CSR pattern of the symmetric binary A without self-loops (rowptr[n+1], colidx[nnz],
+ *      columns ascending within a row).
+ * Out: HOST CSR of A~ with the diagonal inserted: out_rowptr[n+1], out_colidx[nnz+n] ascending,
+ *      out_vals[nnz+n] = fp32(1/sqrt((d_i+1)(d_j+1))) computed in fp64. Caller owns all arrays.
+ * Errors: EINVAL on NULL, negative n, non-monotone rowptr, column out of range or a self-loop.
+ */
+pdadmm_status pdadmm_normalize_adj(int32_t n, const int32_t* rowptr, const int32_t* colidx,
+                                   int32_t* out_rowptr, int32_t* out_colidx, float* out_vals);
+
+/*
+ * Multi-hop augmentation (Sections 3.1, 5.1): X_aug = [X | A~X | ... | A~^hops X] along features.
+ * All pointers DEVICE. rowptr[n+1], colidx[nnz], vals[nnz] = CSR of A~; X is [n, d] row-major;
+ * X_aug is [n, (hops+1)*d] row-major, written entirely. Rounding is fixed: each product is rounded
+ * to fp32 and added to an fp32 accumulator starting at +0 in CSR order (no fused multiply-add), so
+ * the result is reproducible bit for bit. Asynchronous on `stream`. hops >= 0, d >= 1.
+ * nnz = number of stored entries (needed to validate nothing on the device; pass rowptr[n]).
+ */
+pdadmm_status pdadmm_augment(int32_t n, int64_t nnz, const int32_t* rowptr, const int32_t* colidx,
+                             const float* vals, const float* X, int32_t d, int32_t hops,
+                             float* X_aug, void* stream);
+
+/*
+ * Projection onto the uniform set Delta (Section 3.3, Appendix B): elementwise
+ * argmin_{delta in Delta} |delta - v|. DEVICE in v[count]; DEVICE out idx[count] (uint8) and/or
+ * val[count] (either may be NULL). step = (hi-lo)/(levels-1) in fp32; t = (v-lo)/step;
+ * idx = clamp(round-half-even(t), 0, levels-1); delta = lo + idx*step (product, then sum, each
+ * rounded to fp32). NaN maps to index 0. levels in 2..256. Asynchronous on `stream`.
+ */
+pdadmm_status pdadmm_quantize(const float* v, int64_t count, float lo, float hi, int32_t levels,
+                              uint8_t* idx, float* val, void* stream);
+
+/*
+ * Dense fp32 products on the matrix cores, exposed for tests and micro-benchmarks of the kernels
+ * that carry the layer updates (the n_l x n_{l-1} x |V| products named in Section 3.2).
+ *   pdadmm_gemm_nt: C[M,N] = A[M,K] * B[N,K]^T         (row-major, leading dimensions in floats)
+ *   pdadmm_gemm_tn: C[M,N] = alpha * A[K,M]^T * B[K,N]  with the K range split in `splitk` parts
+ *                   that are summed in a fixed order; `part` is DEVICE scratch of at least
+ *                   splitk*M*ldc floats.
+ * All pointers DEVICE. Asynchronous on `stream`. EINVAL on non-positive sizes or ld < width.
+ */
+pdadmm_status pdadmm_gemm_nt(int32_t M, int32_t N, int32_t K, const float* A, int32_t lda,
+                             const float* B, int32_t ldb, float* C, int32_t ldc, void* stream);
+pdadmm_status pdadmm_gemm_tn(int32_t M, int32_t N, int32_t K, float alpha, const float* A, int32_t lda,
+                             const float* B, int32_t ldb, float* C, int32_t ldc, int32_t splitk,
+                             float* part, void* stream);
+
+/* Bytes of DEVICE workspace pdadmm_init needs for this configuration (0 if it is invalid). */
+size_t pdadmm_workspace_bytes(const pdadmm_config* cfg);
+
+/*
+ * Create a context and the forward-consistent starting point of Algorithm 1:
+ * p_1 = X_aug; z_l = W_l p_l + b_l; q_l = f(z_l); p_{l+1} = q_l (projected onto Delta for -Q);
+ * u_l = 0; tau_l = tau0, theta_l = theta0.
+ *  workspace: DEVICE, >= pdadmm_workspace_bytes(cfg), 256-byte aligned, owned by the caller and kept
+ *             alive until pdadmm_destroy. X_aug [N, n_0], labels [N] int32 in [0, n_L),
+ *             train_mask [N] uint8 or NULL (= every node labelled), W0[l-1] [n_l, n_{l-1}],
+ *             b0[l-1] [n_l]: all DEVICE, copied during the call (the caller may free them afterwards).
+ *  W0, b0: HOST arrays of L DEVICE pointers. stream: hipStream_t or NULL.
+ * The call synchronises the stream before returning.
+ */
+pdadmm_status pdadmm_init(pdadmm_ctx** out, const pdadmm_config* cfg, void* workspace, size_t workspace_bytes,
+                          const float* X_aug, const int32_t* labels, const uint8_t* train_mask,
+                          const float* const* W0, const float* const* b0, void* stream);
+
+/*
+ * Copy a variable in or out. `layer` is the paper's l. The buffer is dense (leading dimension =
+ * width) and may be HOST or DEVICE memory, except TAU/THETA (HOST double). Both calls synchronise.
+ * set_var of P in -Q mode projects the values onto Delta. After any set_var the carried residual
+ * W_l p_l + b_l - z_l is recomputed from scratch at the next iteration.
+ */
+pdadmm_status pdadmm_set_var(pdadmm_ctx* ctx, int32_t kind, int32_t layer, const void* src);
+pdadmm_status pdadmm_get_var(pdadmm_ctx* ctx, int32_t kind, int32_t layer, void* dst);
+
+/* Run n_iters iterations of Algorithm 1 (phases p, W, b, z, q, u; every phase over all layers). */
+pdadmm_status pdadmm_iterate(pdadmm_ctx* ctx, int32_t n_iters);
+
+/* Run one phase group of the current iteration (diagnostics; iterate = P, W, BZQU in this order). */
+pdadmm_status pdadmm_step_phase(pdadmm_ctx* ctx, int32_t phase);
+
+/* Wait for all enqueued work; report sticky device-side errors (EBACKTRACK, ENONFINITE). */
+pdadmm_status pdadmm_sync(pdadmm_ctx* ctx);
+
+/* L_rho and its terms, evaluated from the variables (W_l p_l + b_l is recomputed). Synchronises. */
+pdadmm_status pdadmm_objective(pdadmm_ctx* ctx, pdadmm_objective_terms* out);
+
+/* sqrt(sum_l ||p_{l+1} - q_l||_F^2) (Algorithm 1, residual line) and, if per_layer != NULL, the L-1
+ * per-layer norms (HOST). Synchronises. */
+pdadmm_status pdadmm_residual(pdadmm_ctx* ctx, double* total, double* per_layer);
+
+/* HOST outputs, each L entries or NULL: tau_l (entry 0 unused), theta_l, trials used by the last
+ * p- and W-update. r_drift (or NULL): relative L2 distance between the carried and a freshly
+ * computed W_l p_l + b_l - z_l over all layers. Synchronises. */
+pdadmm_status pdadmm_stats(pdadmm_ctx* ctx, double* tau, double* theta, int32_t* p_trials,
+                           int32_t* w_trials, double* r_drift);
+
+const char* pdadmm_last_error(const pdadmm_ctx* ctx);
+void pdadmm_destroy(pdadmm_ctx* ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PDADMM_H */

@@ -1,0 +1,66 @@
+// Shared device/host definitions for the pdADMM kernels (gfx950, wave64).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace pdadmm {
+
+constexpr int kWave = 64;
+constexpr int kXcd = 8;   // MI355X: 8 accelerator dies, workgroups are dealt to them round-robin
+
+// Map the hardware block id to a logical block id so that logically consecutive blocks run on
+// the same die (and share its L2): die x gets the contiguous logical range [start_x, start_x+cnt_x).
+__device__ __forceinline__ int xcd_remap(int bid, int total) {
+  const int q = total / kXcd, r = total % kXcd;
+  const int x = bid % kXcd, slot = bid / kXcd;
+  return x * q + (x < r ? x : r) + slot;
+}
+
+__device__ __forceinline__ double wave_sum(double v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, kWave);
+  return v;
+}
+
+// Sum of one double per thread over a 256-thread block in a fixed order; result valid in thread 0.
+__device__ __forceinline__ double block_sum_256(double v, double* smem /* >= 4 doubles */) {
+  v = wave_sum(v);
+  const int w = threadIdx.x >> 6;
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) smem[w] = v;
+  __syncthreads();
+  return smem[0] + smem[1] + smem[2] + smem[3];
+}
+
+// Device-side sticky error bits.
+enum : int { kErrBacktrack = 1, kErrNonFinite = 2 };
+
+// Per-layer scalars that live in device memory and are produced/consumed by kernels only.
+struct LayerScal {
+  double tau, theta;       // current backtracking parameters
+  double norm_g, norm_t;   // last reduced squared norms (diagnostics)
+  float inv_tau, inv_theta;  // 1/tau, 1/theta as applied by the step kernels (0 = skip the step)
+  float trial_t;           // -Q: tau of the trial in flight
+  int p_trials, w_trials;
+  int active;              // -Q: 1 while the p-update of this layer is still searching
+  int pad;
+};
+
+struct QuantGrid {
+  float lo, step;
+  int levels;
+};
+
+// Projection onto the uniform grid, every operation rounded to fp32 separately.
+__device__ __forceinline__ int quant_index(float v, const QuantGrid g) {
+  const float t = __fdiv_rn(__fsub_rn(v, g.lo), g.step);
+  float r = rintf(t);
+  if (!(r == r)) r = 0.0f;                      // NaN -> 0
+  r = fminf(fmaxf(r, 0.0f), (float)(g.levels - 1));
+  return (int)r;
+}
+__device__ __forceinline__ float quant_value(int idx, const QuantGrid g) {
+  return __fadd_rn(g.lo, __fmul_rn((float)idx, g.step));
+}
+
+}  // namespace pdadmm

@@ -1,0 +1,599 @@
+// Memory-bound kernels of one pdADMM iteration: step-size selection, the p/W/b steps, the
+// closed-form z, q and u updates, projection onto Delta, FISTA for z_L and the reductions behind
+// the objective. All are grouped over layers through small descriptor tables in device memory;
+// every reduction is two-stage with a fixed summation order (bit-reproducible, no atomics).
+#pragma once
+#include "common.h"
+
+namespace pdadmm {
+
+// ------------------------------------------------------------------------------------------
+// Flat y -= s * x over float4 groups; s comes from the layer's scalars.
+// ------------------------------------------------------------------------------------------
+enum : int { kScaleInvTau = 0, kScaleInvTheta = 1, kScaleMinusOneIfStep = 2 };
+
+struct AxpySeg {
+  float* y;
+  const float* x;
+  size_t n4;        // number of float4 groups
+  int blk0, nblk;
+  int layer, which;
+};
+
+__global__ __launch_bounds__(256) void axpy_kernel(const AxpySeg* __restrict__ segs, int nseg,
+                                                   const LayerScal* __restrict__ scal) {
+  const int lb = blockIdx.x;
+  int si = 0;
+  while (si + 1 < nseg && lb >= segs[si + 1].blk0) ++si;
+  const AxpySeg S = segs[si];
+  const LayerScal& sc = scal[S.layer];
+  float s;
+  if (S.which == kScaleInvTau) s = sc.inv_tau;
+  else if (S.which == kScaleInvTheta) s = sc.inv_theta;
+  else s = sc.inv_tau != 0.0f ? -1.0f : 0.0f;
+  if (s == 0.0f) return;
+  float4* y = reinterpret_cast<float4*>(S.y);
+  const float4* x = reinterpret_cast<const float4*>(S.x);
+  const size_t stride = (size_t)S.nblk * 256;
+  for (size_t i = (size_t)(lb - S.blk0) * 256 + threadIdx.x; i < S.n4; i += stride) {
+    float4 a = y[i];
+    const float4 b = x[i];
+    a.x -= s * b.x;
+    a.y -= s * b.y;
+    a.z -= s * b.z;
+    a.w -= s * b.w;
+    y[i] = a;
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// Step-size selection (Appendix A: tau must satisfy phi(p_new) <= U_l(p_new; tau), theta the
+// analogous condition with V_l). phi is exactly quadratic in p_l and in W_l, so for the
+// unprojected step the condition reads  t >= lambda  with
+//   lambda_p = rho + nu ||W g||^2 / ||g||^2,   lambda_W = nu ||G p||^2 / ||G||^2.
+// Schedule: start at previous/eta, multiply by eta until t >= lambda.
+// One block per layer; partial sums are added in a fixed order.
+// ------------------------------------------------------------------------------------------
+struct SelectDesc {
+  const double* part_g;   // partials of ||g||^2 (or ||G||^2, or ||d||^2)
+  const double* part_t;   // partials of ||W g||^2 (or ||G p||^2, or ||W d||^2)
+  int ng, nt;
+  int stride_t;           // doubles per block in part_t (1 or 2)
+  int layer;
+};
+
+__device__ __forceinline__ double fixed_order_sum(const double* p, int n, int stride, double* red) {
+  double s = 0.0;
+  for (int i = threadIdx.x; i < n; i += 256) s += p[(size_t)i * stride];
+  return block_sum_256(s, red);
+}
+
+// mode 0: tau (p-update, unprojected); mode 1: theta (W-update)
+__global__ __launch_bounds__(256) void select_step_kernel(const SelectDesc* __restrict__ descs, LayerScal* scal,
+                                                          int mode, float rho, float nu, float eta, int max_trials,
+                                                          int* err) {
+  __shared__ double red[4];
+  const SelectDesc D = descs[blockIdx.x];
+  const double sg = fixed_order_sum(D.part_g, D.ng, 1, red);
+  const double st = fixed_order_sum(D.part_t, D.nt, D.stride_t, red);
+  if (threadIdx.x != 0) return;
+  LayerScal& sc = scal[D.layer];
+  sc.norm_g = sg;
+  sc.norm_t = st;
+  float inv = 0.0f;
+  int trials = 0;
+  if (!(sg == sg) || !(st == st) || sg > 1.7e308 || st > 1.7e308) {
+    atomicOr(err, kErrNonFinite);
+  } else if (sg > 0.0) {
+    const double lambda = (mode == 0 ? (double)rho : 0.0) + (double)nu * st / sg;
+    double t = (mode == 0 ? sc.tau : sc.theta) / (double)eta;
+    trials = 1;
+    while (t < lambda && trials < max_trials) {
+      t *= (double)eta;
+      ++trials;
+    }
+    if (t < lambda) atomicOr(err, kErrBacktrack);
+    else {
+      if (mode == 0) sc.tau = t; else sc.theta = t;
+      inv = (float)(1.0 / t);
+    }
+  }
+  if (mode == 0) { sc.inv_tau = inv; sc.p_trials = trials; }
+  else { sc.inv_theta = inv; sc.w_trials = trials; }
+}
+
+// ------------------------------------------------------------------------------------------
+// W-step: W <- W - G/theta, plus the transposed copy Wt[n_in][ld_out] kept for the W^T r product.
+// 32x32 tiles through LDS so that both the read of W and the write of Wt are coalesced.
+// ------------------------------------------------------------------------------------------
+struct WStepSeg {
+  float* W;         // [n_out][ld_in]
+  float* Wt;        // [n_in][ld_out]
+  const float* G;   // [n_out][ld_in]
+  int n_out, n_in, ld_in, ld_out;
+  int tiles_c;      // tiles along n_in
+  int blk0, nblk;
+  int layer;
+};
+
+__global__ __launch_bounds__(256) void w_step_kernel(const WStepSeg* __restrict__ segs, int nseg,
+                                                     const LayerScal* __restrict__ scal, int copy_only) {
+  __shared__ float tile[32][33];
+  const int lb = blockIdx.x;
+  int si = 0;
+  while (si + 1 < nseg && lb >= segs[si + 1].blk0) ++si;
+  const WStepSeg S = segs[si];
+  const float inv = copy_only ? 0.0f : scal[S.layer].inv_theta;
+  const int local = lb - S.blk0;
+  const int tr = local / S.tiles_c, tc = local % S.tiles_c;
+  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    const int r = tr * 32 + ty + 8 * k, c = tc * 32 + tx;
+    float w = 0.0f;
+    if (r < S.n_out && c < S.n_in) {
+      const size_t i = (size_t)r * S.ld_in + c;
+      w = S.W[i];
+      if (inv != 0.0f) {
+        w -= inv * S.G[i];
+        S.W[i] = w;
+      }
+    }
+    tile[ty + 8 * k][tx] = w;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    const int c = tc * 32 + ty + 8 * k, r = tr * 32 + tx;   // Wt row = c (n_in), Wt col = r (n_out)
+    if (c < S.n_in && r < S.n_out) S.Wt[(size_t)c * S.ld_out + r] = tile[tx][ty + 8 * k];
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// Row-structured passes over [rows, ld] arrays. A block covers 128 rows x 256 columns:
+// thread (ty = wave, cq = lane) owns one float4 column group and walks rows ty, ty+4, ...
+// ------------------------------------------------------------------------------------------
+constexpr int kRowsPerBlock = 128;
+
+struct RowSeg {
+  float* R;             // carried residual W p + b - z
+  const float* T;       // G p (W-step direction image)
+  float* z;
+  float* q;
+  float* u;
+  const float* pnext;   // p_{l+1}
+  const float* m;       // column means (b-step), [ld]
+  double* colpart;      // [row_blocks][ld]
+  double* rpart;        // per block: ||p_{l+1} - q_l||^2
+  int rows, ncols, ld;
+  int col_blocks, row_blocks;
+  int blk0, nblk;
+  int layer;
+};
+
+// R <- R - T/theta and per-block column sums of the new R (b-update, Appendix A 'update b':
+// the minimiser over the broadcast bias subtracts the node-mean of W p + b - z).
+__global__ __launch_bounds__(256) void resid_colsum_kernel(const RowSeg* __restrict__ segs, int nseg,
+                                                           const LayerScal* __restrict__ scal) {
+  __shared__ double sm[4][64][4];
+  const int lb = blockIdx.x;
+  int si = 0;
+  while (si + 1 < nseg && lb >= segs[si + 1].blk0) ++si;
+  const RowSeg S = segs[si];
+  const float inv = scal[S.layer].inv_theta;
+  const int local = lb - S.blk0;
+  const int cb = local % S.col_blocks, rb = local / S.col_blocks;
+  const int cq = threadIdx.x & 63, ty = threadIdx.x >> 6;
+  const int col = (cb * 64 + cq) * 4;
+  double a0 = 0, a1 = 0, a2 = 0, a3 = 0;
+  if (col < S.ld) {
+    const int rend = min(S.rows, (rb + 1) * kRowsPerBlock);
+    for (int r = rb * kRowsPerBlock + ty; r < rend; r += 4) {
+      const size_t i = (size_t)r * S.ld + col;
+      float4 v = *reinterpret_cast<const float4*>(S.R + i);
+      if (inv != 0.0f) {
+        const float4 t = *reinterpret_cast<const float4*>(S.T + i);
+        v.x -= inv * t.x;
+        v.y -= inv * t.y;
+        v.z -= inv * t.z;
+        v.w -= inv * t.w;
+        *reinterpret_cast<float4*>(S.R + i) = v;
+      }
+      a0 += v.x; a1 += v.y; a2 += v.z; a3 += v.w;
+    }
+  }
+  sm[ty][cq][0] = a0; sm[ty][cq][1] = a1; sm[ty][cq][2] = a2; sm[ty][cq][3] = a3;
+  __syncthreads();
+  if (ty == 0 && col < S.ld) {
+    double* out = S.colpart + (size_t)rb * S.ld + col;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) out[k] = sm[0][cq][k] + sm[1][cq][k] + sm[2][cq][k] + sm[3][cq][k];
+  }
+}
+
+// b <- b - mean; m <- mean. One thread per column.
+struct BiasSeg {
+  float* b;
+  float* m;
+  const double* colpart;
+  int ncols, ld, row_blocks, rows;
+  int blk0, nblk;
+};
+
+__global__ __launch_bounds__(256) void bias_step_kernel(const BiasSeg* __restrict__ segs, int nseg) {
+  const int lb = blockIdx.x;
+  int si = 0;
+  while (si + 1 < nseg && lb >= segs[si + 1].blk0) ++si;
+  const BiasSeg S = segs[si];
+  const int c = (lb - S.blk0) * 256 + threadIdx.x;
+  if (c >= S.ld) return;
+  double s = 0.0;
+  for (int rb = 0; rb < S.row_blocks; ++rb) s += S.colpart[(size_t)rb * S.ld + c];
+  const float mean = c < S.ncols ? (float)(s / (double)S.rows) : 0.0f;
+  S.m[c] = mean;
+  if (c < S.ncols) S.b[c] -= mean;
+}
+
+// Closed-form ReLU z-update (Appendix A 'update z', l < L) on one element.
+// a = W p + b (new), s = a + z_old. Candidates min(s/2, 0) and max((s+q)/3, 0); the better one
+// in the subproblem objective (z-a)^2 + (q-relu(z))^2 + (z-z_old)^2 is: the positive candidate if
+// s >= 0; the non-positive one if s + q <= 0; otherwise the positive one iff (s+q)^2/3 > s^2/2.
+__device__ __forceinline__ float z_closed_form(float s, float q) {
+  const float sq = s + q;
+  const float zneg = fminf(0.5f * s, 0.0f);
+  const float zpos = fmaxf(sq / 3.0f, 0.0f);
+  if (s >= 0.0f) return zpos;
+  if (sq <= 0.0f) return zneg;
+  return (sq * sq) / 3.0f > (s * s) * 0.5f ? zpos : zneg;
+}
+
+// Fused b-shift, z-update, q-update, residual and dual update for layers l < L
+// (Appendix A 'update z', 'update q', 'update u'):
+//   a = R - m + z_old; z = closed form; R <- a - z;
+//   q = (rho p_{l+1} + u + nu relu(z)) / (rho + nu); r = p_{l+1} - q; u <- u + rho r.
+__global__ __launch_bounds__(256) void zqu_kernel(const RowSeg* __restrict__ segs, int nseg, float rho, float nu) {
+  __shared__ double red[4];
+  const int lb = blockIdx.x;
+  int si = 0;
+  while (si + 1 < nseg && lb >= segs[si + 1].blk0) ++si;
+  const RowSeg S = segs[si];
+  const int local = lb - S.blk0;
+  const int cb = local % S.col_blocks, rb = local / S.col_blocks;
+  const int cq = threadIdx.x & 63, ty = threadIdx.x >> 6;
+  const int col = (cb * 64 + cq) * 4;
+  const float inv_rn = 1.0f / (rho + nu);
+  double rs = 0.0;
+  if (col < S.ld) {
+    const float4 mm = *reinterpret_cast<const float4*>(S.m + col);
+    const int rend = min(S.rows, (rb + 1) * kRowsPerBlock);
+    for (int r = rb * kRowsPerBlock + ty; r < rend; r += 4) {
+      const size_t i = (size_t)r * S.ld + col;
+      const float4 Rv = *reinterpret_cast<const float4*>(S.R + i);
+      const float4 zo = *reinterpret_cast<const float4*>(S.z + i);
+      const float4 qo = *reinterpret_cast<const float4*>(S.q + i);
+      const float4 pn = *reinterpret_cast<const float4*>(S.pnext + i);
+      const float4 uo = *reinterpret_cast<const float4*>(S.u + i);
+      float4 zn, Rn, qn, un;
+#define PDADMM_ZQU(c)                                                     \
+  {                                                                       \
+    const float a = Rv.c - mm.c + zo.c;                                   \
+    const float z = z_closed_form(a + zo.c, qo.c);                        \
+    zn.c = z;                                                             \
+    Rn.c = a - z;                                                         \
+    const float qq = (rho * pn.c + uo.c + nu * fmaxf(z, 0.0f)) * inv_rn;  \
+    const float rr = pn.c - qq;                                           \
+    qn.c = qq;                                                            \
+    un.c = uo.c + rho * rr;                                               \
+    rs += (double)rr * (double)rr;                                        \
+  }
+      PDADMM_ZQU(x) PDADMM_ZQU(y) PDADMM_ZQU(z) PDADMM_ZQU(w)
+#undef PDADMM_ZQU
+      *reinterpret_cast<float4*>(S.z + i) = zn;
+      *reinterpret_cast<float4*>(S.R + i) = Rn;
+      *reinterpret_cast<float4*>(S.q + i) = qn;
+      *reinterpret_cast<float4*>(S.u + i) = un;
+    }
+  }
+  const double t = block_sum_256(rs, red);
+  if (threadIdx.x == 0) S.rpart[local] = t;
+}
+
+// ------------------------------------------------------------------------------------------
+// z_L-update: FISTA with a fixed number of steps on CE(z; y) + (nu/2)||z - a||^2, per node.
+// A group of G = 2^k lanes (G >= C, G <= 64) owns one node; for C > 64 each lane holds E classes.
+// Step 1/(nu + 1/2) (the cross-entropy Hessian is bounded by 1/2). Unlabelled nodes take z = a.
+// ------------------------------------------------------------------------------------------
+template <int E>
+__global__ __launch_bounds__(256) void fista_kernel(float* __restrict__ R, float* __restrict__ z,
+                                                    const float* __restrict__ m, const int* __restrict__ y,
+                                                    const uint8_t* __restrict__ mask, int rows, int C, int ld,
+                                                    int G, float nu, int iters) {
+  const int gid = (blockIdx.x * 256 + threadIdx.x) / G;
+  const int gl = threadIdx.x % G;
+  const bool live = gid < rows;
+  const int node = live ? gid : rows - 1;
+  const int label = y[node];
+  const bool lab = mask ? mask[node] != 0 : true;
+  float a[E], x[E], w[E];
+  bool valid[E];
+#pragma unroll
+  for (int e = 0; e < E; ++e) {
+    const int c = gl + e * G;
+    valid[e] = c < C;
+    const size_t i = (size_t)node * ld + (valid[e] ? c : 0);
+    const float zo = z[i];
+    a[e] = R[i] - m[valid[e] ? c : 0] + zo;
+    x[e] = zo;
+    w[e] = zo;
+  }
+  const float inv_lip = 1.0f / (nu + 0.5f);
+  double t = 1.0;
+  if (lab) {
+    for (int it = 0; it < iters; ++it) {
+      float mx = -INFINITY;
+#pragma unroll
+      for (int e = 0; e < E; ++e) if (valid[e]) mx = fmaxf(mx, w[e]);
+      for (int off = G >> 1; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, G));
+      float ex[E], sum = 0.0f;
+#pragma unroll
+      for (int e = 0; e < E; ++e) {
+        ex[e] = valid[e] ? expf(w[e] - mx) : 0.0f;
+        sum += ex[e];
+      }
+      for (int off = G >> 1; off > 0; off >>= 1) sum += __shfl_xor(sum, off, G);
+      const double tn = 0.5 * (1.0 + sqrt(1.0 + 4.0 * t * t));
+      const float mom = (float)((t - 1.0) / tn);
+#pragma unroll
+      for (int e = 0; e < E; ++e) {
+        const int c = gl + e * G;
+        const float grad = ex[e] / sum - (c == label ? 1.0f : 0.0f) + nu * (w[e] - a[e]);
+        const float xn = w[e] - grad * inv_lip;
+        w[e] = xn + mom * (xn - x[e]);
+        x[e] = xn;
+      }
+      t = tn;
+    }
+  } else {
+#pragma unroll
+    for (int e = 0; e < E; ++e) x[e] = a[e];
+  }
+  if (live) {
+#pragma unroll
+    for (int e = 0; e < E; ++e) {
+      if (valid[e]) {
+        const size_t i = (size_t)node * ld + gl + e * G;
+        z[i] = x[e];
+        R[i] = a[e] - x[e];
+      }
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// pdADMM-G-Q p-update (Appendix B): p <- argmin_{delta in Delta} |delta - (p - g/tau)|.
+// One backtracking trial: candidate indices, d = candidate - p, per-block ||d||^2.
+// ------------------------------------------------------------------------------------------
+struct QuantSeg {
+  float* p;
+  const float* g;
+  float* d;
+  uint8_t* idx;       // [rows][ld]
+  double* dpart;      // per block
+  size_t n4;          // rows*ld/4
+  int ncols, ld;
+  int blk0, nblk;
+  int layer;
+};
+
+__global__ __launch_bounds__(256) void quant_trial_kernel(const QuantSeg* __restrict__ segs, int nseg,
+                                                          const LayerScal* __restrict__ scal, QuantGrid grid) {
+  __shared__ double red[4];
+  const int lb = blockIdx.x;
+  int si = 0;
+  while (si + 1 < nseg && lb >= segs[si + 1].blk0) ++si;
+  const QuantSeg S = segs[si];
+  if (!scal[S.layer].active) return;
+  const float t = scal[S.layer].trial_t;
+  const size_t stride = (size_t)S.nblk * 256;
+  double ds = 0.0;
+  for (size_t i = (size_t)(lb - S.blk0) * 256 + threadIdx.x; i < S.n4; i += stride) {
+    const float4 pv = reinterpret_cast<const float4*>(S.p)[i];
+    const float4 gv = reinterpret_cast<const float4*>(S.g)[i];
+    const int col0 = (int)((i * 4) % (size_t)S.ld);
+    float4 dv;
+    uchar4 iv;
+#define PDADMM_QT(c, k)                                                       \
+  {                                                                           \
+    if (col0 + k < S.ncols) {                                                 \
+      const float v = __fsub_rn(pv.c, __fdiv_rn(gv.c, t));                    \
+      const int id = quant_index(v, grid);                                    \
+      iv.c = (unsigned char)id;                                               \
+      dv.c = __fsub_rn(quant_value(id, grid), pv.c);                          \
+      ds += (double)dv.c * (double)dv.c;                                      \
+    } else {                                                                  \
+      iv.c = 0;                                                               \
+      dv.c = 0.0f;                                                            \
+    }                                                                         \
+  }
+    PDADMM_QT(x, 0) PDADMM_QT(y, 1) PDADMM_QT(z, 2) PDADMM_QT(w, 3)
+#undef PDADMM_QT
+    reinterpret_cast<float4*>(S.d)[i] = dv;
+    reinterpret_cast<uchar4*>(S.idx)[i] = iv;
+  }
+  const double tot = block_sum_256(ds, red);
+  if (threadIdx.x == 0) S.dpart[lb - S.blk0] = tot;
+}
+
+// Accept/reject one -Q trial: phi(p+d) - phi(p) - <g,d> = (nu/2)||W d||^2 + (rho/2)||d||^2 exactly,
+// so the condition phi(p_new) <= U_l(p_new; t) is  nu||W d||^2 + rho||d||^2 <= t ||d||^2.
+// phase 0: arm the search (active = 1, trial_t = tau/eta) for layers with g != 0.
+// phase 1: judge the trial in flight.
+__global__ __launch_bounds__(256) void select_quant_kernel(const SelectDesc* __restrict__ descs, LayerScal* scal,
+                                                           int phase, float rho, float nu, float eta,
+                                                           int max_trials, int* err, int* flags) {
+  __shared__ double red[4];
+  const SelectDesc D = descs[blockIdx.x];
+  LayerScal& sc = scal[D.layer];
+  if (phase == 0) {
+    const double sg = fixed_order_sum(D.part_g, D.ng, 1, red);
+    if (threadIdx.x != 0) return;
+    sc.norm_g = sg;
+    sc.inv_tau = 0.0f;
+    sc.p_trials = 0;
+    sc.active = 0;
+    if (!(sg == sg) || sg > 1.7e308) atomicOr(err, kErrNonFinite);
+    else if (sg > 0.0) {
+      sc.active = 1;
+      sc.trial_t = (float)(sc.tau / (double)eta);
+      sc.p_trials = 1;
+    }
+    flags[D.layer] = sc.active;
+    return;
+  }
+  if (!sc.active) return;      // uniform per block
+  const double sd = fixed_order_sum(D.part_g, D.ng, 1, red);
+  const double st = fixed_order_sum(D.part_t, D.nt, D.stride_t, red);
+  if (threadIdx.x != 0) return;
+  sc.norm_t = st;
+  const double t = (double)sc.trial_t;
+  if (!(sd == sd) || !(st == st) || sd > 1.7e308 || st > 1.7e308) {
+    atomicOr(err, kErrNonFinite);
+    sc.active = 0;
+    sc.p_trials = 0;
+  } else if ((double)nu * st + (double)rho * sd <= t * sd) {
+    sc.tau = t;
+    sc.inv_tau = 1.0f;     // marks "a step was accepted"
+    sc.active = 0;
+  } else if (sc.p_trials >= max_trials) {
+    atomicOr(err, kErrBacktrack);
+    sc.active = 0;
+    sc.p_trials = 0;
+  } else {
+    sc.trial_t = (float)(t * (double)eta);
+    sc.p_trials += 1;
+  }
+  flags[D.layer] = sc.active;
+}
+
+// p <- Delta[idx] for layers whose trial was accepted.
+__global__ __launch_bounds__(256) void quant_apply_kernel(const QuantSeg* __restrict__ segs, int nseg,
+                                                          const LayerScal* __restrict__ scal, QuantGrid grid) {
+  const int lb = blockIdx.x;
+  int si = 0;
+  while (si + 1 < nseg && lb >= segs[si + 1].blk0) ++si;
+  const QuantSeg S = segs[si];
+  if (scal[S.layer].inv_tau == 0.0f) return;
+  const size_t stride = (size_t)S.nblk * 256;
+  for (size_t i = (size_t)(lb - S.blk0) * 256 + threadIdx.x; i < S.n4; i += stride) {
+    const uchar4 iv = reinterpret_cast<const uchar4*>(S.idx)[i];
+    const int col0 = (int)((i * 4) % (size_t)S.ld);
+    float4 pv;
+    pv.x = col0 + 0 < S.ncols ? quant_value(iv.x, grid) : 0.0f;
+    pv.y = col0 + 1 < S.ncols ? quant_value(iv.y, grid) : 0.0f;
+    pv.z = col0 + 2 < S.ncols ? quant_value(iv.z, grid) : 0.0f;
+    pv.w = col0 + 3 < S.ncols ? quant_value(iv.w, grid) : 0.0f;
+    reinterpret_cast<float4*>(S.p)[i] = pv;
+  }
+}
+
+// Standalone projection of a [rows, ld] array (ncols valid columns): writes indices and/or values.
+__global__ __launch_bounds__(256) void quantize_kernel(const float* __restrict__ v, size_t n4, int ncols, int ld,
+                                                       QuantGrid grid, uint8_t* __restrict__ idx,
+                                                       float* __restrict__ val) {
+  const size_t stride = (size_t)gridDim.x * 256;
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n4; i += stride) {
+    const float4 x = reinterpret_cast<const float4*>(v)[i];
+    const int col0 = (int)((i * 4) % (size_t)ld);
+    const int i0 = col0 + 0 < ncols ? quant_index(x.x, grid) : 0;
+    const int i1 = col0 + 1 < ncols ? quant_index(x.y, grid) : 0;
+    const int i2 = col0 + 2 < ncols ? quant_index(x.z, grid) : 0;
+    const int i3 = col0 + 3 < ncols ? quant_index(x.w, grid) : 0;
+    if (idx) reinterpret_cast<uchar4*>(idx)[i] = make_uchar4(i0, i1, i2, i3);
+    if (val) {
+      float4 o;
+      o.x = col0 + 0 < ncols ? quant_value(i0, grid) : 0.0f;
+      o.y = col0 + 1 < ncols ? quant_value(i1, grid) : 0.0f;
+      o.z = col0 + 2 < ncols ? quant_value(i2, grid) : 0.0f;
+      o.w = col0 + 3 < ncols ? quant_value(i3, grid) : 0.0f;
+      reinterpret_cast<float4*>(val)[i] = o;
+    }
+  }
+}
+// Scalar variant for arrays whose length or alignment rules out float4 access.
+__global__ __launch_bounds__(256) void quantize_scalar_kernel(const float* __restrict__ v, size_t n, QuantGrid grid,
+                                                              uint8_t* __restrict__ idx, float* __restrict__ val) {
+  const size_t stride = (size_t)gridDim.x * 256;
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += stride) {
+    const int id = quant_index(v[i], grid);
+    if (idx) idx[i] = (uint8_t)id;
+    if (val) val[i] = quant_value(id, grid);
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// Reductions behind the objective (Section 3.2, L_rho) and the residual (Algorithm 1).
+// Per block three partials: sum (q - relu(z))^2, sum u (p_next - q), sum (p_next - q)^2.
+// ------------------------------------------------------------------------------------------
+struct PairSeg {
+  const float* z;
+  const float* q;
+  const float* u;
+  const float* pnext;
+  double* part;       // 3 per block
+  size_t n4;
+  int blk0, nblk;
+};
+
+__global__ __launch_bounds__(256) void pair_reduce_kernel(const PairSeg* __restrict__ segs, int nseg) {
+  __shared__ double red[4];
+  const int lb = blockIdx.x;
+  int si = 0;
+  while (si + 1 < nseg && lb >= segs[si + 1].blk0) ++si;
+  const PairSeg S = segs[si];
+  const size_t stride = (size_t)S.nblk * 256;
+  double s_act = 0, s_dl = 0, s_dq = 0;
+  for (size_t i = (size_t)(lb - S.blk0) * 256 + threadIdx.x; i < S.n4; i += stride) {
+    const float4 z = reinterpret_cast<const float4*>(S.z)[i];
+    const float4 q = reinterpret_cast<const float4*>(S.q)[i];
+    const float4 u = reinterpret_cast<const float4*>(S.u)[i];
+    const float4 p = reinterpret_cast<const float4*>(S.pnext)[i];
+#define PDADMM_PR(c)                                              \
+  {                                                               \
+    const double a = (double)q.c - (double)fmaxf(z.c, 0.0f);      \
+    const double r = (double)p.c - (double)q.c;                   \
+    s_act += a * a;                                               \
+    s_dl += (double)u.c * r;                                      \
+    s_dq += r * r;                                                \
+  }
+    PDADMM_PR(x) PDADMM_PR(y) PDADMM_PR(z) PDADMM_PR(w)
+#undef PDADMM_PR
+  }
+  const double t0 = block_sum_256(s_act, red);
+  const double t1 = block_sum_256(s_dl, red);
+  const double t2 = block_sum_256(s_dq, red);
+  if (threadIdx.x == 0) {
+    double* o = S.part + (size_t)(lb - S.blk0) * 3;
+    o[0] = t0; o[1] = t1; o[2] = t2;
+  }
+}
+
+// R(z_L; y) = sum over labelled nodes of logsumexp(z) - z_y. One thread per node.
+__global__ __launch_bounds__(256) void risk_kernel(const float* __restrict__ z, const int* __restrict__ y,
+                                                   const uint8_t* __restrict__ mask, int rows, int C, int ld,
+                                                   double* __restrict__ part) {
+  __shared__ double red[4];
+  const int node = blockIdx.x * 256 + threadIdx.x;
+  double v = 0.0;
+  if (node < rows && (!mask || mask[node])) {
+    const float* zr = z + (size_t)node * ld;
+    float mx = zr[0];
+    for (int c = 1; c < C; ++c) mx = fmaxf(mx, zr[c]);
+    double s = 0.0;
+    for (int c = 0; c < C; ++c) s += exp((double)zr[c] - (double)mx);
+    v = (double)mx + log(s) - (double)zr[y[node]];
+  }
+  const double t = block_sum_256(v, red);
+  if (threadIdx.x == 0) part[blockIdx.x] = t;
+}
+
+}  // namespace pdadmm

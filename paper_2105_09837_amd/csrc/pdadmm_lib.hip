@@ -1,0 +1,993 @@
+// C ABI of the pdADMM-G / pdADMM-G-Q iteration for MI355X (see include/pdadmm.h).
+// Host side: workspace layout, descriptor tables for the layer-grouped launches, phase sequencing.
+#include "../../include/pdadmm.h"
+
+#include <algorithm>
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <string>
+#include <vector>
+
+#include "common.h"
+#include "elementwise.h"
+#include "gemm.h"
+#include "spmm.h"
+
+using namespace pdadmm;
+
+namespace {
+
+// ------------------------------------------------------------------------------------------
+// Single-problem entry kernels (descriptor by value: no device memory needed for the table).
+// ------------------------------------------------------------------------------------------
+struct Carver {
+  char* base;
+  size_t off = 0;
+  explicit Carver(void* b) : base(static_cast<char*>(b)) {}
+  template <class T>
+  T* take(size_t count) {
+    off = (off + 255) & ~size_t(255);
+    T* p = base ? reinterpret_cast<T*>(base + off) : nullptr;
+    off += count * sizeof(T);
+    return p;
+  }
+};
+
+inline int round4(int n) { return (n + 3) & ~3; }
+inline int cdiv(int a, int b) { return (a + b - 1) / b; }
+inline int flat_blocks(size_t n4) {
+  size_t b = (n4 + 1023) / 1024;
+  return (int)std::min<size_t>(std::max<size_t>(b, 1), 2048);
+}
+
+struct LayerBufs {
+  int n_in, n_out, ld_in, ld_out;
+  float *W, *Wt, *b, *z, *R, *T, *G, *m, *Gpart;
+  float* p;                 // input of the layer, [N, ld_in]
+  float *g, *d;             // l >= 2: gradient of phi in p, -Q trial direction
+  uint8_t* pidx;            // l >= 2, -Q
+  float *q, *u;             // l < L
+  double *part_a, *part_b, *part_c, *colpart, *pairpart;
+  int splitk, k_chunk;
+  int tiles_in, tiles_out;  // GEMM tiles of [N, n_in] and [N, n_out]
+  int row_blocks, col_blocks;
+};
+
+}  // namespace
+
+struct pdadmm_ctx {
+  pdadmm_config cfg;
+  std::vector<int> dims;
+  int N = 0, L = 0;
+  hipStream_t stream = nullptr;
+  std::vector<LayerBufs> lay;
+  LayerScal* scal = nullptr;
+  int* err = nullptr;
+  int* flags = nullptr;
+  int* h_flags = nullptr;     // pinned host mirror
+  int* labels = nullptr;
+  uint8_t* mask = nullptr;
+  double* riskpart = nullptr;
+  int risk_blocks = 0;
+  QuantGrid grid{0.f, 0.f, 0};
+  // descriptor tables in device memory
+  GemmProb *t_pgrad = nullptr, *t_ptrial = nullptr, *t_wgrad = nullptr, *t_wtrial = nullptr, *t_resid = nullptr,
+           *t_resid_obj = nullptr, *t_fwd = nullptr;
+  int nb_pgrad = 0, nb_ptrial = 0, nb_wgrad = 0, nb_wtrial = 0, nb_resid = 0;
+  std::vector<int> fwd_blocks;
+  ReduceProb* t_red = nullptr;
+  int nb_red = 0;
+  AxpySeg *s_pstep = nullptr, *s_qapply_r = nullptr;
+  int nb_pstep = 0, nb_qapply_r = 0;
+  SelectDesc *sel_p = nullptr, *sel_w = nullptr, *sel_q = nullptr;
+  WStepSeg* s_w = nullptr;
+  int nb_w = 0;
+  RowSeg* s_rows = nullptr;
+  int nb_rows_all = 0, nb_rows_hidden = 0;
+  BiasSeg* s_bias = nullptr;
+  int nb_bias = 0;
+  QuantSeg* s_quant = nullptr;
+  int nb_quant = 0;
+  PairSeg* s_pair = nullptr;
+  int nb_pair = 0;
+  bool dirty = true;
+  long iter = 0;
+  std::string msg;
+};
+
+namespace {
+
+pdadmm_status fail(pdadmm_ctx* c, pdadmm_status s, const std::string& m) {
+  if (c) c->msg = m;
+  return s;
+}
+
+#define HIP_TRY(ctx, call)                                                                   \
+  do {                                                                                       \
+    hipError_t e_ = (call);                                                                  \
+    if (e_ != hipSuccess)                                                                    \
+      return fail(ctx, PDADMM_EHIP, std::string(#call) + ": " + hipGetErrorString(e_));      \
+  } while (0)
+
+#define LAUNCH_CHECK(ctx, what)                                                              \
+  do {                                                                                       \
+    hipError_t e_ = hipGetLastError();                                                       \
+    if (e_ != hipSuccess)                                                                    \
+      return fail(ctx, PDADMM_EHIP, std::string("launch ") + what + ": " + hipGetErrorString(e_)); \
+  } while (0)
+
+bool config_ok(const pdadmm_config* c, std::string* why) {
+  auto bad = [&](const char* m) { if (why) *why = m; return false; };
+  if (!c) return bad("config is NULL");
+  if (c->n_nodes < 1) return bad("n_nodes < 1");
+  if (c->n_layers < 1 || c->n_layers > 4096) return bad("n_layers out of range");
+  if (!c->dims) return bad("dims is NULL");
+  for (int i = 0; i <= c->n_layers; ++i)
+    if (c->dims[i] < 1) return bad("a layer width is < 1");
+  if (c->dims[c->n_layers] > 1024) return bad("n_L > 1024 classes is not supported");
+  if (!(c->rho > 0.f) || !(c->nu > 0.f)) return bad("rho and nu must be > 0");
+  if (c->quantize != 0 && c->quantize != 1) return bad("quantize must be 0 or 1");
+  if (c->quantize) {
+    if (c->q_levels < 2 || c->q_levels > 256) return bad("q_levels must be in 2..256");
+    if (!(c->q_hi > c->q_lo)) return bad("q_hi must exceed q_lo");
+  }
+  if (c->fista_iters < 0) return bad("fista_iters < 0");
+  if (!(c->bt_eta > 1.f)) return bad("bt_eta must be > 1");
+  if (!(c->tau0 > 0.f) || !(c->theta0 > 0.f)) return bad("tau0/theta0 must be > 0");
+  if (c->bt_max_trials < 1) return bad("bt_max_trials < 1");
+  if (c->refresh_every < 0) return bad("refresh_every < 0");
+  return true;
+}
+
+QuantGrid make_grid(float lo, float hi, int levels) {
+  QuantGrid g;
+  g.lo = lo;
+  g.step = (hi - lo) / (float)(levels - 1);
+  g.levels = levels;
+  return g;
+}
+
+// Lay the workspace out. With base == nullptr only the size is computed.
+size_t plan(pdadmm_ctx* c, void* base) {
+  Carver cv(base);
+  const int N = c->N, L = c->L;
+  const bool Q = c->cfg.quantize != 0;
+  c->lay.assign(L, LayerBufs{});
+  // split-K plan for the W-gradient products: equal rows of nodes per block across layers
+  size_t tile_rows = 0;
+  for (int i = 0; i < L; ++i) tile_rows += (size_t)cdiv(c->dims[i + 1], BM) * cdiv(c->dims[i], BN) * N;
+  const size_t want_blocks = 1536;
+  int chunk = (int)std::max<size_t>(256, tile_rows / want_blocks);
+  chunk = std::min(chunk, N);
+  chunk = cdiv(chunk, BK) * BK;
+  for (int i = 0; i < L; ++i) {
+    LayerBufs& b = c->lay[i];
+    b.n_in = c->dims[i];
+    b.n_out = c->dims[i + 1];
+    b.ld_in = round4(b.n_in);
+    b.ld_out = round4(b.n_out);
+    b.splitk = cdiv(N, chunk);
+    b.k_chunk = chunk;
+    b.tiles_in = cdiv(N, BM) * cdiv(b.n_in, BN);
+    b.tiles_out = cdiv(N, BM) * cdiv(b.n_out, BN);
+    b.row_blocks = cdiv(N, kRowsPerBlock);
+    b.col_blocks = cdiv(b.ld_out / 4, 64);
+    const size_t in_sz = (size_t)N * b.ld_in, out_sz = (size_t)N * b.ld_out;
+    b.W = cv.take<float>((size_t)b.n_out * b.ld_in);
+    b.Wt = cv.take<float>((size_t)b.n_in * b.ld_out);
+    b.G = cv.take<float>((size_t)b.n_out * b.ld_in);
+    b.Gpart = cv.take<float>((size_t)b.splitk * b.n_out * b.ld_in);
+    b.b = cv.take<float>(b.ld_out);
+    b.m = cv.take<float>(b.ld_out);
+    b.z = cv.take<float>(out_sz);
+    b.R = cv.take<float>(out_sz);
+    b.T = cv.take<float>(out_sz);
+    b.p = cv.take<float>(in_sz);
+    if (i >= 1) {
+      b.g = cv.take<float>(in_sz);
+      if (Q) {
+        b.d = cv.take<float>(in_sz);
+        b.pidx = cv.take<uint8_t>(in_sz);
+      }
+    }
+    if (i < L - 1) {
+      b.q = cv.take<float>(out_sz);
+      b.u = cv.take<float>(out_sz);
+    }
+    const size_t np = 2 * (size_t)std::max({b.tiles_in, b.tiles_out, 2048});
+    b.part_a = cv.take<double>(np);
+    b.part_b = cv.take<double>(np);
+    b.part_c = cv.take<double>(np);
+    b.colpart = cv.take<double>((size_t)b.row_blocks * b.ld_out);
+    b.pairpart = cv.take<double>(3 * 2048);
+  }
+  c->scal = cv.take<LayerScal>(L);
+  c->err = cv.take<int>(1);
+  c->flags = cv.take<int>(L);
+  c->labels = cv.take<int>(N);
+  c->mask = cv.take<uint8_t>(N);
+  c->risk_blocks = cdiv(N, 256);
+  c->riskpart = cv.take<double>(c->risk_blocks);
+  c->t_pgrad = cv.take<GemmProb>(L);
+  c->t_ptrial = cv.take<GemmProb>(L);
+  c->t_wgrad = cv.take<GemmProb>(L);
+  c->t_wtrial = cv.take<GemmProb>(L);
+  c->t_resid = cv.take<GemmProb>(L);
+  c->t_resid_obj = cv.take<GemmProb>(L);
+  c->t_fwd = cv.take<GemmProb>(L);
+  c->t_red = cv.take<ReduceProb>(L);
+  c->s_pstep = cv.take<AxpySeg>(2 * L);
+  c->s_qapply_r = cv.take<AxpySeg>(L);
+  c->sel_p = cv.take<SelectDesc>(L);
+  c->sel_w = cv.take<SelectDesc>(L);
+  c->sel_q = cv.take<SelectDesc>(L);
+  c->s_w = cv.take<WStepSeg>(L);
+  c->s_rows = cv.take<RowSeg>(L);
+  c->s_bias = cv.take<BiasSeg>(L);
+  c->s_quant = cv.take<QuantSeg>(L);
+  c->s_pair = cv.take<PairSeg>(L);
+  return (cv.off + 255) & ~size_t(255);
+}
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+
+GemmProb make_nt(const float* A, int lda, const float* B, int ldb, float* C, int ldc, int M, int N, int K) {
+  GemmProb P{};
+  P.A = A; P.B = B; P.C = C;
+  P.M = M; P.N = N; P.K = K;
+  P.lda = lda; P.ldb = ldb; P.ldc = ldc;
+  P.tiles_m = cdiv(M, BM);
+  P.tiles_n = cdiv(N, BN);
+  P.splitk = 1;
+  P.k_chunk = K;
+  P.nblk = P.tiles_m * P.tiles_n;
+  P.vecA = (lda % 4 == 0) && aligned16(A);
+  P.vecB = (ldb % 4 == 0) && aligned16(B);
+  P.alpha = 1.f;
+  P.beta = 0.f;
+  P.layer = 0;
+  return P;
+}
+
+GemmProb make_tn(const float* A, int lda, const float* B, int ldb, float* part, int ldc, int M, int N, int K,
+                 int splitk, int k_chunk) {
+  GemmProb P = make_nt(A, lda, B, ldb, part, ldc, M, N, K);
+  P.splitk = splitk;
+  P.k_chunk = k_chunk;
+  P.nblk = P.tiles_m * P.tiles_n * splitk;
+  return P;
+}
+
+template <class T>
+pdadmm_status upload(pdadmm_ctx* c, T* dst, const std::vector<T>& src) {
+  if (src.empty()) return PDADMM_OK;
+  HIP_TRY(c, hipMemcpyAsync(dst, src.data(), src.size() * sizeof(T), hipMemcpyHostToDevice, c->stream));
+  HIP_TRY(c, hipStreamSynchronize(c->stream));   // the host vector goes out of scope in the caller
+  return PDADMM_OK;
+}
+
+template <class T>
+int assign_blocks(std::vector<T>& v) {
+  int b = 0;
+  for (auto& e : v) {
+    e.blk0 = b;
+    b += e.nblk;
+  }
+  return b;
+}
+
+pdadmm_status build_tables(pdadmm_ctx* c) {
+  const int N = c->N, L = c->L;
+  const float rho = c->cfg.rho, nu = c->cfg.nu;
+  const bool Q = c->cfg.quantize != 0;
+  std::vector<GemmProb> pgrad, ptrial, wgrad, wtrial, resid, resid_obj, fwd;
+  std::vector<ReduceProb> red;
+  std::vector<AxpySeg> pstep, qapply_r;
+  std::vector<SelectDesc> sel_p, sel_w, sel_q;
+  std::vector<WStepSeg> wseg;
+  std::vector<RowSeg> rows;
+  std::vector<BiasSeg> bias;
+  std::vector<QuantSeg> quant;
+  std::vector<PairSeg> pair;
+  for (int i = 0; i < L; ++i) {
+    LayerBufs& b = c->lay[i];
+    if (i >= 1) {
+      // gradient of phi in p_l: g = nu * R W + u_{l-1} + rho (p_l - q_{l-1});  R W = R (Wt)^T
+      GemmProb P = make_nt(b.R, b.ld_out, b.Wt, b.ld_out, b.g, b.ld_in, N, b.n_in, b.n_out);
+      P.e0 = c->lay[i - 1].u; P.e1 = b.p; P.e2 = c->lay[i - 1].q;
+      P.alpha = nu; P.beta = rho; P.part = b.part_a; P.layer = i;
+      pgrad.push_back(P);
+      // image of the step direction under W_l: T = dir W^T (dir = g, or d in -Q)
+      GemmProb T = make_nt(Q ? b.d : b.g, b.ld_in, b.W, b.ld_in, b.T, b.ld_out, N, b.n_out, b.n_in);
+      T.part = b.part_b; T.layer = i;
+      ptrial.push_back(T);
+      SelectDesc s{};
+      s.part_g = b.part_a; s.ng = P.nblk; s.part_t = b.part_b; s.nt = T.nblk; s.stride_t = 1; s.layer = i;
+      sel_p.push_back(s);
+      AxpySeg a{};
+      a.y = b.p; a.x = b.g; a.n4 = (size_t)N * b.ld_in / 4; a.nblk = flat_blocks(a.n4); a.layer = i;
+      a.which = kScaleInvTau;
+      AxpySeg r{};
+      r.y = b.R; r.x = b.T; r.n4 = (size_t)N * b.ld_out / 4; r.nblk = flat_blocks(r.n4); r.layer = i;
+      r.which = kScaleInvTau;
+      pstep.push_back(a);
+      pstep.push_back(r);
+      if (Q) {
+        QuantSeg qs{};
+        qs.p = b.p; qs.g = b.g; qs.d = b.d; qs.idx = b.pidx; qs.dpart = b.part_c;
+        qs.n4 = (size_t)N * b.ld_in / 4; qs.ncols = b.n_in; qs.ld = b.ld_in;
+        qs.nblk = flat_blocks(qs.n4); qs.layer = i;
+        quant.push_back(qs);
+        SelectDesc sq{};
+        sq.part_g = b.part_c; sq.ng = qs.nblk; sq.part_t = b.part_b; sq.nt = T.nblk; sq.stride_t = 1; sq.layer = i;
+        sel_q.push_back(sq);
+        AxpySeg ar = r;
+        ar.which = kScaleMinusOneIfStep;
+        qapply_r.push_back(ar);
+      }
+    }
+    // gradient of phi in W_l: G = nu * R^T p  (contraction over the nodes, split in chunks)
+    GemmProb Wg = make_tn(b.R, b.ld_out, b.p, b.ld_in, b.Gpart, b.ld_in, b.n_out, b.n_in, N, b.splitk, b.k_chunk);
+    Wg.layer = i;
+    wgrad.push_back(Wg);
+    ReduceProb rp{};
+    rp.part = b.Gpart; rp.G = b.G; rp.norm_part = b.part_a; rp.M = b.n_out; rp.N = b.n_in; rp.ld = b.ld_in;
+    rp.splitk = b.splitk; rp.alpha = nu;
+    rp.nblk = std::min(2048, std::max(1, cdiv(b.n_out * b.ld_in, 1024)));
+    red.push_back(rp);
+    // image of G under p: T = p G^T
+    GemmProb Wt_ = make_nt(b.p, b.ld_in, b.G, b.ld_in, b.T, b.ld_out, N, b.n_out, b.n_in);
+    Wt_.part = b.part_b; Wt_.layer = i;
+    wtrial.push_back(Wt_);
+    SelectDesc sw{};
+    sw.part_g = b.part_a; sw.ng = rp.nblk; sw.part_t = b.part_b; sw.nt = Wt_.nblk; sw.stride_t = 1; sw.layer = i;
+    sel_w.push_back(sw);
+    WStepSeg ws{};
+    ws.W = b.W; ws.Wt = b.Wt; ws.G = b.G; ws.n_out = b.n_out; ws.n_in = b.n_in; ws.ld_in = b.ld_in;
+    ws.ld_out = b.ld_out; ws.tiles_c = cdiv(b.n_in, 32); ws.nblk = cdiv(b.n_out, 32) * ws.tiles_c; ws.layer = i;
+    wseg.push_back(ws);
+    // carried residual from scratch: R = p W^T + b - z
+    GemmProb Rf = make_nt(b.p, b.ld_in, b.W, b.ld_in, b.R, b.ld_out, N, b.n_out, b.n_in);
+    Rf.e0 = b.b; Rf.e1 = b.z; Rf.e2 = nullptr; Rf.part = b.part_b; Rf.layer = i;
+    resid.push_back(Rf);
+    GemmProb Ro = Rf;
+    Ro.C = b.T; Ro.e2 = b.R;
+    resid_obj.push_back(Ro);
+    // forward pass of the starting point
+    GemmProb Fw = make_nt(b.p, b.ld_in, b.W, b.ld_in, b.z, b.ld_out, N, b.n_out, b.n_in);
+    Fw.e0 = b.b;
+    if (i < L - 1) { Fw.o1 = b.q; Fw.o2 = c->lay[i + 1].p; }
+    Fw.grid = Q ? c->grid : QuantGrid{0.f, 0.f, 0};
+    Fw.blk0 = 0;
+    fwd.push_back(Fw);
+    RowSeg rs{};
+    rs.R = b.R; rs.T = b.T; rs.z = b.z; rs.q = b.q; rs.u = b.u;
+    rs.pnext = i < L - 1 ? c->lay[i + 1].p : nullptr;
+    rs.m = b.m; rs.colpart = b.colpart; rs.rpart = nullptr;
+    rs.rows = N; rs.ncols = b.n_out; rs.ld = b.ld_out;
+    rs.col_blocks = b.col_blocks; rs.row_blocks = b.row_blocks; rs.nblk = b.col_blocks * b.row_blocks; rs.layer = i;
+    rows.push_back(rs);
+    BiasSeg bs{};
+    bs.b = b.b; bs.m = b.m; bs.colpart = b.colpart; bs.ncols = b.n_out; bs.ld = b.ld_out;
+    bs.row_blocks = b.row_blocks; bs.rows = N; bs.nblk = cdiv(b.ld_out, 256);
+    bias.push_back(bs);
+    if (i < L - 1) {
+      PairSeg ps{};
+      ps.z = b.z; ps.q = b.q; ps.u = b.u; ps.pnext = c->lay[i + 1].p; ps.part = b.pairpart;
+      ps.n4 = (size_t)N * b.ld_out / 4; ps.nblk = flat_blocks(ps.n4);
+      pair.push_back(ps);
+    }
+  }
+  c->nb_pgrad = assign_blocks(pgrad);
+  c->nb_ptrial = assign_blocks(ptrial);
+  c->nb_wgrad = assign_blocks(wgrad);
+  c->nb_wtrial = assign_blocks(wtrial);
+  c->nb_resid = assign_blocks(resid);
+  assign_blocks(resid_obj);
+  c->nb_red = assign_blocks(red);
+  c->nb_pstep = assign_blocks(pstep);
+  c->nb_qapply_r = assign_blocks(qapply_r);
+  c->nb_w = assign_blocks(wseg);
+  {
+    // rows: hidden layers first in block order is not needed; the zqu launch simply uses the first L-1 entries
+    c->nb_rows_all = assign_blocks(rows);
+    c->nb_rows_hidden = L > 1 ? rows[L - 1].blk0 : 0;
+  }
+  c->nb_bias = assign_blocks(bias);
+  c->nb_quant = assign_blocks(quant);
+  c->nb_pair = assign_blocks(pair);
+  c->fwd_blocks.clear();
+  for (auto& f : fwd) c->fwd_blocks.push_back(f.nblk);
+  pdadmm_status s;
+#define UP(dst, v) if ((s = upload(c, dst, v)) != PDADMM_OK) return s
+  UP(c->t_pgrad, pgrad); UP(c->t_ptrial, ptrial); UP(c->t_wgrad, wgrad); UP(c->t_wtrial, wtrial);
+  UP(c->t_resid, resid); UP(c->t_resid_obj, resid_obj); UP(c->t_fwd, fwd); UP(c->t_red, red);
+  UP(c->s_pstep, pstep); UP(c->s_qapply_r, qapply_r); UP(c->sel_p, sel_p); UP(c->sel_w, sel_w); UP(c->sel_q, sel_q);
+  UP(c->s_w, wseg); UP(c->s_rows, rows); UP(c->s_bias, bias); UP(c->s_quant, quant); UP(c->s_pair, pair);
+#undef UP
+  return PDADMM_OK;
+}
+
+template <bool KC, class Epi>
+void launch_gemm(pdadmm_ctx* c, const GemmProb* table, int nprob, int blocks, int predicated) {
+  if (blocks <= 0) return;
+  hipLaunchKernelGGL((gemm_kernel<KC, Epi>), dim3(blocks), dim3(256), 0, c->stream, table, nprob, blocks, c->scal,
+                     predicated);
+}
+
+pdadmm_status refresh_residual(pdadmm_ctx* c) {
+  // transposed weights, then R = p W^T + b - z for every layer
+  hipLaunchKernelGGL(w_step_kernel, dim3(c->nb_w), dim3(256), 0, c->stream, c->s_w, c->L, c->scal, 1);
+  LAUNCH_CHECK(c, "w_step(copy)");
+  launch_gemm<true, EpiResid>(c, c->t_resid, c->L, c->nb_resid, 0);
+  LAUNCH_CHECK(c, "gemm resid");
+  c->dirty = false;
+  return PDADMM_OK;
+}
+
+pdadmm_status phase_p(pdadmm_ctx* c) {
+  const int L = c->L;
+  if (L < 2) return PDADMM_OK;
+  const pdadmm_config& g = c->cfg;
+  launch_gemm<true, EpiPGrad>(c, c->t_pgrad, L - 1, c->nb_pgrad, 0);
+  LAUNCH_CHECK(c, "gemm pgrad");
+  if (!g.quantize) {
+    launch_gemm<true, EpiStoreNorm>(c, c->t_ptrial, L - 1, c->nb_ptrial, 0);
+    LAUNCH_CHECK(c, "gemm ptrial");
+    hipLaunchKernelGGL(select_step_kernel, dim3(L - 1), dim3(256), 0, c->stream, c->sel_p, c->scal, 0, g.rho, g.nu,
+                       g.bt_eta, g.bt_max_trials, c->err);
+    LAUNCH_CHECK(c, "select tau");
+    hipLaunchKernelGGL(axpy_kernel, dim3(c->nb_pstep), dim3(256), 0, c->stream, c->s_pstep, 2 * (L - 1), c->scal);
+    LAUNCH_CHECK(c, "p step");
+    return PDADMM_OK;
+  }
+  // -Q: trial rounds; the host only learns which layers are still searching
+  hipLaunchKernelGGL(select_quant_kernel, dim3(L - 1), dim3(256), 0, c->stream, c->sel_p, c->scal, 0, g.rho, g.nu,
+                     g.bt_eta, g.bt_max_trials, c->err, c->flags);
+  LAUNCH_CHECK(c, "select quant arm");
+  for (int round = 0; round <= g.bt_max_trials; ++round) {
+    HIP_TRY(c, hipMemcpyAsync(c->h_flags, c->flags, sizeof(int) * L, hipMemcpyDeviceToHost, c->stream));
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    bool any = false;
+    for (int i = 1; i < L; ++i) any = any || c->h_flags[i] != 0;
+    if (!any) break;
+    hipLaunchKernelGGL(quant_trial_kernel, dim3(c->nb_quant), dim3(256), 0, c->stream, c->s_quant, L - 1, c->scal,
+                       c->grid);
+    LAUNCH_CHECK(c, "quant trial");
+    launch_gemm<true, EpiStoreNorm>(c, c->t_ptrial, L - 1, c->nb_ptrial, 1);
+    LAUNCH_CHECK(c, "gemm qtrial");
+    hipLaunchKernelGGL(select_quant_kernel, dim3(L - 1), dim3(256), 0, c->stream, c->sel_q, c->scal, 1, g.rho, g.nu,
+                       g.bt_eta, g.bt_max_trials, c->err, c->flags);
+    LAUNCH_CHECK(c, "select quant judge");
+  }
+  hipLaunchKernelGGL(quant_apply_kernel, dim3(c->nb_quant), dim3(256), 0, c->stream, c->s_quant, L - 1, c->scal,
+                     c->grid);
+  LAUNCH_CHECK(c, "quant apply");
+  hipLaunchKernelGGL(axpy_kernel, dim3(c->nb_qapply_r), dim3(256), 0, c->stream, c->s_qapply_r, L - 1, c->scal);
+  LAUNCH_CHECK(c, "quant apply R");
+  return PDADMM_OK;
+}
+
+pdadmm_status phase_w(pdadmm_ctx* c) {
+  const int L = c->L;
+  const pdadmm_config& g = c->cfg;
+  launch_gemm<false, EpiStore>(c, c->t_wgrad, L, c->nb_wgrad, 0);
+  LAUNCH_CHECK(c, "gemm wgrad");
+  hipLaunchKernelGGL(splitk_reduce_kernel, dim3(c->nb_red), dim3(256), 0, c->stream, c->t_red, L);
+  LAUNCH_CHECK(c, "splitk reduce");
+  launch_gemm<true, EpiStoreNorm>(c, c->t_wtrial, L, c->nb_wtrial, 0);
+  LAUNCH_CHECK(c, "gemm wtrial");
+  hipLaunchKernelGGL(select_step_kernel, dim3(L), dim3(256), 0, c->stream, c->sel_w, c->scal, 1, g.rho, g.nu,
+                     g.bt_eta, g.bt_max_trials, c->err);
+  LAUNCH_CHECK(c, "select theta");
+  hipLaunchKernelGGL(w_step_kernel, dim3(c->nb_w), dim3(256), 0, c->stream, c->s_w, L, c->scal, 0);
+  LAUNCH_CHECK(c, "w step");
+  return PDADMM_OK;
+}
+
+pdadmm_status launch_fista(pdadmm_ctx* c) {
+  const LayerBufs& b = c->lay[c->L - 1];
+  const int C = b.n_out;
+  int G = 1;
+  while (G < C && G < 64) G <<= 1;
+  const int E = cdiv(C, G);
+  const int nodes_per_block = 256 / G;
+  const int blocks = cdiv(c->N, nodes_per_block);
+  const uint8_t* mask = c->mask;
+#define FISTA(EE)                                                                                              \
+  hipLaunchKernelGGL((fista_kernel<EE>), dim3(blocks), dim3(256), 0, c->stream, b.R, b.z, b.m, c->labels, mask, \
+                     c->N, C, b.ld_out, G, c->cfg.nu, c->cfg.fista_iters)
+  if (E <= 1) FISTA(1);
+  else if (E <= 2) FISTA(2);
+  else if (E <= 4) FISTA(4);
+  else if (E <= 8) FISTA(8);
+  else FISTA(16);
+#undef FISTA
+  LAUNCH_CHECK(c, "fista");
+  return PDADMM_OK;
+}
+
+pdadmm_status phase_bzqu(pdadmm_ctx* c) {
+  const int L = c->L;
+  const pdadmm_config& g = c->cfg;
+  hipLaunchKernelGGL(resid_colsum_kernel, dim3(c->nb_rows_all), dim3(256), 0, c->stream, c->s_rows, L, c->scal);
+  LAUNCH_CHECK(c, "resid colsum");
+  hipLaunchKernelGGL(bias_step_kernel, dim3(c->nb_bias), dim3(256), 0, c->stream, c->s_bias, L);
+  LAUNCH_CHECK(c, "bias step");
+  if (L > 1) {
+    hipLaunchKernelGGL(zqu_kernel, dim3(c->nb_rows_hidden), dim3(256), 0, c->stream, c->s_rows, L - 1, g.rho, g.nu);
+    LAUNCH_CHECK(c, "zqu");
+  }
+  return launch_fista(c);
+}
+
+pdadmm_status check_device_flags(pdadmm_ctx* c) {
+  int e = 0;
+  HIP_TRY(c, hipMemcpyAsync(c->h_flags, c->err, sizeof(int), hipMemcpyDeviceToHost, c->stream));
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  e = c->h_flags[0];
+  if (e & kErrNonFinite) return fail(c, PDADMM_ENONFINITE, "a step-size norm became NaN/Inf");
+  if (e & kErrBacktrack) return fail(c, PDADMM_EBACKTRACK, "bt_max_trials exceeded");
+  return PDADMM_OK;
+}
+
+struct VarRef {
+  void* ptr;
+  int rows, cols, ld;
+  size_t elem;
+};
+
+pdadmm_status locate(pdadmm_ctx* c, int kind, int layer, bool writing, VarRef* v) {
+  const int L = c->L;
+  if (layer < 1 || layer > L) return fail(c, PDADMM_EINVAL, "layer out of range");
+  LayerBufs& b = c->lay[layer - 1];
+  v->elem = sizeof(float);
+  switch (kind) {
+    case PDADMM_VAR_P:
+      if (writing && layer == 1) return fail(c, PDADMM_EINVAL, "p_1 = X is fixed");
+      *v = {b.p, c->N, b.n_in, b.ld_in, sizeof(float)};
+      return PDADMM_OK;
+    case PDADMM_VAR_W: *v = {b.W, b.n_out, b.n_in, b.ld_in, sizeof(float)}; return PDADMM_OK;
+    case PDADMM_VAR_B: *v = {b.b, 1, b.n_out, b.ld_out, sizeof(float)}; return PDADMM_OK;
+    case PDADMM_VAR_Z: *v = {b.z, c->N, b.n_out, b.ld_out, sizeof(float)}; return PDADMM_OK;
+    case PDADMM_VAR_Q:
+    case PDADMM_VAR_U:
+      if (layer == L) return fail(c, PDADMM_EINVAL, "q_l, u_l exist for l < L only");
+      *v = {kind == PDADMM_VAR_Q ? b.q : b.u, c->N, b.n_out, b.ld_out, sizeof(float)};
+      return PDADMM_OK;
+    case PDADMM_VAR_PIDX:
+      if (writing || !c->cfg.quantize || layer < 2) return fail(c, PDADMM_EINVAL, "PIDX: get only, -Q, l >= 2");
+      *v = {b.pidx, c->N, b.n_in, b.ld_in, 1};
+      return PDADMM_OK;
+    case PDADMM_VAR_RESID:
+      if (writing) return fail(c, PDADMM_EINVAL, "read-only variable");
+      *v = {b.R, c->N, b.n_out, b.ld_out, sizeof(float)};
+      return PDADMM_OK;
+    case PDADMM_VAR_GRAD_P:
+      if (writing || layer < 2) return fail(c, PDADMM_EINVAL, "GRAD_P: get only, l >= 2");
+      *v = {b.g, c->N, b.n_in, b.ld_in, sizeof(float)};
+      return PDADMM_OK;
+    case PDADMM_VAR_GRAD_W:
+      if (writing) return fail(c, PDADMM_EINVAL, "read-only variable");
+      *v = {b.G, b.n_out, b.n_in, b.ld_in, sizeof(float)};
+      return PDADMM_OK;
+    default: return fail(c, PDADMM_EINVAL, "unknown variable kind");
+  }
+}
+
+}  // namespace
+
+// ==========================================================================================
+// C ABI
+// ==========================================================================================
+extern "C" {
+
+pdadmm_status pdadmm_normalize_adj(int32_t n, const int32_t* rowptr, const int32_t* colidx, int32_t* out_rowptr,
+                                   int32_t* out_colidx, float* out_vals) {
+  if (n < 0 || !rowptr || !out_rowptr || (!colidx && n > 0 && rowptr[n] > 0) || !out_colidx || !out_vals)
+    return PDADMM_EINVAL;
+  if (rowptr[0] != 0) return PDADMM_EINVAL;
+  for (int i = 0; i < n; ++i) {
+    if (rowptr[i + 1] < rowptr[i]) return PDADMM_EINVAL;
+    for (int e = rowptr[i]; e < rowptr[i + 1]; ++e) {
+      const int j = colidx[e];
+      if (j < 0 || j >= n || j == i) return PDADMM_EINVAL;
+      if (e > rowptr[i] && colidx[e - 1] >= j) return PDADMM_EINVAL;
+    }
+  }
+  int64_t o = 0;
+  out_rowptr[0] = 0;
+  for (int i = 0; i < n; ++i) {
+    const int64_t di = (int64_t)(rowptr[i + 1] - rowptr[i]) + 1;
+    bool self_done = false;
+    auto emit = [&](int j) {
+      const int64_t dj = (int64_t)(rowptr[j + 1] - rowptr[j]) + 1;
+      out_colidx[o] = j;
+      out_vals[o] = (float)(1.0 / std::sqrt((double)(di * dj)));
+      ++o;
+    };
+    for (int e = rowptr[i]; e < rowptr[i + 1]; ++e) {
+      const int j = colidx[e];
+      if (!self_done && j > i) {
+        emit(i);
+        self_done = true;
+      }
+      emit(j);
+    }
+    if (!self_done) emit(i);
+    if (o > INT32_MAX) return PDADMM_EINVAL;
+    out_rowptr[i + 1] = (int32_t)o;
+  }
+  return PDADMM_OK;
+}
+
+pdadmm_status pdadmm_augment(int32_t n, int64_t nnz, const int32_t* rowptr, const int32_t* colidx, const float* vals,
+                             const float* X, int32_t d, int32_t hops, float* X_aug, void* stream) {
+  if (n < 0 || nnz < 0 || d < 1 || hops < 0) return PDADMM_EINVAL;
+  if (n == 0) return PDADMM_OK;
+  if (!rowptr || !X || !X_aug || (nnz > 0 && (!colidx || !vals))) return PDADMM_EINVAL;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const int ld = (hops + 1) * d;
+  if (hipMemcpy2DAsync(X_aug, (size_t)ld * 4, X, (size_t)d * 4, (size_t)d * 4, n, hipMemcpyDeviceToDevice, st) !=
+      hipSuccess)
+    return PDADMM_EHIP;
+  const bool vec = (d % 4 == 0) && aligned16(X_aug);
+  for (int k = 1; k <= hops; ++k) {
+    const float* src = X_aug + (size_t)(k - 1) * d;
+    float* dst = X_aug + (size_t)k * d;
+    if (vec) {
+      const size_t items = (size_t)n * (d / 4);
+      hipLaunchKernelGGL((spmm_hop_kernel<4>), dim3((unsigned)((items + 255) / 256)), dim3(256), 0, st, n, rowptr,
+                         colidx, vals, src, dst, d, ld);
+    } else {
+      const size_t items = (size_t)n * d;
+      hipLaunchKernelGGL((spmm_hop_kernel<1>), dim3((unsigned)((items + 255) / 256)), dim3(256), 0, st, n, rowptr,
+                         colidx, vals, src, dst, d, ld);
+    }
+    if (hipGetLastError() != hipSuccess) return PDADMM_EHIP;
+  }
+  return PDADMM_OK;
+}
+
+pdadmm_status pdadmm_quantize(const float* v, int64_t count, float lo, float hi, int32_t levels, uint8_t* idx,
+                              float* val, void* stream) {
+  if (count < 0 || levels < 2 || levels > 256 || !(hi > lo)) return PDADMM_EINVAL;
+  if (count == 0) return PDADMM_OK;
+  if (!v || (!idx && !val)) return PDADMM_EINVAL;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const QuantGrid g = make_grid(lo, hi, levels);
+  const bool vec = count % 4 == 0 && aligned16(v) && (!val || aligned16(val)) &&
+                   (!idx || (reinterpret_cast<uintptr_t>(idx) & 3) == 0);
+  if (vec) {
+    const size_t n4 = (size_t)count / 4;
+    // ld = a multiple of 4 large enough that no column is masked
+    hipLaunchKernelGGL(quantize_kernel, dim3(flat_blocks(n4)), dim3(256), 0, st, v, n4, 4, 4, g, idx, val);
+  } else {
+    hipLaunchKernelGGL(quantize_scalar_kernel, dim3(flat_blocks(((size_t)count + 3) / 4)), dim3(256), 0, st, v,
+                       (size_t)count, g, idx, val);
+  }
+  return hipGetLastError() == hipSuccess ? PDADMM_OK : PDADMM_EHIP;
+}
+
+}  // extern "C"
+
+
+extern "C" {
+
+pdadmm_status pdadmm_gemm_nt(int32_t M, int32_t N, int32_t K, const float* A, int32_t lda, const float* B,
+                             int32_t ldb, float* C, int32_t ldc, void* stream) {
+  if (M < 1 || N < 1 || K < 1 || !A || !B || !C || lda < K || ldb < K || ldc < N) return PDADMM_EINVAL;
+  GemmProb P = make_nt(A, lda, B, ldb, C, ldc, M, N, K);
+  hipLaunchKernelGGL((gemm_one_kernel<true, EpiStore>), dim3(P.nblk), dim3(256), 0, static_cast<hipStream_t>(stream),
+                     P);
+  return hipGetLastError() == hipSuccess ? PDADMM_OK : PDADMM_EHIP;
+}
+
+pdadmm_status pdadmm_gemm_tn(int32_t M, int32_t N, int32_t K, float alpha, const float* A, int32_t lda,
+                             const float* B, int32_t ldb, float* C, int32_t ldc, int32_t splitk, float* part,
+                             void* stream) {
+  if (M < 1 || N < 1 || K < 1 || !A || !B || !C || !part || lda < M || ldb < N || ldc < N || splitk < 1 ||
+      splitk > K)
+    return PDADMM_EINVAL;
+  const int chunk = cdiv(cdiv(K, splitk), BK) * BK;
+  const int sk = cdiv(K, chunk);
+  GemmProb P = make_tn(A, lda, B, ldb, part, ldc, M, N, K, sk, chunk);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  hipLaunchKernelGGL((gemm_one_kernel<false, EpiStore>), dim3(P.nblk), dim3(256), 0, st, P);
+  if (hipGetLastError() != hipSuccess) return PDADMM_EHIP;
+  ReduceProb R{};
+  R.part = part; R.G = C; R.norm_part = nullptr; R.M = M; R.N = N; R.ld = ldc; R.splitk = sk; R.alpha = alpha;
+  R.nblk = std::min(2048, std::max(1, cdiv(M * ldc, 1024)));
+  hipLaunchKernelGGL(splitk_reduce_one_kernel, dim3(R.nblk), dim3(256), 0, st, R);
+  return hipGetLastError() == hipSuccess ? PDADMM_OK : PDADMM_EHIP;
+}
+
+size_t pdadmm_workspace_bytes(const pdadmm_config* cfg) {
+  if (!config_ok(cfg, nullptr)) return 0;
+  pdadmm_ctx tmp;
+  tmp.cfg = *cfg;
+  tmp.N = cfg->n_nodes;
+  tmp.L = cfg->n_layers;
+  tmp.dims.assign(cfg->dims, cfg->dims + cfg->n_layers + 1);
+  return plan(&tmp, nullptr);
+}
+
+pdadmm_status pdadmm_init(pdadmm_ctx** out, const pdadmm_config* cfg, void* workspace, size_t workspace_bytes,
+                          const float* X_aug, const int32_t* labels, const uint8_t* train_mask,
+                          const float* const* W0, const float* const* b0, void* stream) {
+  if (!out) return PDADMM_EINVAL;
+  *out = nullptr;
+  std::string why;
+  if (!config_ok(cfg, &why)) return PDADMM_EINVAL;
+  if (!workspace || !X_aug || !labels || !W0 || !b0) return PDADMM_EINVAL;
+  if (reinterpret_cast<uintptr_t>(workspace) & 255) return PDADMM_EINVAL;
+  for (int i = 0; i < cfg->n_layers; ++i)
+    if (!W0[i] || !b0[i]) return PDADMM_EINVAL;
+  pdadmm_ctx* c = new pdadmm_ctx;
+  c->cfg = *cfg;
+  c->N = cfg->n_nodes;
+  c->L = cfg->n_layers;
+  c->dims.assign(cfg->dims, cfg->dims + cfg->n_layers + 1);
+  c->cfg.dims = c->dims.data();
+  c->stream = static_cast<hipStream_t>(stream);
+  if (cfg->quantize) c->grid = make_grid(cfg->q_lo, cfg->q_hi, cfg->q_levels);
+  const size_t need = plan(c, nullptr);
+  if (workspace_bytes < need) {
+    delete c;
+    return PDADMM_ENOMEM;
+  }
+  plan(c, workspace);
+  *out = c;   // from here on errors are reported through the context; the caller destroys it
+  const int N = c->N, L = c->L;
+  HIP_TRY(c, hipHostMalloc(reinterpret_cast<void**>(&c->h_flags), sizeof(int) * std::max(L, 4), hipHostMallocDefault));
+  HIP_TRY(c, hipMemsetAsync(workspace, 0, need, c->stream));
+  HIP_TRY(c, hipMemcpyAsync(c->labels, labels, sizeof(int) * N, hipMemcpyDeviceToDevice, c->stream));
+  if (train_mask) HIP_TRY(c, hipMemcpyAsync(c->mask, train_mask, N, hipMemcpyDeviceToDevice, c->stream));
+  else c->mask = nullptr;
+  {
+    const LayerBufs& b = c->lay[0];
+    HIP_TRY(c, hipMemcpy2DAsync(b.p, (size_t)b.ld_in * 4, X_aug, (size_t)b.n_in * 4, (size_t)b.n_in * 4, N,
+                                hipMemcpyDeviceToDevice, c->stream));
+  }
+  std::vector<LayerScal> hs(L);
+  for (int i = 0; i < L; ++i) {
+    const LayerBufs& b = c->lay[i];
+    HIP_TRY(c, hipMemcpy2DAsync(b.W, (size_t)b.ld_in * 4, W0[i], (size_t)b.n_in * 4, (size_t)b.n_in * 4, b.n_out,
+                                hipMemcpyDeviceToDevice, c->stream));
+    HIP_TRY(c, hipMemcpyAsync(b.b, b0[i], sizeof(float) * b.n_out, hipMemcpyDeviceToDevice, c->stream));
+    std::memset(&hs[i], 0, sizeof(LayerScal));
+    hs[i].tau = cfg->tau0;
+    hs[i].theta = cfg->theta0;
+  }
+  HIP_TRY(c, hipMemcpyAsync(c->scal, hs.data(), sizeof(LayerScal) * L, hipMemcpyHostToDevice, c->stream));
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  pdadmm_status s = build_tables(c);
+  if (s != PDADMM_OK) return s;
+  // forward-consistent start, layer after layer
+  for (int i = 0; i < L; ++i) {
+    hipLaunchKernelGGL((gemm_kernel<true, EpiForward>), dim3(c->fwd_blocks[i]), dim3(256), 0, c->stream,
+                       c->t_fwd + i, 1, c->fwd_blocks[i], c->scal, 0);
+    LAUNCH_CHECK(c, "gemm forward");
+  }
+  if (cfg->quantize) {
+    for (int i = 1; i < L; ++i) {
+      const LayerBufs& b = c->lay[i];
+      const size_t n4 = (size_t)N * b.ld_in / 4;
+      hipLaunchKernelGGL(quantize_kernel, dim3(flat_blocks(n4)), dim3(256), 0, c->stream, b.p, n4, b.n_in, b.ld_in,
+                         c->grid, b.pidx, (float*)nullptr);
+      LAUNCH_CHECK(c, "quantize idx");
+    }
+  }
+  c->dirty = true;
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  return PDADMM_OK;
+}
+
+pdadmm_status pdadmm_set_var(pdadmm_ctx* c, int32_t kind, int32_t layer, const void* src) {
+  if (!c || !src) return PDADMM_EINVAL;
+  if (kind == PDADMM_VAR_TAU || kind == PDADMM_VAR_THETA) {
+    if (layer < (kind == PDADMM_VAR_TAU ? 2 : 1) || layer > c->L) return fail(c, PDADMM_EINVAL, "layer out of range");
+    const double v = *static_cast<const double*>(src);
+    if (!(v > 0.0)) return fail(c, PDADMM_EINVAL, "tau/theta must be > 0");
+    LayerScal* dst = c->scal + (layer - 1);
+    const size_t off = kind == PDADMM_VAR_TAU ? offsetof(LayerScal, tau) : offsetof(LayerScal, theta);
+    HIP_TRY(c, hipMemcpyAsync(reinterpret_cast<char*>(dst) + off, &v, sizeof(double), hipMemcpyHostToDevice,
+                              c->stream));
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    return PDADMM_OK;
+  }
+  VarRef v;
+  pdadmm_status s = locate(c, kind, layer, true, &v);
+  if (s != PDADMM_OK) return s;
+  HIP_TRY(c, hipMemcpy2DAsync(v.ptr, (size_t)v.ld * v.elem, src, (size_t)v.cols * v.elem, (size_t)v.cols * v.elem,
+                              v.rows, hipMemcpyDefault, c->stream));
+  if (kind == PDADMM_VAR_P && c->cfg.quantize) {
+    const LayerBufs& b = c->lay[layer - 1];
+    const size_t n4 = (size_t)c->N * b.ld_in / 4;
+    hipLaunchKernelGGL(quantize_kernel, dim3(flat_blocks(n4)), dim3(256), 0, c->stream, b.p, n4, b.n_in, b.ld_in,
+                       c->grid, b.pidx, b.p);
+    LAUNCH_CHECK(c, "quantize set_var");
+  }
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  c->dirty = true;
+  return PDADMM_OK;
+}
+
+pdadmm_status pdadmm_get_var(pdadmm_ctx* c, int32_t kind, int32_t layer, void* dst) {
+  if (!c || !dst) return PDADMM_EINVAL;
+  if (kind == PDADMM_VAR_TAU || kind == PDADMM_VAR_THETA) {
+    if (layer < (kind == PDADMM_VAR_TAU ? 2 : 1) || layer > c->L) return fail(c, PDADMM_EINVAL, "layer out of range");
+    const LayerScal* src = c->scal + (layer - 1);
+    const size_t off = kind == PDADMM_VAR_TAU ? offsetof(LayerScal, tau) : offsetof(LayerScal, theta);
+    HIP_TRY(c, hipMemcpyAsync(dst, reinterpret_cast<const char*>(src) + off, sizeof(double), hipMemcpyDeviceToHost,
+                              c->stream));
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    return PDADMM_OK;
+  }
+  VarRef v;
+  pdadmm_status s = locate(c, kind, layer, false, &v);
+  if (s != PDADMM_OK) return s;
+  if (kind == PDADMM_VAR_RESID && c->dirty) {
+    if ((s = refresh_residual(c)) != PDADMM_OK) return s;
+  }
+  HIP_TRY(c, hipMemcpy2DAsync(dst, (size_t)v.cols * v.elem, v.ptr, (size_t)v.ld * v.elem, (size_t)v.cols * v.elem,
+                              v.rows, hipMemcpyDefault, c->stream));
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  return PDADMM_OK;
+}
+
+pdadmm_status pdadmm_step_phase(pdadmm_ctx* c, int32_t phase) {
+  if (!c) return PDADMM_EINVAL;
+  pdadmm_status s;
+  if (c->dirty && (s = refresh_residual(c)) != PDADMM_OK) return s;
+  switch (phase) {
+    case PDADMM_PHASE_P: return phase_p(c);
+    case PDADMM_PHASE_W: return phase_w(c);
+    case PDADMM_PHASE_BZQU: return phase_bzqu(c);
+    default: return fail(c, PDADMM_EINVAL, "unknown phase");
+  }
+}
+
+pdadmm_status pdadmm_iterate(pdadmm_ctx* c, int32_t n_iters) {
+  if (!c || n_iters < 0) return PDADMM_EINVAL;
+  pdadmm_status s;
+  for (int it = 0; it < n_iters; ++it) {
+    const bool periodic = c->cfg.refresh_every > 0 && c->iter > 0 && c->iter % c->cfg.refresh_every == 0;
+    if ((c->dirty || periodic) && (s = refresh_residual(c)) != PDADMM_OK) return s;
+    if ((s = phase_p(c)) != PDADMM_OK) return s;
+    if ((s = phase_w(c)) != PDADMM_OK) return s;
+    if ((s = phase_bzqu(c)) != PDADMM_OK) return s;
+    ++c->iter;
+  }
+  return PDADMM_OK;
+}
+
+pdadmm_status pdadmm_sync(pdadmm_ctx* c) {
+  if (!c) return PDADMM_EINVAL;
+  return check_device_flags(c);
+}
+
+static pdadmm_status sum_partials(pdadmm_ctx* c, const double* dev, size_t count, std::vector<double>* host) {
+  host->resize(count);
+  if (count == 0) return PDADMM_OK;
+  HIP_TRY(c, hipMemcpyAsync(host->data(), dev, count * sizeof(double), hipMemcpyDeviceToHost, c->stream));
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  return PDADMM_OK;
+}
+
+static pdadmm_status pair_sums(pdadmm_ctx* c, std::vector<double>* act, std::vector<double>* dl,
+                               std::vector<double>* dq) {
+  const int L = c->L;
+  act->assign(L, 0.0);
+  dl->assign(L, 0.0);
+  dq->assign(L, 0.0);
+  if (L < 2) return PDADMM_OK;
+  hipLaunchKernelGGL(pair_reduce_kernel, dim3(c->nb_pair), dim3(256), 0, c->stream, c->s_pair, L - 1);
+  LAUNCH_CHECK(c, "pair reduce");
+  std::vector<double> h;
+  for (int i = 0; i < L - 1; ++i) {
+    const LayerBufs& b = c->lay[i];
+    const int nblk = flat_blocks((size_t)c->N * b.ld_out / 4);
+    pdadmm_status s = sum_partials(c, b.pairpart, (size_t)nblk * 3, &h);
+    if (s != PDADMM_OK) return s;
+    for (int k = 0; k < nblk; ++k) {
+      (*act)[i] += h[3 * k];
+      (*dl)[i] += h[3 * k + 1];
+      (*dq)[i] += h[3 * k + 2];
+    }
+  }
+  return PDADMM_OK;
+}
+
+// fresh residuals into the T buffers; returns sum ||r||^2 and sum ||r - carried||^2
+static pdadmm_status fresh_residual_sums(pdadmm_ctx* c, double* lin, double* drift) {
+  pdadmm_status s;
+  if (c->dirty && (s = refresh_residual(c)) != PDADMM_OK) return s;
+  launch_gemm<true, EpiResid>(c, c->t_resid_obj, c->L, c->nb_resid, 0);
+  LAUNCH_CHECK(c, "gemm resid objective");
+  *lin = 0.0;
+  *drift = 0.0;
+  std::vector<double> h;
+  for (int i = 0; i < c->L; ++i) {
+    const LayerBufs& b = c->lay[i];
+    if ((s = sum_partials(c, b.part_b, (size_t)b.tiles_out * 2, &h)) != PDADMM_OK) return s;
+    for (int k = 0; k < b.tiles_out; ++k) {
+      *lin += h[2 * k];
+      *drift += h[2 * k + 1];
+    }
+  }
+  return PDADMM_OK;
+}
+
+pdadmm_status pdadmm_objective(pdadmm_ctx* c, pdadmm_objective_terms* out) {
+  if (!c || !out) return PDADMM_EINVAL;
+  pdadmm_status s;
+  double lin = 0, drift = 0;
+  if ((s = fresh_residual_sums(c, &lin, &drift)) != PDADMM_OK) return s;
+  std::vector<double> act, dl, dq, h;
+  if ((s = pair_sums(c, &act, &dl, &dq)) != PDADMM_OK) return s;
+  const LayerBufs& bl = c->lay[c->L - 1];
+  hipLaunchKernelGGL(risk_kernel, dim3(c->risk_blocks), dim3(256), 0, c->stream, bl.z, c->labels, c->mask, c->N,
+                     bl.n_out, bl.ld_out, c->riskpart);
+  LAUNCH_CHECK(c, "risk");
+  if ((s = sum_partials(c, c->riskpart, c->risk_blocks, &h)) != PDADMM_OK) return s;
+  double risk = 0;
+  for (double v : h) risk += v;
+  double sa = 0, sl = 0, sq = 0;
+  for (int i = 0; i < c->L; ++i) { sa += act[i]; sl += dl[i]; sq += dq[i]; }
+  out->risk = risk;
+  out->lin_pen = 0.5 * c->cfg.nu * lin;
+  out->act_pen = 0.5 * c->cfg.nu * sa;
+  out->dual_lin = sl;
+  out->dual_quad = 0.5 * c->cfg.rho * sq;
+  out->F = out->risk + out->lin_pen + out->act_pen;
+  out->L_rho = out->F + out->dual_lin + out->dual_quad;
+  return check_device_flags(c);
+}
+
+pdadmm_status pdadmm_residual(pdadmm_ctx* c, double* total, double* per_layer) {
+  if (!c || !total) return PDADMM_EINVAL;
+  std::vector<double> act, dl, dq;
+  pdadmm_status s = pair_sums(c, &act, &dl, &dq);
+  if (s != PDADMM_OK) return s;
+  double t = 0;
+  for (int i = 0; i < c->L - 1; ++i) {
+    t += dq[i];
+    if (per_layer) per_layer[i] = std::sqrt(dq[i]);
+  }
+  *total = std::sqrt(t);
+  return check_device_flags(c);
+}
+
+pdadmm_status pdadmm_stats(pdadmm_ctx* c, double* tau, double* theta, int32_t* p_trials, int32_t* w_trials,
+                           double* r_drift) {
+  if (!c) return PDADMM_EINVAL;
+  std::vector<LayerScal> hs(c->L);
+  HIP_TRY(c, hipMemcpyAsync(hs.data(), c->scal, sizeof(LayerScal) * c->L, hipMemcpyDeviceToHost, c->stream));
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  for (int i = 0; i < c->L; ++i) {
+    if (tau) tau[i] = hs[i].tau;
+    if (theta) theta[i] = hs[i].theta;
+    if (p_trials) p_trials[i] = hs[i].p_trials;
+    if (w_trials) w_trials[i] = hs[i].w_trials;
+  }
+  if (r_drift) {
+    double lin = 0, drift = 0;
+    pdadmm_status s = fresh_residual_sums(c, &lin, &drift);
+    if (s != PDADMM_OK) return s;
+    *r_drift = lin > 0 ? std::sqrt(drift / lin) : std::sqrt(drift);
+  }
+  return check_device_flags(c);
+}
+
+const char* pdadmm_last_error(const pdadmm_ctx* c) { return c ? c->msg.c_str() : "context is NULL"; }
+
+void pdadmm_destroy(pdadmm_ctx* c) {
+  if (!c) return;
+  if (c->stream || true) (void)hipStreamSynchronize(c->stream);
+  if (c->h_flags) (void)hipHostFree(c->h_flags);
+  delete c;
+}
+
+}  // extern "C"

@@ -1,0 +1,43 @@
+// CSR SpMM for the multi-hop feature augmentation X_k = A~ X_{k-1} (Sections 3.1, 5.1).
+// One thread owns VEC consecutive feature columns of one node and walks the node's CSR row in
+// order; neighbouring threads own neighbouring column groups, so every gathered row segment is
+// a coalesced read. Products and sums are rounded separately (no FMA): the result is fixed bit
+// for bit by the CSR order.
+#pragma once
+#include "common.h"
+
+namespace pdadmm {
+
+template <int VEC>
+__global__ __launch_bounds__(256) void spmm_hop_kernel(int n, const int* __restrict__ rowptr,
+                                                       const int* __restrict__ colidx,
+                                                       const float* __restrict__ vals,
+                                                       const float* __restrict__ src,  // block k-1, row stride ld
+                                                       float* __restrict__ dst,        // block k,   row stride ld
+                                                       int d, int ld) {
+  const int groups = (d + VEC - 1) / VEC;
+  const size_t item = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (item >= (size_t)n * groups) return;
+  const int row = (int)(item / groups);
+  const int c0 = (int)(item % groups) * VEC;
+  const int beg = rowptr[row], end = rowptr[row + 1];
+  if (VEC == 4) {
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int e = beg; e < end; ++e) {
+      const float a = vals[e];
+      const float4 x = *reinterpret_cast<const float4*>(src + (size_t)colidx[e] * ld + c0);
+      acc.x = __fadd_rn(acc.x, __fmul_rn(a, x.x));
+      acc.y = __fadd_rn(acc.y, __fmul_rn(a, x.y));
+      acc.z = __fadd_rn(acc.z, __fmul_rn(a, x.z));
+      acc.w = __fadd_rn(acc.w, __fmul_rn(a, x.w));
+    }
+    *reinterpret_cast<float4*>(dst + (size_t)row * ld + c0) = acc;
+  } else {
+    float acc = 0.f;
+    for (int e = beg; e < end; ++e)
+      acc = __fadd_rn(acc, __fmul_rn(vals[e], src[(size_t)colidx[e] * ld + c0]));
+    dst[(size_t)row * ld + c0] = acc;
+  }
+}
+
+}  // namespace pdadmm
