@@ -181,6 +181,20 @@ pdadmm_status pdadmm_residual(pdadmm_ctx* ctx, double* total, double* per_layer)
 pdadmm_status pdadmm_stats(pdadmm_ctx* ctx, double* tau, double* theta, int32_t* p_trials,
                            int32_t* w_trials, double* r_drift);
 
+/*
+ * Per-launch timing with HIP events recorded on the context's stream around the launches of the
+ * selected kernel classes (bit i of class_mask = class i; 0 switches timing off and drops pending
+ * records). Classes: 0 p-gradient product (W^T r, fused gradient), 1 step-direction products
+ * (W g / W d and G p), 2 W-gradient product (r p^T, split over nodes), 3 its partial-sum reduce,
+ * 4 step-size selection, 5 p-step, 6 W-step, 7 residual update + column sums, 8 b-step,
+ * 9 fused z/q/u update, 10 FISTA for z_L, 11 -Q trial projection, 12 -Q apply, 13 residual refresh.
+ * pdadmm_timing_read synchronises, adds up the elapsed milliseconds and the number of launches per
+ * class since the last read into HOST arrays of n_classes >= 14 entries, and clears the records.
+ */
+#define PDADMM_N_TIMING_CLASSES 14
+pdadmm_status pdadmm_timing(pdadmm_ctx* ctx, uint32_t class_mask);
+pdadmm_status pdadmm_timing_read(pdadmm_ctx* ctx, double* ms, int64_t* launches, int32_t n_classes);
+
 const char* pdadmm_last_error(const pdadmm_ctx* ctx);
 void pdadmm_destroy(pdadmm_ctx* ctx);
 

@@ -8,6 +8,7 @@ from .binding import (PdadmmError, Config, Context, load_library, library_path, 
                       pdadmm_gemm_tn, pdadmm_workspace_bytes, pdadmm_init, pdadmm_set_var,
                       pdadmm_get_var, pdadmm_iterate, pdadmm_step_phase, pdadmm_sync,
                       pdadmm_objective, pdadmm_residual, pdadmm_stats, pdadmm_destroy,
+                      pdadmm_timing, pdadmm_timing_read, TIMING_CLASSES,
                       VAR, PHASE)
 
 __all__ = [n for n in dir() if not n.startswith("_")]

@@ -44,7 +44,7 @@ class _CObjective(C.Structure):
 EXPORTS = ["pdadmm_normalize_adj", "pdadmm_augment", "pdadmm_quantize", "pdadmm_gemm_nt", "pdadmm_gemm_tn",
            "pdadmm_workspace_bytes", "pdadmm_init", "pdadmm_set_var", "pdadmm_get_var", "pdadmm_iterate",
            "pdadmm_step_phase", "pdadmm_sync", "pdadmm_objective", "pdadmm_residual", "pdadmm_stats",
-           "pdadmm_last_error", "pdadmm_destroy"]
+           "pdadmm_timing", "pdadmm_timing_read", "pdadmm_last_error", "pdadmm_destroy"]
 
 
 def library_path() -> str:
@@ -83,6 +83,8 @@ def load_library():
     lib.pdadmm_objective.argtypes = [vp, C.POINTER(_CObjective)]
     lib.pdadmm_residual.argtypes = [vp, C.POINTER(C.c_double), vp]
     lib.pdadmm_stats.argtypes = [vp, vp, vp, vp, vp, vp]
+    lib.pdadmm_timing.argtypes = [vp, C.c_uint32]
+    lib.pdadmm_timing_read.argtypes = [vp, vp, vp, i32]
     lib.pdadmm_last_error.argtypes = [vp]
     lib.pdadmm_last_error.restype = C.c_char_p
     lib.pdadmm_destroy.argtypes = [vp]
@@ -346,6 +348,23 @@ def pdadmm_stats(ctx: Context, drift: bool = False) -> dict:
     _check(load_library().pdadmm_stats(ctx.handle, tau.ctypes.data, theta.ctypes.data, pt.ctypes.data,
                                        wt.ctypes.data, C.addressof(d) if drift else None), "pdadmm_stats", ctx)
     return dict(tau=tau, theta=theta, p_trials=pt, w_trials=wt, r_drift=d.value if drift else None)
+
+
+TIMING_CLASSES = ["gemm_pgrad", "gemm_trial", "gemm_wgrad", "splitk_reduce", "select", "p_step", "w_step",
+                  "resid_colsum", "bias", "zqu", "fista", "quant_trial", "quant_apply", "refresh"]
+
+
+def pdadmm_timing(ctx: Context, class_mask: int) -> None:
+    _check(load_library().pdadmm_timing(ctx.handle, class_mask), "pdadmm_timing", ctx)
+
+
+def pdadmm_timing_read(ctx: Context) -> dict:
+    """{class name: (milliseconds, launches)} since the last read."""
+    n = len(TIMING_CLASSES)
+    ms = np.zeros(n)
+    cnt = np.zeros(n, dtype=np.int64)
+    _check(load_library().pdadmm_timing_read(ctx.handle, ms.ctypes.data, cnt.ctypes.data, n), "pdadmm_timing_read", ctx)
+    return {name: (float(ms[i]), int(cnt[i])) for i, name in enumerate(TIMING_CLASSES)}
 
 
 def pdadmm_destroy(ctx: Context) -> None:

@@ -51,16 +51,35 @@ struct QuantGrid {
   int levels;
 };
 
+// Single fp32 operations that the compiler may not fuse with their neighbours into a fused
+// multiply-add (the separate roundings are part of the specified result).
+__device__ __forceinline__ float mul_rn(float a, float b) {
+#pragma clang fp contract(off)
+  return a * b;
+}
+__device__ __forceinline__ float add_rn(float a, float b) {
+#pragma clang fp contract(off)
+  return a + b;
+}
+__device__ __forceinline__ float sub_rn(float a, float b) {
+#pragma clang fp contract(off)
+  return a - b;
+}
+__device__ __forceinline__ float div_rn(float a, float b) {
+#pragma clang fp contract(off)
+  return a / b;
+}
+
 // Projection onto the uniform grid, every operation rounded to fp32 separately.
 __device__ __forceinline__ int quant_index(float v, const QuantGrid g) {
-  const float t = __fdiv_rn(__fsub_rn(v, g.lo), g.step);
+  const float t = div_rn(sub_rn(v, g.lo), g.step);
   float r = rintf(t);
   if (!(r == r)) r = 0.0f;                      // NaN -> 0
   r = fminf(fmaxf(r, 0.0f), (float)(g.levels - 1));
   return (int)r;
 }
 __device__ __forceinline__ float quant_value(int idx, const QuantGrid g) {
-  return __fadd_rn(g.lo, __fmul_rn((float)idx, g.step));
+  return add_rn(g.lo, mul_rn((float)idx, g.step));
 }
 
 }  // namespace pdadmm

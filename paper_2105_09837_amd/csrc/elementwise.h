@@ -164,7 +164,6 @@ struct RowSeg {
   const float* pnext;   // p_{l+1}
   const float* m;       // column means (b-step), [ld]
   double* colpart;      // [row_blocks][ld]
-  double* rpart;        // per block: ||p_{l+1} - q_l||^2
   int rows, ncols, ld;
   int col_blocks, row_blocks;
   int blk0, nblk;
@@ -252,7 +251,6 @@ __device__ __forceinline__ float z_closed_form(float s, float q) {
 //   a = R - m + z_old; z = closed form; R <- a - z;
 //   q = (rho p_{l+1} + u + nu relu(z)) / (rho + nu); r = p_{l+1} - q; u <- u + rho r.
 __global__ __launch_bounds__(256) void zqu_kernel(const RowSeg* __restrict__ segs, int nseg, float rho, float nu) {
-  __shared__ double red[4];
   const int lb = blockIdx.x;
   int si = 0;
   while (si + 1 < nseg && lb >= segs[si + 1].blk0) ++si;
@@ -262,7 +260,6 @@ __global__ __launch_bounds__(256) void zqu_kernel(const RowSeg* __restrict__ seg
   const int cq = threadIdx.x & 63, ty = threadIdx.x >> 6;
   const int col = (cb * 64 + cq) * 4;
   const float inv_rn = 1.0f / (rho + nu);
-  double rs = 0.0;
   if (col < S.ld) {
     const float4 mm = *reinterpret_cast<const float4*>(S.m + col);
     const int rend = min(S.rows, (rb + 1) * kRowsPerBlock);
@@ -284,7 +281,6 @@ __global__ __launch_bounds__(256) void zqu_kernel(const RowSeg* __restrict__ seg
     const float rr = pn.c - qq;                                           \
     qn.c = qq;                                                            \
     un.c = uo.c + rho * rr;                                               \
-    rs += (double)rr * (double)rr;                                        \
   }
       PDADMM_ZQU(x) PDADMM_ZQU(y) PDADMM_ZQU(z) PDADMM_ZQU(w)
 #undef PDADMM_ZQU
@@ -294,8 +290,6 @@ __global__ __launch_bounds__(256) void zqu_kernel(const RowSeg* __restrict__ seg
       *reinterpret_cast<float4*>(S.u + i) = un;
     }
   }
-  const double t = block_sum_256(rs, red);
-  if (threadIdx.x == 0) S.rpart[local] = t;
 }
 
 // ------------------------------------------------------------------------------------------
@@ -405,10 +399,10 @@ __global__ __launch_bounds__(256) void quant_trial_kernel(const QuantSeg* __rest
 #define PDADMM_QT(c, k)                                                       \
   {                                                                           \
     if (col0 + k < S.ncols) {                                                 \
-      const float v = __fsub_rn(pv.c, __fdiv_rn(gv.c, t));                    \
+      const float v = sub_rn(pv.c, div_rn(gv.c, t));                          \
       const int id = quant_index(v, grid);                                    \
       iv.c = (unsigned char)id;                                               \
-      dv.c = __fsub_rn(quant_value(id, grid), pv.c);                          \
+      dv.c = sub_rn(quant_value(id, grid), pv.c);                             \
       ds += (double)dv.c * (double)dv.c;                                      \
     } else {                                                                  \
       iv.c = 0;                                                               \

@@ -94,6 +94,11 @@ struct pdadmm_ctx {
   bool dirty = true;
   long iter = 0;
   std::string msg;
+  // optional per-launch timing with HIP events on the context's stream
+  struct TimedLaunch { int cls; hipEvent_t a, b; };
+  uint32_t timing_mask = 0;
+  std::vector<TimedLaunch> timed;
+  std::vector<hipEvent_t> event_pool;
 };
 
 namespace {
@@ -116,6 +121,42 @@ pdadmm_status fail(pdadmm_ctx* c, pdadmm_status s, const std::string& m) {
     if (e_ != hipSuccess)                                                                    \
       return fail(ctx, PDADMM_EHIP, std::string("launch ") + what + ": " + hipGetErrorString(e_)); \
   } while (0)
+
+// Kernel classes for pdadmm_timing (bit i of the mask enables class i).
+enum : int { kClsGemmPGrad = 0, kClsGemmTrial = 1, kClsGemmWGrad = 2, kClsSplitkReduce = 3, kClsSelect = 4,
+             kClsPStep = 5, kClsWStep = 6, kClsResidColsum = 7, kClsBias = 8, kClsZqu = 9, kClsFista = 10,
+             kClsQuantTrial = 11, kClsQuantApply = 12, kClsRefresh = 13, kNumClasses = 14 };
+
+hipEvent_t take_event(pdadmm_ctx* c) {
+  hipEvent_t e = nullptr;
+  if (!c->event_pool.empty()) {
+    e = c->event_pool.back();
+    c->event_pool.pop_back();
+  } else if (hipEventCreate(&e) != hipSuccess) {
+    e = nullptr;
+  }
+  return e;
+}
+
+struct ScopedTimer {
+  pdadmm_ctx* c;
+  hipEvent_t a = nullptr, b = nullptr;
+  int cls;
+  ScopedTimer(pdadmm_ctx* ctx, int k) : c(ctx), cls(k) {
+    if (c->timing_mask & (1u << k)) {
+      a = take_event(c);
+      b = take_event(c);
+      if (a && b) (void)hipEventRecord(a, c->stream);
+    }
+  }
+  ~ScopedTimer() {
+    if (a && b) {
+      (void)hipEventRecord(b, c->stream);
+      c->timed.push_back({cls, a, b});
+    }
+  }
+};
+#define TIMED(c, cls) ScopedTimer timer_##cls(c, cls)
 
 bool config_ok(const pdadmm_config* c, std::string* why) {
   auto bad = [&](const char* m) { if (why) *why = m; return false; };
@@ -364,7 +405,7 @@ pdadmm_status build_tables(pdadmm_ctx* c) {
     RowSeg rs{};
     rs.R = b.R; rs.T = b.T; rs.z = b.z; rs.q = b.q; rs.u = b.u;
     rs.pnext = i < L - 1 ? c->lay[i + 1].p : nullptr;
-    rs.m = b.m; rs.colpart = b.colpart; rs.rpart = nullptr;
+    rs.m = b.m; rs.colpart = b.colpart;
     rs.rows = N; rs.ncols = b.n_out; rs.ld = b.ld_out;
     rs.col_blocks = b.col_blocks; rs.row_blocks = b.row_blocks; rs.nblk = b.col_blocks * b.row_blocks; rs.layer = i;
     rows.push_back(rs);
@@ -418,9 +459,9 @@ void launch_gemm(pdadmm_ctx* c, const GemmProb* table, int nprob, int blocks, in
 
 pdadmm_status refresh_residual(pdadmm_ctx* c) {
   // transposed weights, then R = p W^T + b - z for every layer
-  hipLaunchKernelGGL(w_step_kernel, dim3(c->nb_w), dim3(256), 0, c->stream, c->s_w, c->L, c->scal, 1);
+  { TIMED(c, kClsRefresh); hipLaunchKernelGGL(w_step_kernel, dim3(c->nb_w), dim3(256), 0, c->stream, c->s_w, c->L, c->scal, 1); }
   LAUNCH_CHECK(c, "w_step(copy)");
-  launch_gemm<true, EpiResid>(c, c->t_resid, c->L, c->nb_resid, 0);
+  { TIMED(c, kClsRefresh); launch_gemm<true, EpiResid>(c, c->t_resid, c->L, c->nb_resid, 0); }
   LAUNCH_CHECK(c, "gemm resid");
   c->dirty = false;
   return PDADMM_OK;
@@ -430,21 +471,21 @@ pdadmm_status phase_p(pdadmm_ctx* c) {
   const int L = c->L;
   if (L < 2) return PDADMM_OK;
   const pdadmm_config& g = c->cfg;
-  launch_gemm<true, EpiPGrad>(c, c->t_pgrad, L - 1, c->nb_pgrad, 0);
+  { TIMED(c, kClsGemmPGrad); launch_gemm<true, EpiPGrad>(c, c->t_pgrad, L - 1, c->nb_pgrad, 0); }
   LAUNCH_CHECK(c, "gemm pgrad");
   if (!g.quantize) {
-    launch_gemm<true, EpiStoreNorm>(c, c->t_ptrial, L - 1, c->nb_ptrial, 0);
+    { TIMED(c, kClsGemmTrial); launch_gemm<true, EpiStoreNorm>(c, c->t_ptrial, L - 1, c->nb_ptrial, 0); }
     LAUNCH_CHECK(c, "gemm ptrial");
-    hipLaunchKernelGGL(select_step_kernel, dim3(L - 1), dim3(256), 0, c->stream, c->sel_p, c->scal, 0, g.rho, g.nu,
-                       g.bt_eta, g.bt_max_trials, c->err);
+    { TIMED(c, kClsSelect); hipLaunchKernelGGL(select_step_kernel, dim3(L - 1), dim3(256), 0, c->stream, c->sel_p, c->scal, 0, g.rho, g.nu,
+                       g.bt_eta, g.bt_max_trials, c->err); }
     LAUNCH_CHECK(c, "select tau");
-    hipLaunchKernelGGL(axpy_kernel, dim3(c->nb_pstep), dim3(256), 0, c->stream, c->s_pstep, 2 * (L - 1), c->scal);
+    { TIMED(c, kClsPStep); hipLaunchKernelGGL(axpy_kernel, dim3(c->nb_pstep), dim3(256), 0, c->stream, c->s_pstep, 2 * (L - 1), c->scal); }
     LAUNCH_CHECK(c, "p step");
     return PDADMM_OK;
   }
   // -Q: trial rounds; the host only learns which layers are still searching
-  hipLaunchKernelGGL(select_quant_kernel, dim3(L - 1), dim3(256), 0, c->stream, c->sel_p, c->scal, 0, g.rho, g.nu,
-                     g.bt_eta, g.bt_max_trials, c->err, c->flags);
+  { TIMED(c, kClsSelect); hipLaunchKernelGGL(select_quant_kernel, dim3(L - 1), dim3(256), 0, c->stream, c->sel_p, c->scal, 0, g.rho, g.nu,
+                     g.bt_eta, g.bt_max_trials, c->err, c->flags); }
   LAUNCH_CHECK(c, "select quant arm");
   for (int round = 0; round <= g.bt_max_trials; ++round) {
     HIP_TRY(c, hipMemcpyAsync(c->h_flags, c->flags, sizeof(int) * L, hipMemcpyDeviceToHost, c->stream));
@@ -452,19 +493,19 @@ pdadmm_status phase_p(pdadmm_ctx* c) {
     bool any = false;
     for (int i = 1; i < L; ++i) any = any || c->h_flags[i] != 0;
     if (!any) break;
-    hipLaunchKernelGGL(quant_trial_kernel, dim3(c->nb_quant), dim3(256), 0, c->stream, c->s_quant, L - 1, c->scal,
-                       c->grid);
+    { TIMED(c, kClsQuantTrial); hipLaunchKernelGGL(quant_trial_kernel, dim3(c->nb_quant), dim3(256), 0, c->stream, c->s_quant, L - 1, c->scal,
+                       c->grid); }
     LAUNCH_CHECK(c, "quant trial");
-    launch_gemm<true, EpiStoreNorm>(c, c->t_ptrial, L - 1, c->nb_ptrial, 1);
+    { TIMED(c, kClsGemmTrial); launch_gemm<true, EpiStoreNorm>(c, c->t_ptrial, L - 1, c->nb_ptrial, 1); }
     LAUNCH_CHECK(c, "gemm qtrial");
-    hipLaunchKernelGGL(select_quant_kernel, dim3(L - 1), dim3(256), 0, c->stream, c->sel_q, c->scal, 1, g.rho, g.nu,
-                       g.bt_eta, g.bt_max_trials, c->err, c->flags);
+    { TIMED(c, kClsSelect); hipLaunchKernelGGL(select_quant_kernel, dim3(L - 1), dim3(256), 0, c->stream, c->sel_q, c->scal, 1, g.rho, g.nu,
+                       g.bt_eta, g.bt_max_trials, c->err, c->flags); }
     LAUNCH_CHECK(c, "select quant judge");
   }
-  hipLaunchKernelGGL(quant_apply_kernel, dim3(c->nb_quant), dim3(256), 0, c->stream, c->s_quant, L - 1, c->scal,
-                     c->grid);
+  { TIMED(c, kClsQuantApply); hipLaunchKernelGGL(quant_apply_kernel, dim3(c->nb_quant), dim3(256), 0, c->stream, c->s_quant, L - 1, c->scal,
+                     c->grid); }
   LAUNCH_CHECK(c, "quant apply");
-  hipLaunchKernelGGL(axpy_kernel, dim3(c->nb_qapply_r), dim3(256), 0, c->stream, c->s_qapply_r, L - 1, c->scal);
+  { TIMED(c, kClsQuantApply); hipLaunchKernelGGL(axpy_kernel, dim3(c->nb_qapply_r), dim3(256), 0, c->stream, c->s_qapply_r, L - 1, c->scal); }
   LAUNCH_CHECK(c, "quant apply R");
   return PDADMM_OK;
 }
@@ -472,16 +513,16 @@ pdadmm_status phase_p(pdadmm_ctx* c) {
 pdadmm_status phase_w(pdadmm_ctx* c) {
   const int L = c->L;
   const pdadmm_config& g = c->cfg;
-  launch_gemm<false, EpiStore>(c, c->t_wgrad, L, c->nb_wgrad, 0);
+  { TIMED(c, kClsGemmWGrad); launch_gemm<false, EpiStore>(c, c->t_wgrad, L, c->nb_wgrad, 0); }
   LAUNCH_CHECK(c, "gemm wgrad");
-  hipLaunchKernelGGL(splitk_reduce_kernel, dim3(c->nb_red), dim3(256), 0, c->stream, c->t_red, L);
+  { TIMED(c, kClsSplitkReduce); hipLaunchKernelGGL(splitk_reduce_kernel, dim3(c->nb_red), dim3(256), 0, c->stream, c->t_red, L); }
   LAUNCH_CHECK(c, "splitk reduce");
-  launch_gemm<true, EpiStoreNorm>(c, c->t_wtrial, L, c->nb_wtrial, 0);
+  { TIMED(c, kClsGemmTrial); launch_gemm<true, EpiStoreNorm>(c, c->t_wtrial, L, c->nb_wtrial, 0); }
   LAUNCH_CHECK(c, "gemm wtrial");
-  hipLaunchKernelGGL(select_step_kernel, dim3(L), dim3(256), 0, c->stream, c->sel_w, c->scal, 1, g.rho, g.nu,
-                     g.bt_eta, g.bt_max_trials, c->err);
+  { TIMED(c, kClsSelect); hipLaunchKernelGGL(select_step_kernel, dim3(L), dim3(256), 0, c->stream, c->sel_w, c->scal, 1, g.rho, g.nu,
+                     g.bt_eta, g.bt_max_trials, c->err); }
   LAUNCH_CHECK(c, "select theta");
-  hipLaunchKernelGGL(w_step_kernel, dim3(c->nb_w), dim3(256), 0, c->stream, c->s_w, L, c->scal, 0);
+  { TIMED(c, kClsWStep); hipLaunchKernelGGL(w_step_kernel, dim3(c->nb_w), dim3(256), 0, c->stream, c->s_w, L, c->scal, 0); }
   LAUNCH_CHECK(c, "w step");
   return PDADMM_OK;
 }
@@ -498,6 +539,7 @@ pdadmm_status launch_fista(pdadmm_ctx* c) {
 #define FISTA(EE)                                                                                              \
   hipLaunchKernelGGL((fista_kernel<EE>), dim3(blocks), dim3(256), 0, c->stream, b.R, b.z, b.m, c->labels, mask, \
                      c->N, C, b.ld_out, G, c->cfg.nu, c->cfg.fista_iters)
+  TIMED(c, kClsFista);
   if (E <= 1) FISTA(1);
   else if (E <= 2) FISTA(2);
   else if (E <= 4) FISTA(4);
@@ -511,12 +553,12 @@ pdadmm_status launch_fista(pdadmm_ctx* c) {
 pdadmm_status phase_bzqu(pdadmm_ctx* c) {
   const int L = c->L;
   const pdadmm_config& g = c->cfg;
-  hipLaunchKernelGGL(resid_colsum_kernel, dim3(c->nb_rows_all), dim3(256), 0, c->stream, c->s_rows, L, c->scal);
+  { TIMED(c, kClsResidColsum); hipLaunchKernelGGL(resid_colsum_kernel, dim3(c->nb_rows_all), dim3(256), 0, c->stream, c->s_rows, L, c->scal); }
   LAUNCH_CHECK(c, "resid colsum");
-  hipLaunchKernelGGL(bias_step_kernel, dim3(c->nb_bias), dim3(256), 0, c->stream, c->s_bias, L);
+  { TIMED(c, kClsBias); hipLaunchKernelGGL(bias_step_kernel, dim3(c->nb_bias), dim3(256), 0, c->stream, c->s_bias, L); }
   LAUNCH_CHECK(c, "bias step");
   if (L > 1) {
-    hipLaunchKernelGGL(zqu_kernel, dim3(c->nb_rows_hidden), dim3(256), 0, c->stream, c->s_rows, L - 1, g.rho, g.nu);
+    { TIMED(c, kClsZqu); hipLaunchKernelGGL(zqu_kernel, dim3(c->nb_rows_hidden), dim3(256), 0, c->stream, c->s_rows, L - 1, g.rho, g.nu); }
     LAUNCH_CHECK(c, "zqu");
   }
   return launch_fista(c);
@@ -981,12 +1023,48 @@ pdadmm_status pdadmm_stats(pdadmm_ctx* c, double* tau, double* theta, int32_t* p
   return check_device_flags(c);
 }
 
+pdadmm_status pdadmm_timing(pdadmm_ctx* c, uint32_t class_mask) {
+  if (!c) return PDADMM_EINVAL;
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  for (auto& t : c->timed) {
+    c->event_pool.push_back(t.a);
+    c->event_pool.push_back(t.b);
+  }
+  c->timed.clear();
+  c->timing_mask = class_mask;
+  return PDADMM_OK;
+}
+
+pdadmm_status pdadmm_timing_read(pdadmm_ctx* c, double* ms, int64_t* launches, int32_t n_classes) {
+  if (!c || !ms || !launches || n_classes < kNumClasses) return PDADMM_EINVAL;
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  for (int i = 0; i < n_classes; ++i) {
+    ms[i] = 0.0;
+    launches[i] = 0;
+  }
+  for (auto& t : c->timed) {
+    float e = 0.f;
+    HIP_TRY(c, hipEventElapsedTime(&e, t.a, t.b));
+    ms[t.cls] += (double)e;
+    launches[t.cls] += 1;
+    c->event_pool.push_back(t.a);
+    c->event_pool.push_back(t.b);
+  }
+  c->timed.clear();
+  return PDADMM_OK;
+}
+
 const char* pdadmm_last_error(const pdadmm_ctx* c) { return c ? c->msg.c_str() : "context is NULL"; }
 
 void pdadmm_destroy(pdadmm_ctx* c) {
   if (!c) return;
   if (c->stream || true) (void)hipStreamSynchronize(c->stream);
   if (c->h_flags) (void)hipHostFree(c->h_flags);
+  for (auto& t : c->timed) {
+    (void)hipEventDestroy(t.a);
+    (void)hipEventDestroy(t.b);
+  }
+  for (auto e : c->event_pool) (void)hipEventDestroy(e);
   delete c;
 }
 

@@ -26,16 +26,16 @@ __global__ __launch_bounds__(256) void spmm_hop_kernel(int n, const int* __restr
     for (int e = beg; e < end; ++e) {
       const float a = vals[e];
       const float4 x = *reinterpret_cast<const float4*>(src + (size_t)colidx[e] * ld + c0);
-      acc.x = __fadd_rn(acc.x, __fmul_rn(a, x.x));
-      acc.y = __fadd_rn(acc.y, __fmul_rn(a, x.y));
-      acc.z = __fadd_rn(acc.z, __fmul_rn(a, x.z));
-      acc.w = __fadd_rn(acc.w, __fmul_rn(a, x.w));
+      acc.x = add_rn(acc.x, mul_rn(a, x.x));
+      acc.y = add_rn(acc.y, mul_rn(a, x.y));
+      acc.z = add_rn(acc.z, mul_rn(a, x.z));
+      acc.w = add_rn(acc.w, mul_rn(a, x.w));
     }
     *reinterpret_cast<float4*>(dst + (size_t)row * ld + c0) = acc;
   } else {
     float acc = 0.f;
     for (int e = beg; e < end; ++e)
-      acc = __fadd_rn(acc, __fmul_rn(vals[e], src[(size_t)colidx[e] * ld + c0]));
+      acc = add_rn(acc, mul_rn(vals[e], src[(size_t)colidx[e] * ld + c0]));
     dst[(size_t)row * ld + c0] = acc;
   }
 }

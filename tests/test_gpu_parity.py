@@ -222,9 +222,19 @@ def test_one_iteration_phase_by_phase(env, case):
     np.testing.assert_allclose(rg[1], ro[1], rtol=TOL_TRAJ)
 
 
+def _same_step_sizes(H, ctx, st):
+    tau, theta, _, _ = H.step_sizes(ctx)
+    return all(tau[i] == st.tau[i] for i in range(1, st.L)) and all(theta[i] == st.theta[i] for i in range(st.L))
+
+
 @pytest.mark.parametrize("case,iters", [("C1-full", 10), ("C2-small", 20), ("C3-small", 20), ("C4-small", 20),
                                         ("C5-small", 20)])
 def test_trajectories(env, case, iters):
+    """Free-running trajectories of objective and residual. pdADMM-G: within 1e-3 at every iteration and
+    identical step-size decisions. pdADMM-G-Q: rounding noise flips single quantisation indices, the
+    flips multiply from iteration to iteration (the projection is discontinuous) and can eventually flip a
+    backtracking decision, after which the two runs are two different valid trajectories; the 1e-3 bound
+    is therefore required up to the first differing step-size decision, which must not come early."""
     torch, P, H = env
     w = CASES[case]()
     _say(f"trajectory {case} x{iters}")
@@ -232,6 +242,7 @@ def test_trajectories(env, case, iters):
     st = H.round_state_to_fp32(oracle_state(w, inp))
     ctx = H.gpu_context(w, inp, st)
     worst_obj = worst_res = 0.0
+    first_flip = None
     for k in range(iters):
         O.iterate(st)
         P.pdadmm_iterate(ctx, 1)
@@ -240,14 +251,58 @@ def test_trajectories(env, case, iters):
         eo = abs(og["L_rho"] - oo["L_rho"]) / abs(oo["L_rho"])
         ef = abs(og["F"] - oo["F"]) / abs(oo["F"])
         er = abs(rg - ro) / ro
-        worst_obj, worst_res = max(worst_obj, eo, ef), max(worst_res, er)
         _say(f"  it {k + 1}: L_rho {og['L_rho']:.6e} / {oo['L_rho']:.6e}  res {rg:.6e} / {ro:.6e}")
         if w.quant is None:
             _check_step_sizes(H, ctx, st)
-        assert eo <= TOL_TRAJ and ef <= TOL_TRAJ and er <= TOL_TRAJ, (k, eo, ef, er)
+        elif first_flip is None and not _same_step_sizes(H, ctx, st):
+            first_flip = k + 1
+            _say(f"  step-size decisions differ from iteration {first_flip} on")
+        if first_flip is None:
+            worst_obj, worst_res = max(worst_obj, eo, ef), max(worst_res, er)
+            assert eo <= TOL_TRAJ and ef <= TOL_TRAJ and er <= TOL_TRAJ, (k, eo, ef, er)
+        else:
+            assert eo <= 0.25 and np.isfinite(rg), (k, eo, er)   # two valid paths of the same problem
+    assert first_flip is None or first_flip > iters // 2
     s = P.pdadmm_stats(ctx, drift=True)
     _say(f"  worst obj err {worst_obj:.2e}, worst residual err {worst_res:.2e}, carried-residual drift {s['r_drift']:.2e}")
     assert s["r_drift"] < 1e-4
+
+
+def test_quantized_trajectory_every_step_is_an_oracle_step(env):
+    """pdADMM-G-Q over 20 iterations with the oracle shadowing the GPU: before each GPU iteration its state
+    is copied into the oracle, both take one iteration, and the results must agree (indices up to
+    isolated one-level flips at midpoints, step sizes exactly, objective and residual within 1e-3).
+    This shows that every step of the GPU's own trajectory is a valid step of the method."""
+    torch, P, H = env
+    w = CASES["C5-small"]()
+    inp = oracle_inputs(w)
+    st0 = H.round_state_to_fp32(oracle_state(w, inp))
+    ctx = H.gpu_context(w, inp, st0)
+    total_bad = 0
+    for k in range(20):
+        st = H.pull_state(ctx, st0)
+        O.iterate(st)
+        P.pdadmm_iterate(ctx, 1)
+        P.pdadmm_sync(ctx)
+        bad, total = _quant_index_report(P, ctx, st)
+        total_bad += bad
+        assert bad <= max(3, 3e-5 * total), (k, bad, total)
+        _check_step_sizes(H, ctx, st)
+        ok, worst, rep = H.compare_state(ctx, st, 2e-3, what=f"shadow it {k + 1}")
+        assert ok, rep
+        og, oo = P.pdadmm_objective(ctx), O.objective(st)
+        rg, ro = P.pdadmm_residual(ctx)[0], O.residual(st)[0]
+        assert abs(og["L_rho"] - oo["L_rho"]) <= TOL_TRAJ * abs(oo["L_rho"])
+        assert abs(og["F"] - oo["F"]) <= TOL_TRAJ * abs(oo["F"])
+        assert abs(rg - ro) <= TOL_TRAJ * ro
+        # Lemma (q optimality): u = nu (q - f(z)) after every iteration, on the GPU's own state
+        for l in range(1, st.L):
+            u = P.pdadmm_get_var(ctx, P.VAR.U, l).astype(F64)
+            q = P.pdadmm_get_var(ctx, P.VAR.Q, l).astype(F64)
+            z = P.pdadmm_get_var(ctx, P.VAR.Z, l).astype(F64)
+            ref = w.nu * (q - np.maximum(z, 0))
+            assert np.max(np.abs(u - ref)) <= 1e-5 * w.nu * max(1.0, np.max(np.abs(q)))
+    _say(f"  shadowed -Q run: {total_bad} one-level index differences in 20 iterations")
 
 
 def test_iterate_is_bit_reproducible(env):
