@@ -5,15 +5,30 @@
 
 namespace pdadmm {
 
+#define PD_GLOBAL __attribute__((address_space(1)))
+
+// Pointers that are known to address global memory (pointers read from descriptor tables are
+// generic to the compiler, which would otherwise emit flat loads that also tie up the LDS counter).
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef const float PD_GLOBAL* gcf;
+typedef const f32x4 PD_GLOBAL* gcf4;
+
 constexpr int kWave = 64;
 constexpr int kXcd = 8;   // MI355X: 8 accelerator dies, workgroups are dealt to them round-robin
 
-// Map the hardware block id to a logical block id so that logically consecutive blocks run on
-// the same die (and share its L2): die x gets the contiguous logical range [start_x, start_x+cnt_x).
-__device__ __forceinline__ int xcd_remap(int bid, int total) {
-  const int q = total / kXcd, r = total % kXcd;
-  const int x = bid % kXcd, slot = bid / kXcd;
-  return x * q + (x < r ? x : r) + slot;
+// Map the hardware block id to a logical block id. Workgroups are dealt to the 8 dies round-robin
+// in block-id order, so block b runs on die b % 8 as the (b / 8)-th block of that die. Logical
+// blocks are cut into panels of `panel` consecutive ids (tiles that share an operand row panel);
+// a die takes whole panels, the dies take panels round-robin: neighbours in the logical order
+// share a die's L2, and problems of different cost per tile are spread evenly over the dies.
+// The launch is padded to a multiple of 8*panel blocks; ids >= total must exit.
+__device__ __forceinline__ int xcd_remap(int bid, int panel) {
+  const int x = bid % kXcd, j = bid / kXcd;
+  return ((j / panel) * kXcd + x) * panel + (j % panel);
+}
+__host__ __device__ inline int xcd_padded(int total, int panel) {
+  const int g = kXcd * panel;
+  return (total + g - 1) / g * g;
 }
 
 __device__ __forceinline__ double wave_sum(double v) {

@@ -210,7 +210,9 @@ __global__ __launch_bounds__(256) void resid_colsum_kernel(const RowSeg* __restr
   }
 }
 
-// b <- b - mean; m <- mean. One thread per column.
+// b <- b - mean; m <- mean. A block owns 32 columns; its 8 row groups add up a strided share of the
+// per-row-block partial sums each (coalesced 256-byte reads), then the groups are combined in a
+// fixed order.
 struct BiasSeg {
   float* b;
   float* m;
@@ -220,17 +222,26 @@ struct BiasSeg {
 };
 
 __global__ __launch_bounds__(256) void bias_step_kernel(const BiasSeg* __restrict__ segs, int nseg) {
+  __shared__ double sm[8][32];
   const int lb = blockIdx.x;
   int si = 0;
   while (si + 1 < nseg && lb >= segs[si + 1].blk0) ++si;
   const BiasSeg S = segs[si];
-  const int c = (lb - S.blk0) * 256 + threadIdx.x;
-  if (c >= S.ld) return;
+  const int cx = threadIdx.x & 31, g = threadIdx.x >> 5;
+  const int c = (lb - S.blk0) * 32 + cx;
   double s = 0.0;
-  for (int rb = 0; rb < S.row_blocks; ++rb) s += S.colpart[(size_t)rb * S.ld + c];
-  const float mean = c < S.ncols ? (float)(s / (double)S.rows) : 0.0f;
-  S.m[c] = mean;
-  if (c < S.ncols) S.b[c] -= mean;
+  if (c < S.ld)
+    for (int rb = g; rb < S.row_blocks; rb += 8) s += S.colpart[(size_t)rb * S.ld + c];
+  sm[g][cx] = s;
+  __syncthreads();
+  if (g == 0 && c < S.ld) {
+    double t = 0.0;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) t += sm[k][cx];
+    const float mean = c < S.ncols ? (float)(t / (double)S.rows) : 0.0f;
+    S.m[c] = mean;
+    if (c < S.ncols) S.b[c] -= mean;
+  }
 }
 
 // Closed-form ReLU z-update (Appendix A 'update z', l < L) on one element.

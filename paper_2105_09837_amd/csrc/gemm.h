@@ -13,8 +13,6 @@
 
 namespace pdadmm {
 
-constexpr int BM = 128, BN = 128, BK = 16;
-constexpr int LDM = BM + 4;   // LDS row stride in floats (keeps float4 rows 16-byte aligned)
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
@@ -43,14 +41,14 @@ struct EpiStore {     // C = alpha * acc
   static constexpr int NS = 0;
   __device__ static __forceinline__ void apply(const GemmProb& P, float* C, int row, int col, float acc,
                                                double&, double&) {
-    C[(size_t)row * P.ldc + col] = P.alpha * acc;
+    ((float PD_GLOBAL*)C)[(size_t)row * P.ldc + col] = P.alpha * acc;
   }
 };
 struct EpiStoreNorm { // C = acc, s0 += acc^2
   static constexpr int NS = 1;
   __device__ static __forceinline__ void apply(const GemmProb& P, float* C, int row, int col, float acc,
                                                double& s0, double&) {
-    C[(size_t)row * P.ldc + col] = acc;
+    ((float PD_GLOBAL*)C)[(size_t)row * P.ldc + col] = acc;
     s0 += (double)acc * (double)acc;
   }
 };
@@ -59,8 +57,8 @@ struct EpiPGrad {     // g = nu*acc + u + rho*(p - q) (gradient of phi in p_l); 
   __device__ static __forceinline__ void apply(const GemmProb& P, float* C, int row, int col, float acc,
                                                double& s0, double&) {
     const size_t i = (size_t)row * P.ldc + col;
-    const float g = P.alpha * acc + P.e0[i] + P.beta * (P.e1[i] - P.e2[i]);
-    C[i] = g;
+    const float g = P.alpha * acc + ((gcf)P.e0)[i] + P.beta * (((gcf)P.e1)[i] - ((gcf)P.e2)[i]);
+    ((float PD_GLOBAL*)C)[i] = g;
     s0 += (double)g * (double)g;
   }
 };
@@ -93,10 +91,104 @@ struct EpiForward {   // z = acc + b[col]; q = relu(z); p_next = relu(z) (projec
   }
 };
 
-template <bool KCONTIG, class Epi>
+// Tile configuration: block tile BM x BN x BK, 4 waves arranged WM x WN, each wave owns
+// (BM/WM) x (BN/WN) as a grid of 32x32 MFMA blocks.
+template <int BM_, int BN_, int BK_, int WM_, int WN_>
+struct TileCfg {
+  static constexpr int BM = BM_, BN = BN_, BK = BK_, WM = WM_, WN = WN_;
+  static constexpr int TM = BM / WM / 32, TN = BN / WN / 32;   // MFMA blocks per wave
+  static constexpr int LDA = BM + 4, LDB = BN + 4;              // LDS row strides (floats)
+  static_assert(WM * WN == 4, "256 threads = 4 waves");
+  static_assert(BM % (32 * WM) == 0 && BN % (32 * WN) == 0 && BK % 4 == 0, "tile shape");
+};
+
+
+// Loads one operand tile (ROWS "m-like" indices x BK k indices) into registers.
+//  KCONTIG: element (m, k) at base[m*ld + k]; thread owns float4 groups along k.
+//  else   : element (m, k) at base[k*ld + m]; thread owns float4 groups along m.
+// FAST: no bounds logic at all (indices are clamped into the matrix; clamped garbage only ever
+// reaches output rows/columns that are not stored). Otherwise: guarded scalar loads, zero fill.
+template <bool KCONTIG, bool FAST, int ROWS, int BK, int NV>
+__device__ __forceinline__ void load_operand(f32x4 (&reg)[NV], gcf base, int ld, int m0, int mlim, int kb, int kend,
+                                             int tid) {
+  if (KCONTIG) {
+    constexpr int KQ = BK / 4;            // float4 groups per row
+    constexpr int RSTEP = 256 / KQ;
+    const int r = tid / KQ, k = kb + (tid % KQ) * 4;
+#pragma unroll
+    for (int h = 0; h < NV; ++h) {
+      const int m = m0 + r + RSTEP * h;
+      if (FAST) {
+        const int mc = min(m, mlim - 1);
+        reg[h] = *reinterpret_cast<gcf4>(base + (size_t)mc * ld + k);
+      } else {
+        f32x4 v = {0.f, 0.f, 0.f, 0.f};
+        if (m < mlim) {
+          gcf src = base + (size_t)m * ld + k;
+          if (k + 0 < kend) v.x = src[0];
+          if (k + 1 < kend) v.y = src[1];
+          if (k + 2 < kend) v.z = src[2];
+          if (k + 3 < kend) v.w = src[3];
+        }
+        reg[h] = v;
+      }
+    }
+  } else {
+    constexpr int MQ = ROWS / 4;          // float4 groups per k-row
+    constexpr int KSTEP = 256 / MQ;
+    const int kr = tid / MQ, m = m0 + (tid % MQ) * 4;
+#pragma unroll
+    for (int h = 0; h < NV; ++h) {
+      const int k = kb + kr + KSTEP * h;
+      if (FAST) {
+        const int mc = min(m, mlim - 4);
+        reg[h] = *reinterpret_cast<gcf4>(base + (size_t)k * ld + mc);
+      } else {
+        f32x4 v = {0.f, 0.f, 0.f, 0.f};
+        if (k < kend) {
+          gcf src = base + (size_t)k * ld + m;
+          if (m + 0 < mlim) v.x = src[0];
+          if (m + 1 < mlim) v.y = src[1];
+          if (m + 2 < mlim) v.z = src[2];
+          if (m + 3 < mlim) v.w = src[3];
+        }
+        reg[h] = v;
+      }
+    }
+  }
+}
+
+template <bool KCONTIG, int ROWS, int BK, int LD, int NV>
+__device__ __forceinline__ void store_operand(float (*lds)[LD], const f32x4 (&reg)[NV], int tid) {
+  if (KCONTIG) {
+    constexpr int KQ = BK / 4;
+    constexpr int RSTEP = 256 / KQ;
+    const int r = tid / KQ, kq = (tid % KQ) * 4;
+#pragma unroll
+    for (int h = 0; h < NV; ++h) {
+      const int c = r + RSTEP * h;
+      lds[kq + 0][c] = reg[h].x;
+      lds[kq + 1][c] = reg[h].y;
+      lds[kq + 2][c] = reg[h].z;
+      lds[kq + 3][c] = reg[h].w;
+    }
+  } else {
+    constexpr int MQ = ROWS / 4;
+    constexpr int KSTEP = 256 / MQ;
+    const int kr = tid / MQ, mq = (tid % MQ) * 4;
+#pragma unroll
+    for (int h = 0; h < NV; ++h) *reinterpret_cast<f32x4*>(&lds[kr + KSTEP * h][mq]) = reg[h];
+  }
+}
+
+template <class Cfg, bool KCONTIG, class Epi>
 __device__ __forceinline__ void gemm_body(const GemmProb& P, const int local) {
-  __shared__ __attribute__((aligned(16))) float As[2][BK][LDM];
-  __shared__ __attribute__((aligned(16))) float Bs[2][BK][LDM];
+  constexpr int BM = Cfg::BM, BN = Cfg::BN, BK = Cfg::BK, TM = Cfg::TM, TN = Cfg::TN;
+  constexpr int LDA = Cfg::LDA, LDB = Cfg::LDB;
+  constexpr int NVA = BM * BK / 4 / 256, NVB = BN * BK / 4 / 256;
+  static_assert(NVA >= 1 && NVB >= 1, "tile too small for 256 loader threads");
+  __shared__ __attribute__((aligned(16))) float As[2][BK][LDA];
+  __shared__ __attribute__((aligned(16))) float Bs[2][BK][LDB];
   __shared__ double red[4];
 
   const int tiles = P.tiles_m * P.tiles_n;
@@ -110,108 +202,34 @@ __device__ __forceinline__ void gemm_body(const GemmProb& P, const int local) {
 
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
+  const int wm = wave / Cfg::WN, wn = wave % Cfg::WN;
   const int li = lane & 31, lh = lane >> 5;
+  const gcf A = (gcf)P.A;
+  const gcf B = (gcf)P.B;
+  // the branch-free loader needs 16-byte loads to be legal and, for the m-contiguous layout,
+  // whole float4 groups inside the matrix
+  const bool fastA = P.vecA && (KCONTIG || (P.M % 4 == 0 && P.M >= 4));
+  const bool fastB = P.vecB && (KCONTIG || (P.N % 4 == 0 && P.N >= 4));
 
-  float4 ra[2], rb[2];
-
+  f32x4 ra[NVA], rb[NVB];
   auto load_tile = [&](int kt) {
     const int kb = kbeg + kt * BK;
-    if (KCONTIG) {
-      const int r = tid >> 2, kq = (tid & 3) * 4;
-      const int k = kb + kq;
-#pragma unroll
-      for (int h = 0; h < 2; ++h) {
-        const int ma = m0 + r + 64 * h, nb = n0 + r + 64 * h;
-        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (ma < P.M && k < kend) {
-          const float* src = P.A + (size_t)ma * P.lda + k;
-          if (P.vecA && k + 3 < kend) v = *reinterpret_cast<const float4*>(src);
-          else {
-            v.x = src[0];
-            if (k + 1 < kend) v.y = src[1];
-            if (k + 2 < kend) v.z = src[2];
-            if (k + 3 < kend) v.w = src[3];
-          }
-        }
-        ra[h] = v;
-        v = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (nb < P.N && k < kend) {
-          const float* src = P.B + (size_t)nb * P.ldb + k;
-          if (P.vecB && k + 3 < kend) v = *reinterpret_cast<const float4*>(src);
-          else {
-            v.x = src[0];
-            if (k + 1 < kend) v.y = src[1];
-            if (k + 2 < kend) v.z = src[2];
-            if (k + 3 < kend) v.w = src[3];
-          }
-        }
-        rb[h] = v;
-      }
-    } else {
-      const int kr = tid >> 5, mq = (tid & 31) * 4;
-#pragma unroll
-      for (int h = 0; h < 2; ++h) {
-        const int k = kb + kr + 8 * h;
-        const int ma = m0 + mq, nb = n0 + mq;
-        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (k < kend && ma < P.M) {
-          const float* src = P.A + (size_t)k * P.lda + ma;
-          if (P.vecA && ma + 3 < P.M) v = *reinterpret_cast<const float4*>(src);
-          else {
-            v.x = src[0];
-            if (ma + 1 < P.M) v.y = src[1];
-            if (ma + 2 < P.M) v.z = src[2];
-            if (ma + 3 < P.M) v.w = src[3];
-          }
-        }
-        ra[h] = v;
-        v = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (k < kend && nb < P.N) {
-          const float* src = P.B + (size_t)k * P.ldb + nb;
-          if (P.vecB && nb + 3 < P.N) v = *reinterpret_cast<const float4*>(src);
-          else {
-            v.x = src[0];
-            if (nb + 1 < P.N) v.y = src[1];
-            if (nb + 2 < P.N) v.z = src[2];
-            if (nb + 3 < P.N) v.w = src[3];
-          }
-        }
-        rb[h] = v;
-      }
-    }
+    const bool full_k = kb + BK <= kend;
+    if (fastA && full_k) load_operand<KCONTIG, true, BM, BK, NVA>(ra, A, P.lda, m0, P.M, kb, kend, tid);
+    else load_operand<KCONTIG, false, BM, BK, NVA>(ra, A, P.lda, m0, P.M, kb, kend, tid);
+    if (fastB && full_k) load_operand<KCONTIG, true, BN, BK, NVB>(rb, B, P.ldb, n0, P.N, kb, kend, tid);
+    else load_operand<KCONTIG, false, BN, BK, NVB>(rb, B, P.ldb, n0, P.N, kb, kend, tid);
   };
-
   auto store_tile = [&](int buf) {
-    if (KCONTIG) {
-      const int r = tid >> 2, kq = (tid & 3) * 4;
-#pragma unroll
-      for (int h = 0; h < 2; ++h) {
-        const int c = r + 64 * h;
-        As[buf][kq + 0][c] = ra[h].x;
-        As[buf][kq + 1][c] = ra[h].y;
-        As[buf][kq + 2][c] = ra[h].z;
-        As[buf][kq + 3][c] = ra[h].w;
-        Bs[buf][kq + 0][c] = rb[h].x;
-        Bs[buf][kq + 1][c] = rb[h].y;
-        Bs[buf][kq + 2][c] = rb[h].z;
-        Bs[buf][kq + 3][c] = rb[h].w;
-      }
-    } else {
-      const int kr = tid >> 5, mq = (tid & 31) * 4;
-#pragma unroll
-      for (int h = 0; h < 2; ++h) {
-        *reinterpret_cast<float4*>(&As[buf][kr + 8 * h][mq]) = ra[h];
-        *reinterpret_cast<float4*>(&Bs[buf][kr + 8 * h][mq]) = rb[h];
-      }
-    }
+    store_operand<KCONTIG, BM, BK, LDA, NVA>(As[buf], ra, tid);
+    store_operand<KCONTIG, BN, BK, LDB, NVB>(Bs[buf], rb, tid);
   };
 
-  floatx16 acc[2][2];
+  floatx16 acc[TM][TN];
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < TM; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int j = 0; j < TN; ++j)
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
 
@@ -224,14 +242,16 @@ __device__ __forceinline__ void gemm_body(const GemmProb& P, const int local) {
       if (kt + 1 < nkt) load_tile(kt + 1);
 #pragma unroll
       for (int kk = 0; kk < BK; kk += 2) {
-        const float a0 = As[cur][kk + lh][wm * 64 + li];
-        const float a1 = As[cur][kk + lh][wm * 64 + 32 + li];
-        const float b0 = Bs[cur][kk + lh][wn * 64 + li];
-        const float b1 = Bs[cur][kk + lh][wn * 64 + 32 + li];
-        acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, acc[0][0], 0, 0, 0);
-        acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b1, acc[0][1], 0, 0, 0);
-        acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, acc[1][0], 0, 0, 0);
-        acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, acc[1][1], 0, 0, 0);
+        float a[TM], b[TN];
+#pragma unroll
+        for (int i = 0; i < TM; ++i) a[i] = As[cur][kk + lh][wm * (BM / Cfg::WM) + i * 32 + li];
+#pragma unroll
+        for (int j = 0; j < TN; ++j) b[j] = Bs[cur][kk + lh][wn * (BN / Cfg::WN) + j * 32 + li];
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int j = 0; j < TN; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], b[j], acc[i][j], 0, 0, 0);
       }
       if (kt + 1 < nkt) store_tile(cur ^ 1);
       __syncthreads();
@@ -243,14 +263,14 @@ __device__ __forceinline__ void gemm_body(const GemmProb& P, const int local) {
   float* Cout = P.C + (size_t)split * (size_t)P.M * (size_t)P.ldc;
   double s0 = 0.0, s1 = 0.0;
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < TM; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
-      const int col = n0 + wn * 64 + j * 32 + li;
+    for (int j = 0; j < TN; ++j) {
+      const int col = n0 + wn * (BN / Cfg::WN) + j * 32 + li;
       if (col < P.N) {
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
-          const int row = m0 + wm * 64 + i * 32 + 8 * (v >> 2) + 4 * lh + (v & 3);
+          const int row = m0 + wm * (BM / Cfg::WM) + i * 32 + 8 * (v >> 2) + 4 * lh + (v & 3);
           if (row < P.M) Epi::apply(P, Cout, row, col, acc[i][j][v], s0, s1);
         }
       }
@@ -266,21 +286,25 @@ __device__ __forceinline__ void gemm_body(const GemmProb& P, const int local) {
 }
 
 // Grouped launch: block -> (problem, tile) through the table; blocks of one die are contiguous.
-template <bool KCONTIG, class Epi>
+template <class Cfg, bool KCONTIG, class Epi>
 __global__ __launch_bounds__(256) void gemm_kernel(const GemmProb* __restrict__ probs, int nprob, int total,
-                                                   const LayerScal* __restrict__ scal, int predicated) {
-  const int lb = xcd_remap(blockIdx.x, total);
+                                                   const LayerScal* __restrict__ scal, int predicated,
+                                                   int panel) {
+  const int lb = xcd_remap(blockIdx.x, panel);
+  if (lb >= total) return;
   int pi = 0;
   while (pi + 1 < nprob && lb >= probs[pi + 1].blk0) ++pi;
   const GemmProb P = probs[pi];
   if (predicated && !scal[P.layer].active) return;
-  gemm_body<KCONTIG, Epi>(P, lb - P.blk0);
+  gemm_body<Cfg, KCONTIG, Epi>(P, lb - P.blk0);
 }
 
 // Single problem with the descriptor passed by value (no table in device memory needed).
-template <bool KCONTIG, class Epi>
-__global__ __launch_bounds__(256) void gemm_one_kernel(const GemmProb P) {
-  gemm_body<KCONTIG, Epi>(P, xcd_remap(blockIdx.x, P.nblk));
+template <class Cfg, bool KCONTIG, class Epi>
+__global__ __launch_bounds__(256) void gemm_one_kernel(const GemmProb P, int panel) {
+  const int lb = xcd_remap(blockIdx.x, panel);
+  if (lb >= P.nblk) return;
+  gemm_body<Cfg, KCONTIG, Epi>(P, lb);
 }
 
 // Sum the split-K partial products in a fixed order: G = alpha * sum_s part[s]; also write the

@@ -16,6 +16,10 @@
 
 using namespace pdadmm;
 
+// Tile shape of the dense products (see gemm.h).
+using Tile = TileCfg<128, 128, 16, 2, 2>;
+constexpr int BM = Tile::BM, BN = Tile::BN, BK = Tile::BK;
+
 namespace {
 
 // ------------------------------------------------------------------------------------------
@@ -91,6 +95,7 @@ struct pdadmm_ctx {
   int nb_quant = 0;
   PairSeg* s_pair = nullptr;
   int nb_pair = 0;
+  int panel = 4;              // tiles per die-local panel in the grouped product launches
   bool dirty = true;
   long iter = 0;
   std::string msg;
@@ -411,7 +416,7 @@ pdadmm_status build_tables(pdadmm_ctx* c) {
     rows.push_back(rs);
     BiasSeg bs{};
     bs.b = b.b; bs.m = b.m; bs.colpart = b.colpart; bs.ncols = b.n_out; bs.ld = b.ld_out;
-    bs.row_blocks = b.row_blocks; bs.rows = N; bs.nblk = cdiv(b.ld_out, 256);
+    bs.row_blocks = b.row_blocks; bs.rows = N; bs.nblk = cdiv(b.ld_out, 32);
     bias.push_back(bs);
     if (i < L - 1) {
       PairSeg ps{};
@@ -419,6 +424,12 @@ pdadmm_status build_tables(pdadmm_ctx* c) {
       ps.n4 = (size_t)N * b.ld_out / 4; ps.nblk = flat_blocks(ps.n4);
       pair.push_back(ps);
     }
+  }
+  {
+    // panel = number of column tiles of the typical hidden layer (tiles that share one row panel of the
+    // node-major operand), clamped to 1..8
+    const int typical = c->dims[std::min(1, L)];
+    c->panel = std::max(1, std::min(8, cdiv(typical, BN)));
   }
   c->nb_pgrad = assign_blocks(pgrad);
   c->nb_ptrial = assign_blocks(ptrial);
@@ -453,8 +464,8 @@ pdadmm_status build_tables(pdadmm_ctx* c) {
 template <bool KC, class Epi>
 void launch_gemm(pdadmm_ctx* c, const GemmProb* table, int nprob, int blocks, int predicated) {
   if (blocks <= 0) return;
-  hipLaunchKernelGGL((gemm_kernel<KC, Epi>), dim3(blocks), dim3(256), 0, c->stream, table, nprob, blocks, c->scal,
-                     predicated);
+  hipLaunchKernelGGL((gemm_kernel<Tile, KC, Epi>), dim3(xcd_padded(blocks, c->panel)), dim3(256), 0, c->stream, table,
+                     nprob, blocks, c->scal, predicated, c->panel);
 }
 
 pdadmm_status refresh_residual(pdadmm_ctx* c) {
@@ -721,8 +732,9 @@ pdadmm_status pdadmm_gemm_nt(int32_t M, int32_t N, int32_t K, const float* A, in
                              int32_t ldb, float* C, int32_t ldc, void* stream) {
   if (M < 1 || N < 1 || K < 1 || !A || !B || !C || lda < K || ldb < K || ldc < N) return PDADMM_EINVAL;
   GemmProb P = make_nt(A, lda, B, ldb, C, ldc, M, N, K);
-  hipLaunchKernelGGL((gemm_one_kernel<true, EpiStore>), dim3(P.nblk), dim3(256), 0, static_cast<hipStream_t>(stream),
-                     P);
+  const int panel = std::max(1, std::min(8, P.tiles_n));
+  hipLaunchKernelGGL((gemm_one_kernel<Tile, true, EpiStore>), dim3(xcd_padded(P.nblk, panel)), dim3(256), 0,
+                     static_cast<hipStream_t>(stream), P, panel);
   return hipGetLastError() == hipSuccess ? PDADMM_OK : PDADMM_EHIP;
 }
 
@@ -736,7 +748,9 @@ pdadmm_status pdadmm_gemm_tn(int32_t M, int32_t N, int32_t K, float alpha, const
   const int sk = cdiv(K, chunk);
   GemmProb P = make_tn(A, lda, B, ldb, part, ldc, M, N, K, sk, chunk);
   hipStream_t st = static_cast<hipStream_t>(stream);
-  hipLaunchKernelGGL((gemm_one_kernel<false, EpiStore>), dim3(P.nblk), dim3(256), 0, st, P);
+  const int panel = std::max(1, std::min(8, P.tiles_n));
+  hipLaunchKernelGGL((gemm_one_kernel<Tile, false, EpiStore>), dim3(xcd_padded(P.nblk, panel)), dim3(256), 0, st, P,
+                     panel);
   if (hipGetLastError() != hipSuccess) return PDADMM_EHIP;
   ReduceProb R{};
   R.part = part; R.G = C; R.norm_part = nullptr; R.M = M; R.N = N; R.ld = ldc; R.splitk = sk; R.alpha = alpha;
@@ -808,8 +822,8 @@ pdadmm_status pdadmm_init(pdadmm_ctx** out, const pdadmm_config* cfg, void* work
   if (s != PDADMM_OK) return s;
   // forward-consistent start, layer after layer
   for (int i = 0; i < L; ++i) {
-    hipLaunchKernelGGL((gemm_kernel<true, EpiForward>), dim3(c->fwd_blocks[i]), dim3(256), 0, c->stream,
-                       c->t_fwd + i, 1, c->fwd_blocks[i], c->scal, 0);
+    hipLaunchKernelGGL((gemm_kernel<Tile, true, EpiForward>), dim3(xcd_padded(c->fwd_blocks[i], c->panel)), dim3(256),
+                       0, c->stream, c->t_fwd + i, 1, c->fwd_blocks[i], c->scal, 0, c->panel);
     LAUNCH_CHECK(c, "gemm forward");
   }
   if (cfg->quantize) {
