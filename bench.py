@@ -24,7 +24,7 @@ HBM_PEAK_GBS = 8000.0
 
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc runs (FETCH_SIZE / WRITE_SIZE scaled
 # by a copy kernel of known size); see profiles/. None until measured for a workload.
-MEASURED_TRAFFIC_BYTES = {}
+MEASURED_TRAFFIC_BYTES = {"C2": 1.02e9}   # 609 MiB read + 363 MiB written per launch, profiles/C2_iteration_kernels.md
 
 
 def gemm_flops_per_iteration(dims, n_nodes):
@@ -117,6 +117,8 @@ def main():
     ap.add_argument("--workload", default="C2", help="C1..C5 (default C2: the configuration the metric is quoted on)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--all-classes", action="store_true", help="time every kernel class (adds event overhead)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one plain 1 GiB device copy (reference point for FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no sharding, no collectives); use --gpus 1", file=sys.stderr)
@@ -134,6 +136,12 @@ def main():
     w = get_workload(args.workload)
     ctx, info, host = build_problem(w, device)
 
+    if args.copy_calibration:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=device)      # 1 GiB
+        dst = torch.empty_like(src)
+        torch.add(src, 1.0, out=dst)                                       # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
     P.pdadmm_iterate(ctx, args.warmup)
     P.pdadmm_sync(ctx)
     dominant = "gemm_trial"

@@ -31,6 +31,23 @@ __host__ __device__ inline int xcd_padded(int total, int panel) {
   return (total + g - 1) / g * g;
 }
 
+// Block -> group lookup for the layer-grouped launches. The table of first block ids travels in the
+// kernel arguments (no dependent chain of global loads at block start): lane i compares against
+// entry i, a ballot gives the group index. Entries are ascending, blk0[0] = 0, n <= kMaxGroup.
+constexpr int kMaxGroup = 64;
+struct BlockMap {
+  int n, total;
+  int blk0[kMaxGroup];
+};
+__device__ __forceinline__ int find_group(const BlockMap& m, int lb, int* local) {
+  const int lane = threadIdx.x & 63;
+  const int first = lane < m.n ? m.blk0[lane] : 0x7fffffff;
+  const unsigned long long hit = __ballot(lb >= first);
+  const int idx = __builtin_amdgcn_readfirstlane(__popcll(hit) - 1);
+  *local = lb - m.blk0[idx];
+  return idx;
+}
+
 __device__ __forceinline__ double wave_sum(double v) {
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, kWave);

@@ -20,11 +20,10 @@ struct AxpySeg {
   int layer, which;
 };
 
-__global__ __launch_bounds__(256) void axpy_kernel(const AxpySeg* __restrict__ segs, int nseg,
+__global__ __launch_bounds__(256) void axpy_kernel(const AxpySeg* __restrict__ segs, const BlockMap map,
                                                    const LayerScal* __restrict__ scal) {
-  const int lb = blockIdx.x;
-  int si = 0;
-  while (si + 1 < nseg && lb >= segs[si + 1].blk0) ++si;
+  int local;
+  const int si = find_group(map, blockIdx.x, &local);
   const AxpySeg S = segs[si];
   const LayerScal& sc = scal[S.layer];
   float s;
@@ -35,7 +34,7 @@ __global__ __launch_bounds__(256) void axpy_kernel(const AxpySeg* __restrict__ s
   float4* y = reinterpret_cast<float4*>(S.y);
   const float4* x = reinterpret_cast<const float4*>(S.x);
   const size_t stride = (size_t)S.nblk * 256;
-  for (size_t i = (size_t)(lb - S.blk0) * 256 + threadIdx.x; i < S.n4; i += stride) {
+  for (size_t i = (size_t)local * 256 + threadIdx.x; i < S.n4; i += stride) {
     float4 a = y[i];
     const float4 b = x[i];
     a.x -= s * b.x;
@@ -116,15 +115,13 @@ struct WStepSeg {
   int layer;
 };
 
-__global__ __launch_bounds__(256) void w_step_kernel(const WStepSeg* __restrict__ segs, int nseg,
+__global__ __launch_bounds__(256) void w_step_kernel(const WStepSeg* __restrict__ segs, const BlockMap map,
                                                      const LayerScal* __restrict__ scal, int copy_only) {
   __shared__ float tile[32][33];
-  const int lb = blockIdx.x;
-  int si = 0;
-  while (si + 1 < nseg && lb >= segs[si + 1].blk0) ++si;
+  int local;
+  const int si = find_group(map, blockIdx.x, &local);
   const WStepSeg S = segs[si];
   const float inv = copy_only ? 0.0f : scal[S.layer].inv_theta;
-  const int local = lb - S.blk0;
   const int tr = local / S.tiles_c, tc = local % S.tiles_c;
   const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
 #pragma unroll
@@ -172,15 +169,13 @@ struct RowSeg {
 
 // R <- R - T/theta and per-block column sums of the new R (b-update, Appendix A 'update b':
 // the minimiser over the broadcast bias subtracts the node-mean of W p + b - z).
-__global__ __launch_bounds__(256) void resid_colsum_kernel(const RowSeg* __restrict__ segs, int nseg,
+__global__ __launch_bounds__(256) void resid_colsum_kernel(const RowSeg* __restrict__ segs, const BlockMap map,
                                                            const LayerScal* __restrict__ scal) {
   __shared__ double sm[4][64][4];
-  const int lb = blockIdx.x;
-  int si = 0;
-  while (si + 1 < nseg && lb >= segs[si + 1].blk0) ++si;
+  int local;
+  const int si = find_group(map, blockIdx.x, &local);
   const RowSeg S = segs[si];
   const float inv = scal[S.layer].inv_theta;
-  const int local = lb - S.blk0;
   const int cb = local % S.col_blocks, rb = local / S.col_blocks;
   const int cq = threadIdx.x & 63, ty = threadIdx.x >> 6;
   const int col = (cb * 64 + cq) * 4;
@@ -221,14 +216,13 @@ struct BiasSeg {
   int blk0, nblk;
 };
 
-__global__ __launch_bounds__(256) void bias_step_kernel(const BiasSeg* __restrict__ segs, int nseg) {
+__global__ __launch_bounds__(256) void bias_step_kernel(const BiasSeg* __restrict__ segs, const BlockMap map) {
   __shared__ double sm[8][32];
-  const int lb = blockIdx.x;
-  int si = 0;
-  while (si + 1 < nseg && lb >= segs[si + 1].blk0) ++si;
+  int local;
+  const int si = find_group(map, blockIdx.x, &local);
   const BiasSeg S = segs[si];
   const int cx = threadIdx.x & 31, g = threadIdx.x >> 5;
-  const int c = (lb - S.blk0) * 32 + cx;
+  const int c = local * 32 + cx;
   double s = 0.0;
   if (c < S.ld)
     for (int rb = g; rb < S.row_blocks; rb += 8) s += S.colpart[(size_t)rb * S.ld + c];
@@ -261,12 +255,10 @@ __device__ __forceinline__ float z_closed_form(float s, float q) {
 // (Appendix A 'update z', 'update q', 'update u'):
 //   a = R - m + z_old; z = closed form; R <- a - z;
 //   q = (rho p_{l+1} + u + nu relu(z)) / (rho + nu); r = p_{l+1} - q; u <- u + rho r.
-__global__ __launch_bounds__(256) void zqu_kernel(const RowSeg* __restrict__ segs, int nseg, float rho, float nu) {
-  const int lb = blockIdx.x;
-  int si = 0;
-  while (si + 1 < nseg && lb >= segs[si + 1].blk0) ++si;
+__global__ __launch_bounds__(256) void zqu_kernel(const RowSeg* __restrict__ segs, const BlockMap map, float rho, float nu) {
+  int local;
+  const int si = find_group(map, blockIdx.x, &local);
   const RowSeg S = segs[si];
-  const int local = lb - S.blk0;
   const int cb = local % S.col_blocks, rb = local / S.col_blocks;
   const int cq = threadIdx.x & 63, ty = threadIdx.x >> 6;
   const int col = (cb * 64 + cq) * 4;
@@ -390,18 +382,17 @@ struct QuantSeg {
   int layer;
 };
 
-__global__ __launch_bounds__(256) void quant_trial_kernel(const QuantSeg* __restrict__ segs, int nseg,
+__global__ __launch_bounds__(256) void quant_trial_kernel(const QuantSeg* __restrict__ segs, const BlockMap map,
                                                           const LayerScal* __restrict__ scal, QuantGrid grid) {
   __shared__ double red[4];
-  const int lb = blockIdx.x;
-  int si = 0;
-  while (si + 1 < nseg && lb >= segs[si + 1].blk0) ++si;
+  int local;
+  const int si = find_group(map, blockIdx.x, &local);
   const QuantSeg S = segs[si];
   if (!scal[S.layer].active) return;
   const float t = scal[S.layer].trial_t;
   const size_t stride = (size_t)S.nblk * 256;
   double ds = 0.0;
-  for (size_t i = (size_t)(lb - S.blk0) * 256 + threadIdx.x; i < S.n4; i += stride) {
+  for (size_t i = (size_t)local * 256 + threadIdx.x; i < S.n4; i += stride) {
     const float4 pv = reinterpret_cast<const float4*>(S.p)[i];
     const float4 gv = reinterpret_cast<const float4*>(S.g)[i];
     const int col0 = (int)((i * 4) % (size_t)S.ld);
@@ -426,7 +417,7 @@ __global__ __launch_bounds__(256) void quant_trial_kernel(const QuantSeg* __rest
     reinterpret_cast<uchar4*>(S.idx)[i] = iv;
   }
   const double tot = block_sum_256(ds, red);
-  if (threadIdx.x == 0) S.dpart[lb - S.blk0] = tot;
+  if (threadIdx.x == 0) S.dpart[local] = tot;
 }
 
 // Accept/reject one -Q trial: phi(p+d) - phi(p) - <g,d> = (nu/2)||W d||^2 + (rho/2)||d||^2 exactly,
@@ -481,15 +472,14 @@ __global__ __launch_bounds__(256) void select_quant_kernel(const SelectDesc* __r
 }
 
 // p <- Delta[idx] for layers whose trial was accepted.
-__global__ __launch_bounds__(256) void quant_apply_kernel(const QuantSeg* __restrict__ segs, int nseg,
+__global__ __launch_bounds__(256) void quant_apply_kernel(const QuantSeg* __restrict__ segs, const BlockMap map,
                                                           const LayerScal* __restrict__ scal, QuantGrid grid) {
-  const int lb = blockIdx.x;
-  int si = 0;
-  while (si + 1 < nseg && lb >= segs[si + 1].blk0) ++si;
+  int local;
+  const int si = find_group(map, blockIdx.x, &local);
   const QuantSeg S = segs[si];
   if (scal[S.layer].inv_tau == 0.0f) return;
   const size_t stride = (size_t)S.nblk * 256;
-  for (size_t i = (size_t)(lb - S.blk0) * 256 + threadIdx.x; i < S.n4; i += stride) {
+  for (size_t i = (size_t)local * 256 + threadIdx.x; i < S.n4; i += stride) {
     const uchar4 iv = reinterpret_cast<const uchar4*>(S.idx)[i];
     const int col0 = (int)((i * 4) % (size_t)S.ld);
     float4 pv;
@@ -549,15 +539,14 @@ struct PairSeg {
   int blk0, nblk;
 };
 
-__global__ __launch_bounds__(256) void pair_reduce_kernel(const PairSeg* __restrict__ segs, int nseg) {
+__global__ __launch_bounds__(256) void pair_reduce_kernel(const PairSeg* __restrict__ segs, const BlockMap map) {
   __shared__ double red[4];
-  const int lb = blockIdx.x;
-  int si = 0;
-  while (si + 1 < nseg && lb >= segs[si + 1].blk0) ++si;
+  int local;
+  const int si = find_group(map, blockIdx.x, &local);
   const PairSeg S = segs[si];
   const size_t stride = (size_t)S.nblk * 256;
   double s_act = 0, s_dl = 0, s_dq = 0;
-  for (size_t i = (size_t)(lb - S.blk0) * 256 + threadIdx.x; i < S.n4; i += stride) {
+  for (size_t i = (size_t)local * 256 + threadIdx.x; i < S.n4; i += stride) {
     const float4 z = reinterpret_cast<const float4*>(S.z)[i];
     const float4 q = reinterpret_cast<const float4*>(S.q)[i];
     const float4 u = reinterpret_cast<const float4*>(S.u)[i];
@@ -577,7 +566,7 @@ __global__ __launch_bounds__(256) void pair_reduce_kernel(const PairSeg* __restr
   const double t1 = block_sum_256(s_dl, red);
   const double t2 = block_sum_256(s_dq, red);
   if (threadIdx.x == 0) {
-    double* o = S.part + (size_t)(lb - S.blk0) * 3;
+    double* o = S.part + (size_t)local * 3;
     o[0] = t0; o[1] = t1; o[2] = t2;
   }
 }

@@ -106,8 +106,11 @@ struct TileCfg {
 // Loads one operand tile (ROWS "m-like" indices x BK k indices) into registers.
 //  KCONTIG: element (m, k) at base[m*ld + k]; thread owns float4 groups along k.
 //  else   : element (m, k) at base[k*ld + m]; thread owns float4 groups along m.
-// FAST: no bounds logic at all (indices are clamped into the matrix; clamped garbage only ever
-// reaches output rows/columns that are not stored). Otherwise: guarded scalar loads, zero fill.
+// FAST: branch-free 16-byte loads from addresses clamped into the matrix. Whatever a clamped m
+// index fetches only reaches output rows/columns that are never stored; k indices beyond the
+// range are zeroed when the tile is written to LDS (store_operand). Needs ld % 4 == 0, a
+// 16-byte aligned base and, for the m-contiguous layout, a width that is a multiple of 4.
+// Otherwise: guarded scalar loads with zero fill.
 template <bool KCONTIG, bool FAST, int ROWS, int BK, int NV>
 __device__ __forceinline__ void load_operand(f32x4 (&reg)[NV], gcf base, int ld, int m0, int mlim, int kb, int kend,
                                              int tid) {
@@ -120,7 +123,8 @@ __device__ __forceinline__ void load_operand(f32x4 (&reg)[NV], gcf base, int ld,
       const int m = m0 + r + RSTEP * h;
       if (FAST) {
         const int mc = min(m, mlim - 1);
-        reg[h] = *reinterpret_cast<gcf4>(base + (size_t)mc * ld + k);
+        const int kc = min(k, (kend - 1) & ~3);
+        reg[h] = *reinterpret_cast<gcf4>(base + (size_t)mc * ld + kc);
       } else {
         f32x4 v = {0.f, 0.f, 0.f, 0.f};
         if (m < mlim) {
@@ -142,7 +146,8 @@ __device__ __forceinline__ void load_operand(f32x4 (&reg)[NV], gcf base, int ld,
       const int k = kb + kr + KSTEP * h;
       if (FAST) {
         const int mc = min(m, mlim - 4);
-        reg[h] = *reinterpret_cast<gcf4>(base + (size_t)k * ld + mc);
+        const int kc = min(k, kend - 1);
+        reg[h] = *reinterpret_cast<gcf4>(base + (size_t)kc * ld + mc);
       } else {
         f32x4 v = {0.f, 0.f, 0.f, 0.f};
         if (k < kend) {
@@ -158,28 +163,36 @@ __device__ __forceinline__ void load_operand(f32x4 (&reg)[NV], gcf base, int ld,
   }
 }
 
-template <bool KCONTIG, int ROWS, int BK, int LD, int NV>
-__device__ __forceinline__ void store_operand(float (*lds)[LD], const f32x4 (&reg)[NV], int tid) {
+// Writes a register tile to LDS as [k][m]. With FAST the entries whose k lies beyond kend are zeroed here.
+template <bool KCONTIG, bool FAST, int ROWS, int BK, int LD, int NV>
+__device__ __forceinline__ void store_operand(float (*lds)[LD], const f32x4 (&reg)[NV], int kb, int kend, int tid) {
   if (KCONTIG) {
     constexpr int KQ = BK / 4;
     constexpr int RSTEP = 256 / KQ;
     const int r = tid / KQ, kq = (tid % KQ) * 4;
+    const int rem = kend - (kb + kq);     // components c < rem are inside the k range
 #pragma unroll
     for (int h = 0; h < NV; ++h) {
       const int c = r + RSTEP * h;
-      lds[kq + 0][c] = reg[h].x;
-      lds[kq + 1][c] = reg[h].y;
-      lds[kq + 2][c] = reg[h].z;
-      lds[kq + 3][c] = reg[h].w;
+      lds[kq + 0][c] = (!FAST || rem > 0) ? reg[h].x : 0.f;
+      lds[kq + 1][c] = (!FAST || rem > 1) ? reg[h].y : 0.f;
+      lds[kq + 2][c] = (!FAST || rem > 2) ? reg[h].z : 0.f;
+      lds[kq + 3][c] = (!FAST || rem > 3) ? reg[h].w : 0.f;
     }
   } else {
     constexpr int MQ = ROWS / 4;
     constexpr int KSTEP = 256 / MQ;
     const int kr = tid / MQ, mq = (tid % MQ) * 4;
 #pragma unroll
-    for (int h = 0; h < NV; ++h) *reinterpret_cast<f32x4*>(&lds[kr + KSTEP * h][mq]) = reg[h];
+    for (int h = 0; h < NV; ++h) {
+      f32x4 v = reg[h];
+      if (FAST && kb + kr + KSTEP * h >= kend) v = f32x4{0.f, 0.f, 0.f, 0.f};
+      *reinterpret_cast<f32x4*>(&lds[kr + KSTEP * h][mq]) = v;
+    }
   }
 }
+
+template <bool B> struct BoolTag { static constexpr bool value = B; };
 
 template <class Cfg, bool KCONTIG, class Epi>
 __device__ __forceinline__ void gemm_body(const GemmProb& P, const int local) {
@@ -208,22 +221,7 @@ __device__ __forceinline__ void gemm_body(const GemmProb& P, const int local) {
   const gcf B = (gcf)P.B;
   // the branch-free loader needs 16-byte loads to be legal and, for the m-contiguous layout,
   // whole float4 groups inside the matrix
-  const bool fastA = P.vecA && (KCONTIG || (P.M % 4 == 0 && P.M >= 4));
-  const bool fastB = P.vecB && (KCONTIG || (P.N % 4 == 0 && P.N >= 4));
-
-  f32x4 ra[NVA], rb[NVB];
-  auto load_tile = [&](int kt) {
-    const int kb = kbeg + kt * BK;
-    const bool full_k = kb + BK <= kend;
-    if (fastA && full_k) load_operand<KCONTIG, true, BM, BK, NVA>(ra, A, P.lda, m0, P.M, kb, kend, tid);
-    else load_operand<KCONTIG, false, BM, BK, NVA>(ra, A, P.lda, m0, P.M, kb, kend, tid);
-    if (fastB && full_k) load_operand<KCONTIG, true, BN, BK, NVB>(rb, B, P.ldb, n0, P.N, kb, kend, tid);
-    else load_operand<KCONTIG, false, BN, BK, NVB>(rb, B, P.ldb, n0, P.N, kb, kend, tid);
-  };
-  auto store_tile = [&](int buf) {
-    store_operand<KCONTIG, BM, BK, LDA, NVA>(As[buf], ra, tid);
-    store_operand<KCONTIG, BN, BK, LDB, NVB>(Bs[buf], rb, tid);
-  };
+  const bool fast = P.vecA && P.vecB && (KCONTIG || (P.M % 4 == 0 && P.M >= 4 && P.N % 4 == 0 && P.N >= 4));
 
   floatx16 acc[TM][TN];
 #pragma unroll
@@ -233,29 +231,67 @@ __device__ __forceinline__ void gemm_body(const GemmProb& P, const int local) {
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
 
-  if (nkt > 0) {
-    load_tile(0);
-    store_tile(0);
-    __syncthreads();
-    for (int kt = 0; kt < nkt; ++kt) {
-      const int cur = kt & 1;
-      if (kt + 1 < nkt) load_tile(kt + 1);
+  // MFMAs of one staged tile; the fragments of k-step kk+2 are fetched before the MFMAs of kk issue
+  auto compute_tile = [&](int cur, auto&& mid) {
+    float a[2][TM], b[2][TN];
 #pragma unroll
-      for (int kk = 0; kk < BK; kk += 2) {
-        float a[TM], b[TN];
+    for (int i = 0; i < TM; ++i) a[0][i] = As[cur][lh][wm * (BM / Cfg::WM) + i * 32 + li];
 #pragma unroll
-        for (int i = 0; i < TM; ++i) a[i] = As[cur][kk + lh][wm * (BM / Cfg::WM) + i * 32 + li];
+    for (int j = 0; j < TN; ++j) b[0][j] = Bs[cur][lh][wn * (BN / Cfg::WN) + j * 32 + li];
 #pragma unroll
-        for (int j = 0; j < TN; ++j) b[j] = Bs[cur][kk + lh][wn * (BN / Cfg::WN) + j * 32 + li];
+    for (int kk = 0; kk < BK; kk += 2) {
+      const int c = (kk >> 1) & 1, n = c ^ 1;
+      if (kk + 2 < BK) {
 #pragma unroll
-        for (int i = 0; i < TM; ++i)
+        for (int i = 0; i < TM; ++i) a[n][i] = As[cur][kk + 2 + lh][wm * (BM / Cfg::WM) + i * 32 + li];
 #pragma unroll
-          for (int j = 0; j < TN; ++j)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], b[j], acc[i][j], 0, 0, 0);
+        for (int j = 0; j < TN; ++j) b[n][j] = Bs[cur][kk + 2 + lh][wn * (BN / Cfg::WN) + j * 32 + li];
       }
-      if (kt + 1 < nkt) store_tile(cur ^ 1);
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[c][i], b[c][j], acc[i][j], 0, 0, 0);
+      if (kk == (BK / 2 & ~1)) mid();   // LDS store of the next tile rides in the shadow of the MFMAs
+    }
+  };
+  auto nothing = [] {};
+
+  // Main loop with two register sets: the global loads of tile t+2 are issued before the MFMAs of
+  // tile t, the LDS store of tile t+1 (loaded one tile earlier) follows them, one barrier per tile.
+  auto main_loop = [&](auto fast_tag) {
+    constexpr bool FAST = decltype(fast_tag)::value;
+    f32x4 ra0[NVA], rb0[NVB], ra1[NVA], rb1[NVB];
+    auto load_tile = [&](int kt, f32x4 (&ra)[NVA], f32x4 (&rb)[NVB]) {
+      const int kb = kbeg + kt * BK;
+      load_operand<KCONTIG, FAST, BM, BK, NVA>(ra, A, P.lda, m0, P.M, kb, kend, tid);
+      load_operand<KCONTIG, FAST, BN, BK, NVB>(rb, B, P.ldb, n0, P.N, kb, kend, tid);
+    };
+    auto store_tile = [&](int kt, int buf, const f32x4 (&ra)[NVA], const f32x4 (&rb)[NVB]) {
+      const int kb = kbeg + kt * BK;
+      store_operand<KCONTIG, FAST, BM, BK, LDA, NVA>(As[buf], ra, kb, kend, tid);
+      store_operand<KCONTIG, FAST, BN, BK, LDB, NVB>(Bs[buf], rb, kb, kend, tid);
+    };
+    load_tile(0, ra0, rb0);
+    if (nkt > 1) load_tile(1, ra1, rb1);
+    store_tile(0, 0, ra0, rb0);
+    __syncthreads();
+    int kt = 0;
+    for (; kt + 1 < nkt; kt += 2) {
+      // even tile: LDS buffer 0 is current, set 1 holds tile kt+1, set 0 is free
+      if (kt + 2 < nkt) load_tile(kt + 2, ra0, rb0);
+      compute_tile(0, [&] { store_tile(kt + 1, 1, ra1, rb1); });
+      __syncthreads();
+      // odd tile: LDS buffer 1 is current, set 0 holds tile kt+2, set 1 is free
+      if (kt + 3 < nkt) load_tile(kt + 3, ra1, rb1);
+      compute_tile(1, [&] { if (kt + 2 < nkt) store_tile(kt + 2, 0, ra0, rb0); });
       __syncthreads();
     }
+    if (kt < nkt) compute_tile(0, nothing);   // odd tile count: the last tile sits in buffer 0
+  };
+  if (nkt > 0) {
+    if (fast) main_loop(BoolTag<true>{});
+    else main_loop(BoolTag<false>{});
   }
 
   // Epilogue. MFMA 32x32 output layout: register v of lane l holds
@@ -287,16 +323,16 @@ __device__ __forceinline__ void gemm_body(const GemmProb& P, const int local) {
 
 // Grouped launch: block -> (problem, tile) through the table; blocks of one die are contiguous.
 template <class Cfg, bool KCONTIG, class Epi>
-__global__ __launch_bounds__(256) void gemm_kernel(const GemmProb* __restrict__ probs, int nprob, int total,
+__global__ __launch_bounds__(256) void gemm_kernel(const GemmProb* __restrict__ probs, const BlockMap map,
                                                    const LayerScal* __restrict__ scal, int predicated,
                                                    int panel) {
   const int lb = xcd_remap(blockIdx.x, panel);
-  if (lb >= total) return;
-  int pi = 0;
-  while (pi + 1 < nprob && lb >= probs[pi + 1].blk0) ++pi;
+  if (lb >= map.total) return;
+  int local;
+  const int pi = find_group(map, lb, &local);
   const GemmProb P = probs[pi];
   if (predicated && !scal[P.layer].active) return;
-  gemm_body<Cfg, KCONTIG, Epi>(P, lb - P.blk0);
+  gemm_body<Cfg, KCONTIG, Epi>(P, local);
 }
 
 // Single problem with the descriptor passed by value (no table in device memory needed).
@@ -336,12 +372,11 @@ __device__ __forceinline__ void splitk_reduce_body(const ReduceProb& P, const in
   if (threadIdx.x == 0 && P.norm_part) P.norm_part[local] = t;
 }
 
-__global__ __launch_bounds__(256) void splitk_reduce_kernel(const ReduceProb* __restrict__ probs, int nprob) {
-  const int lb = blockIdx.x;
-  int pi = 0;
-  while (pi + 1 < nprob && lb >= probs[pi + 1].blk0) ++pi;
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(const ReduceProb* __restrict__ probs, const BlockMap map) {
+  int local;
+  const int pi = find_group(map, blockIdx.x, &local);
   const ReduceProb P = probs[pi];
-  splitk_reduce_body(P, lb - P.blk0);
+  splitk_reduce_body(P, local);
 }
 __global__ __launch_bounds__(256) void splitk_reduce_one_kernel(const ReduceProb P) {
   splitk_reduce_body(P, blockIdx.x);

@@ -58,6 +58,34 @@ struct LayerBufs {
   int row_blocks, col_blocks;
 };
 
+// A descriptor table in device memory plus, for every launch chunk of at most kMaxGroup entries,
+// the block map that travels in the kernel arguments.
+template <class T>
+struct Group {
+  T* dev = nullptr;
+  std::vector<BlockMap> maps;
+  std::vector<int> start;
+  int count = 0;
+  void build(T* table, const std::vector<T>& v, int n) {
+    dev = table;
+    count = n;
+    maps.clear();
+    start.clear();
+    for (int s0 = 0; s0 < n; s0 += kMaxGroup) {
+      BlockMap m{};
+      m.n = std::min(kMaxGroup, n - s0);
+      int b = 0;
+      for (int j = 0; j < m.n; ++j) {
+        m.blk0[j] = b;
+        b += v[s0 + j].nblk;
+      }
+      m.total = b;
+      maps.push_back(m);
+      start.push_back(s0);
+    }
+  }
+};
+
 }  // namespace
 
 struct pdadmm_ctx {
@@ -75,26 +103,17 @@ struct pdadmm_ctx {
   double* riskpart = nullptr;
   int risk_blocks = 0;
   QuantGrid grid{0.f, 0.f, 0};
-  // descriptor tables in device memory
-  GemmProb *t_pgrad = nullptr, *t_ptrial = nullptr, *t_wgrad = nullptr, *t_wtrial = nullptr, *t_resid = nullptr,
-           *t_resid_obj = nullptr, *t_fwd = nullptr;
-  int nb_pgrad = 0, nb_ptrial = 0, nb_wgrad = 0, nb_wtrial = 0, nb_resid = 0;
-  std::vector<int> fwd_blocks;
-  ReduceProb* t_red = nullptr;
-  int nb_red = 0;
-  AxpySeg *s_pstep = nullptr, *s_qapply_r = nullptr;
-  int nb_pstep = 0, nb_qapply_r = 0;
+  // descriptor tables in device memory, each with the block maps of its launches
+  Group<GemmProb> g_pgrad, g_ptrial, g_wgrad, g_wtrial, g_resid, g_resid_obj;
+  std::vector<GemmProb> fwd;          // forward pass of the starting point: one by-value launch per layer
+  Group<ReduceProb> g_red;
+  Group<AxpySeg> g_pstep, g_qapply_r;
   SelectDesc *sel_p = nullptr, *sel_w = nullptr, *sel_q = nullptr;
-  WStepSeg* s_w = nullptr;
-  int nb_w = 0;
-  RowSeg* s_rows = nullptr;
-  int nb_rows_all = 0, nb_rows_hidden = 0;
-  BiasSeg* s_bias = nullptr;
-  int nb_bias = 0;
-  QuantSeg* s_quant = nullptr;
-  int nb_quant = 0;
-  PairSeg* s_pair = nullptr;
-  int nb_pair = 0;
+  Group<WStepSeg> g_w;
+  Group<RowSeg> g_rows_all, g_rows_hidden;
+  Group<BiasSeg> g_bias;
+  Group<QuantSeg> g_quant;
+  Group<PairSeg> g_pair;
   int panel = 4;              // tiles per die-local panel in the grouped product launches
   bool dirty = true;
   long iter = 0;
@@ -255,24 +274,23 @@ size_t plan(pdadmm_ctx* c, void* base) {
   c->mask = cv.take<uint8_t>(N);
   c->risk_blocks = cdiv(N, 256);
   c->riskpart = cv.take<double>(c->risk_blocks);
-  c->t_pgrad = cv.take<GemmProb>(L);
-  c->t_ptrial = cv.take<GemmProb>(L);
-  c->t_wgrad = cv.take<GemmProb>(L);
-  c->t_wtrial = cv.take<GemmProb>(L);
-  c->t_resid = cv.take<GemmProb>(L);
-  c->t_resid_obj = cv.take<GemmProb>(L);
-  c->t_fwd = cv.take<GemmProb>(L);
-  c->t_red = cv.take<ReduceProb>(L);
-  c->s_pstep = cv.take<AxpySeg>(2 * L);
-  c->s_qapply_r = cv.take<AxpySeg>(L);
+  c->g_pgrad.dev = cv.take<GemmProb>(L);
+  c->g_ptrial.dev = cv.take<GemmProb>(L);
+  c->g_wgrad.dev = cv.take<GemmProb>(L);
+  c->g_wtrial.dev = cv.take<GemmProb>(L);
+  c->g_resid.dev = cv.take<GemmProb>(L);
+  c->g_resid_obj.dev = cv.take<GemmProb>(L);
+  c->g_red.dev = cv.take<ReduceProb>(L);
+  c->g_pstep.dev = cv.take<AxpySeg>(2 * L);
+  c->g_qapply_r.dev = cv.take<AxpySeg>(L);
   c->sel_p = cv.take<SelectDesc>(L);
   c->sel_w = cv.take<SelectDesc>(L);
   c->sel_q = cv.take<SelectDesc>(L);
-  c->s_w = cv.take<WStepSeg>(L);
-  c->s_rows = cv.take<RowSeg>(L);
-  c->s_bias = cv.take<BiasSeg>(L);
-  c->s_quant = cv.take<QuantSeg>(L);
-  c->s_pair = cv.take<PairSeg>(L);
+  c->g_w.dev = cv.take<WStepSeg>(L);
+  c->g_rows_all.dev = cv.take<RowSeg>(L);
+  c->g_bias.dev = cv.take<BiasSeg>(L);
+  c->g_quant.dev = cv.take<QuantSeg>(L);
+  c->g_pair.dev = cv.take<PairSeg>(L);
   return (cv.off + 255) & ~size_t(255);
 }
 
@@ -311,16 +329,6 @@ pdadmm_status upload(pdadmm_ctx* c, T* dst, const std::vector<T>& src) {
   HIP_TRY(c, hipMemcpyAsync(dst, src.data(), src.size() * sizeof(T), hipMemcpyHostToDevice, c->stream));
   HIP_TRY(c, hipStreamSynchronize(c->stream));   // the host vector goes out of scope in the caller
   return PDADMM_OK;
-}
-
-template <class T>
-int assign_blocks(std::vector<T>& v) {
-  int b = 0;
-  for (auto& e : v) {
-    e.blk0 = b;
-    b += e.nblk;
-  }
-  return b;
 }
 
 pdadmm_status build_tables(pdadmm_ctx* c) {
@@ -431,48 +439,50 @@ pdadmm_status build_tables(pdadmm_ctx* c) {
     const int typical = c->dims[std::min(1, L)];
     c->panel = std::max(1, std::min(8, cdiv(typical, BN)));
   }
-  c->nb_pgrad = assign_blocks(pgrad);
-  c->nb_ptrial = assign_blocks(ptrial);
-  c->nb_wgrad = assign_blocks(wgrad);
-  c->nb_wtrial = assign_blocks(wtrial);
-  c->nb_resid = assign_blocks(resid);
-  assign_blocks(resid_obj);
-  c->nb_red = assign_blocks(red);
-  c->nb_pstep = assign_blocks(pstep);
-  c->nb_qapply_r = assign_blocks(qapply_r);
-  c->nb_w = assign_blocks(wseg);
-  {
-    // rows: hidden layers first in block order is not needed; the zqu launch simply uses the first L-1 entries
-    c->nb_rows_all = assign_blocks(rows);
-    c->nb_rows_hidden = L > 1 ? rows[L - 1].blk0 : 0;
-  }
-  c->nb_bias = assign_blocks(bias);
-  c->nb_quant = assign_blocks(quant);
-  c->nb_pair = assign_blocks(pair);
-  c->fwd_blocks.clear();
-  for (auto& f : fwd) c->fwd_blocks.push_back(f.nblk);
   pdadmm_status s;
-#define UP(dst, v) if ((s = upload(c, dst, v)) != PDADMM_OK) return s
-  UP(c->t_pgrad, pgrad); UP(c->t_ptrial, ptrial); UP(c->t_wgrad, wgrad); UP(c->t_wtrial, wtrial);
-  UP(c->t_resid, resid); UP(c->t_resid_obj, resid_obj); UP(c->t_fwd, fwd); UP(c->t_red, red);
-  UP(c->s_pstep, pstep); UP(c->s_qapply_r, qapply_r); UP(c->sel_p, sel_p); UP(c->sel_w, sel_w); UP(c->sel_q, sel_q);
-  UP(c->s_w, wseg); UP(c->s_rows, rows); UP(c->s_bias, bias); UP(c->s_quant, quant); UP(c->s_pair, pair);
+#define UP(group, v)                                                        \
+  do {                                                                      \
+    if ((s = upload(c, group.dev, v)) != PDADMM_OK) return s;               \
+    group.build(group.dev, v, (int)v.size());                               \
+  } while (0)
+  UP(c->g_pgrad, pgrad); UP(c->g_ptrial, ptrial); UP(c->g_wgrad, wgrad); UP(c->g_wtrial, wtrial);
+  UP(c->g_resid, resid); UP(c->g_resid_obj, resid_obj); UP(c->g_red, red);
+  UP(c->g_pstep, pstep); UP(c->g_qapply_r, qapply_r);
+  UP(c->g_w, wseg); UP(c->g_rows_all, rows); UP(c->g_bias, bias); UP(c->g_quant, quant); UP(c->g_pair, pair);
 #undef UP
+  c->g_rows_hidden.build(c->g_rows_all.dev, rows, L - 1);
+  if ((s = upload(c, c->sel_p, sel_p)) != PDADMM_OK) return s;
+  if ((s = upload(c, c->sel_w, sel_w)) != PDADMM_OK) return s;
+  if ((s = upload(c, c->sel_q, sel_q)) != PDADMM_OK) return s;
+  c->fwd = fwd;
   return PDADMM_OK;
 }
 
+// Launch a grouped kernel once per chunk of its table: kernel(table + first entry, block map, args...).
+template <class T, class K, class... Args>
+void launch_group(pdadmm_ctx* c, const Group<T>& g, K kernel, Args... args) {
+  for (size_t k = 0; k < g.maps.size(); ++k) {
+    if (g.maps[k].total <= 0) continue;
+    hipLaunchKernelGGL(kernel, dim3(g.maps[k].total), dim3(256), 0, c->stream, (const T*)(g.dev + g.start[k]),
+                       g.maps[k], args...);
+  }
+}
+
 template <bool KC, class Epi>
-void launch_gemm(pdadmm_ctx* c, const GemmProb* table, int nprob, int blocks, int predicated) {
-  if (blocks <= 0) return;
-  hipLaunchKernelGGL((gemm_kernel<Tile, KC, Epi>), dim3(xcd_padded(blocks, c->panel)), dim3(256), 0, c->stream, table,
-                     nprob, blocks, c->scal, predicated, c->panel);
+void launch_gemm(pdadmm_ctx* c, const Group<GemmProb>& g, int predicated) {
+  for (size_t k = 0; k < g.maps.size(); ++k) {
+    if (g.maps[k].total <= 0) continue;
+    hipLaunchKernelGGL((gemm_kernel<Tile, KC, Epi>), dim3(xcd_padded(g.maps[k].total, c->panel)), dim3(256), 0,
+                       c->stream, (const GemmProb*)(g.dev + g.start[k]), g.maps[k], (const LayerScal*)c->scal,
+                       predicated, c->panel);
+  }
 }
 
 pdadmm_status refresh_residual(pdadmm_ctx* c) {
   // transposed weights, then R = p W^T + b - z for every layer
-  { TIMED(c, kClsRefresh); hipLaunchKernelGGL(w_step_kernel, dim3(c->nb_w), dim3(256), 0, c->stream, c->s_w, c->L, c->scal, 1); }
+  { TIMED(c, kClsRefresh); launch_group(c, c->g_w, w_step_kernel, (const LayerScal*)c->scal, 1); }
   LAUNCH_CHECK(c, "w_step(copy)");
-  { TIMED(c, kClsRefresh); launch_gemm<true, EpiResid>(c, c->t_resid, c->L, c->nb_resid, 0); }
+  { TIMED(c, kClsRefresh); launch_gemm<true, EpiResid>(c, c->g_resid, 0); }
   LAUNCH_CHECK(c, "gemm resid");
   c->dirty = false;
   return PDADMM_OK;
@@ -482,15 +492,15 @@ pdadmm_status phase_p(pdadmm_ctx* c) {
   const int L = c->L;
   if (L < 2) return PDADMM_OK;
   const pdadmm_config& g = c->cfg;
-  { TIMED(c, kClsGemmPGrad); launch_gemm<true, EpiPGrad>(c, c->t_pgrad, L - 1, c->nb_pgrad, 0); }
+  { TIMED(c, kClsGemmPGrad); launch_gemm<true, EpiPGrad>(c, c->g_pgrad, 0); }
   LAUNCH_CHECK(c, "gemm pgrad");
   if (!g.quantize) {
-    { TIMED(c, kClsGemmTrial); launch_gemm<true, EpiStoreNorm>(c, c->t_ptrial, L - 1, c->nb_ptrial, 0); }
+    { TIMED(c, kClsGemmTrial); launch_gemm<true, EpiStoreNorm>(c, c->g_ptrial, 0); }
     LAUNCH_CHECK(c, "gemm ptrial");
     { TIMED(c, kClsSelect); hipLaunchKernelGGL(select_step_kernel, dim3(L - 1), dim3(256), 0, c->stream, c->sel_p, c->scal, 0, g.rho, g.nu,
                        g.bt_eta, g.bt_max_trials, c->err); }
     LAUNCH_CHECK(c, "select tau");
-    { TIMED(c, kClsPStep); hipLaunchKernelGGL(axpy_kernel, dim3(c->nb_pstep), dim3(256), 0, c->stream, c->s_pstep, 2 * (L - 1), c->scal); }
+    { TIMED(c, kClsPStep); launch_group(c, c->g_pstep, axpy_kernel, (const LayerScal*)c->scal); }
     LAUNCH_CHECK(c, "p step");
     return PDADMM_OK;
   }
@@ -504,19 +514,17 @@ pdadmm_status phase_p(pdadmm_ctx* c) {
     bool any = false;
     for (int i = 1; i < L; ++i) any = any || c->h_flags[i] != 0;
     if (!any) break;
-    { TIMED(c, kClsQuantTrial); hipLaunchKernelGGL(quant_trial_kernel, dim3(c->nb_quant), dim3(256), 0, c->stream, c->s_quant, L - 1, c->scal,
-                       c->grid); }
+    { TIMED(c, kClsQuantTrial); launch_group(c, c->g_quant, quant_trial_kernel, (const LayerScal*)c->scal, c->grid); }
     LAUNCH_CHECK(c, "quant trial");
-    { TIMED(c, kClsGemmTrial); launch_gemm<true, EpiStoreNorm>(c, c->t_ptrial, L - 1, c->nb_ptrial, 1); }
+    { TIMED(c, kClsGemmTrial); launch_gemm<true, EpiStoreNorm>(c, c->g_ptrial, 1); }
     LAUNCH_CHECK(c, "gemm qtrial");
     { TIMED(c, kClsSelect); hipLaunchKernelGGL(select_quant_kernel, dim3(L - 1), dim3(256), 0, c->stream, c->sel_q, c->scal, 1, g.rho, g.nu,
                        g.bt_eta, g.bt_max_trials, c->err, c->flags); }
     LAUNCH_CHECK(c, "select quant judge");
   }
-  { TIMED(c, kClsQuantApply); hipLaunchKernelGGL(quant_apply_kernel, dim3(c->nb_quant), dim3(256), 0, c->stream, c->s_quant, L - 1, c->scal,
-                     c->grid); }
+  { TIMED(c, kClsQuantApply); launch_group(c, c->g_quant, quant_apply_kernel, (const LayerScal*)c->scal, c->grid); }
   LAUNCH_CHECK(c, "quant apply");
-  { TIMED(c, kClsQuantApply); hipLaunchKernelGGL(axpy_kernel, dim3(c->nb_qapply_r), dim3(256), 0, c->stream, c->s_qapply_r, L - 1, c->scal); }
+  { TIMED(c, kClsQuantApply); launch_group(c, c->g_qapply_r, axpy_kernel, (const LayerScal*)c->scal); }
   LAUNCH_CHECK(c, "quant apply R");
   return PDADMM_OK;
 }
@@ -524,16 +532,16 @@ pdadmm_status phase_p(pdadmm_ctx* c) {
 pdadmm_status phase_w(pdadmm_ctx* c) {
   const int L = c->L;
   const pdadmm_config& g = c->cfg;
-  { TIMED(c, kClsGemmWGrad); launch_gemm<false, EpiStore>(c, c->t_wgrad, L, c->nb_wgrad, 0); }
+  { TIMED(c, kClsGemmWGrad); launch_gemm<false, EpiStore>(c, c->g_wgrad, 0); }
   LAUNCH_CHECK(c, "gemm wgrad");
-  { TIMED(c, kClsSplitkReduce); hipLaunchKernelGGL(splitk_reduce_kernel, dim3(c->nb_red), dim3(256), 0, c->stream, c->t_red, L); }
+  { TIMED(c, kClsSplitkReduce); launch_group(c, c->g_red, splitk_reduce_kernel); }
   LAUNCH_CHECK(c, "splitk reduce");
-  { TIMED(c, kClsGemmTrial); launch_gemm<true, EpiStoreNorm>(c, c->t_wtrial, L, c->nb_wtrial, 0); }
+  { TIMED(c, kClsGemmTrial); launch_gemm<true, EpiStoreNorm>(c, c->g_wtrial, 0); }
   LAUNCH_CHECK(c, "gemm wtrial");
   { TIMED(c, kClsSelect); hipLaunchKernelGGL(select_step_kernel, dim3(L), dim3(256), 0, c->stream, c->sel_w, c->scal, 1, g.rho, g.nu,
                      g.bt_eta, g.bt_max_trials, c->err); }
   LAUNCH_CHECK(c, "select theta");
-  { TIMED(c, kClsWStep); hipLaunchKernelGGL(w_step_kernel, dim3(c->nb_w), dim3(256), 0, c->stream, c->s_w, L, c->scal, 0); }
+  { TIMED(c, kClsWStep); launch_group(c, c->g_w, w_step_kernel, (const LayerScal*)c->scal, 0); }
   LAUNCH_CHECK(c, "w step");
   return PDADMM_OK;
 }
@@ -564,12 +572,12 @@ pdadmm_status launch_fista(pdadmm_ctx* c) {
 pdadmm_status phase_bzqu(pdadmm_ctx* c) {
   const int L = c->L;
   const pdadmm_config& g = c->cfg;
-  { TIMED(c, kClsResidColsum); hipLaunchKernelGGL(resid_colsum_kernel, dim3(c->nb_rows_all), dim3(256), 0, c->stream, c->s_rows, L, c->scal); }
+  { TIMED(c, kClsResidColsum); launch_group(c, c->g_rows_all, resid_colsum_kernel, (const LayerScal*)c->scal); }
   LAUNCH_CHECK(c, "resid colsum");
-  { TIMED(c, kClsBias); hipLaunchKernelGGL(bias_step_kernel, dim3(c->nb_bias), dim3(256), 0, c->stream, c->s_bias, L); }
+  { TIMED(c, kClsBias); launch_group(c, c->g_bias, bias_step_kernel); }
   LAUNCH_CHECK(c, "bias step");
   if (L > 1) {
-    { TIMED(c, kClsZqu); hipLaunchKernelGGL(zqu_kernel, dim3(c->nb_rows_hidden), dim3(256), 0, c->stream, c->s_rows, L - 1, g.rho, g.nu); }
+    { TIMED(c, kClsZqu); launch_group(c, c->g_rows_hidden, zqu_kernel, g.rho, g.nu); }
     LAUNCH_CHECK(c, "zqu");
   }
   return launch_fista(c);
@@ -822,8 +830,9 @@ pdadmm_status pdadmm_init(pdadmm_ctx** out, const pdadmm_config* cfg, void* work
   if (s != PDADMM_OK) return s;
   // forward-consistent start, layer after layer
   for (int i = 0; i < L; ++i) {
-    hipLaunchKernelGGL((gemm_kernel<Tile, true, EpiForward>), dim3(xcd_padded(c->fwd_blocks[i], c->panel)), dim3(256),
-                       0, c->stream, c->t_fwd + i, 1, c->fwd_blocks[i], c->scal, 0, c->panel);
+    const GemmProb& F = c->fwd[i];
+    hipLaunchKernelGGL((gemm_one_kernel<Tile, true, EpiForward>), dim3(xcd_padded(F.nblk, c->panel)), dim3(256), 0,
+                       c->stream, F, c->panel);
     LAUNCH_CHECK(c, "gemm forward");
   }
   if (cfg->quantize) {
@@ -939,7 +948,7 @@ static pdadmm_status pair_sums(pdadmm_ctx* c, std::vector<double>* act, std::vec
   dl->assign(L, 0.0);
   dq->assign(L, 0.0);
   if (L < 2) return PDADMM_OK;
-  hipLaunchKernelGGL(pair_reduce_kernel, dim3(c->nb_pair), dim3(256), 0, c->stream, c->s_pair, L - 1);
+  launch_group(c, c->g_pair, pair_reduce_kernel);
   LAUNCH_CHECK(c, "pair reduce");
   std::vector<double> h;
   for (int i = 0; i < L - 1; ++i) {
@@ -960,7 +969,7 @@ static pdadmm_status pair_sums(pdadmm_ctx* c, std::vector<double>* act, std::vec
 static pdadmm_status fresh_residual_sums(pdadmm_ctx* c, double* lin, double* drift) {
   pdadmm_status s;
   if (c->dirty && (s = refresh_residual(c)) != PDADMM_OK) return s;
-  launch_gemm<true, EpiResid>(c, c->t_resid_obj, c->L, c->nb_resid, 0);
+  launch_gemm<true, EpiResid>(c, c->g_resid_obj, 0);
   LAUNCH_CHECK(c, "gemm resid objective");
   *lin = 0.0;
   *drift = 0.0;
