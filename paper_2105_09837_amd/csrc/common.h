@@ -13,6 +13,26 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef const float PD_GLOBAL* gcf;
 typedef const f32x4 PD_GLOBAL* gcf4;
 
+// Loads/stores of data that is touched once per pass (arrays far larger than the caches): the
+// nontemporal hint keeps them from displacing the operands the next product kernel re-reads.
+#ifndef PDADMM_STREAM_HINT
+#define PDADMM_STREAM_HINT 1
+#endif
+__device__ __forceinline__ f32x4 stream_load(const f32x4* p) {
+#if PDADMM_STREAM_HINT
+  return __builtin_nontemporal_load(p);
+#else
+  return *p;
+#endif
+}
+__device__ __forceinline__ void stream_store(f32x4* p, f32x4 v) {
+#if PDADMM_STREAM_HINT
+  __builtin_nontemporal_store(v, p);
+#else
+  *p = v;
+#endif
+}
+
 constexpr int kWave = 64;
 constexpr int kXcd = 8;   // MI355X: 8 accelerator dies, workgroups are dealt to them round-robin
 

@@ -31,18 +31,13 @@ __global__ __launch_bounds__(256) void axpy_kernel(const AxpySeg* __restrict__ s
   else if (S.which == kScaleInvTheta) s = sc.inv_theta;
   else s = sc.inv_tau != 0.0f ? -1.0f : 0.0f;
   if (s == 0.0f) return;
-  float4* y = reinterpret_cast<float4*>(S.y);
-  const float4* x = reinterpret_cast<const float4*>(S.x);
-  const size_t stride = (size_t)S.nblk * 256;
-  for (size_t i = (size_t)local * 256 + threadIdx.x; i < S.n4; i += stride) {
-    float4 a = y[i];
-    const float4 b = x[i];
-    a.x -= s * b.x;
-    a.y -= s * b.y;
-    a.z -= s * b.z;
-    a.w -= s * b.w;
-    y[i] = a;
-  }
+  // one float4 group per thread, consecutive blocks own consecutive 4 KiB chunks: a pure stream
+  const size_t i = (size_t)local * 256 + threadIdx.x;
+  if (i >= S.n4) return;
+  f32x4* y = reinterpret_cast<f32x4*>(S.y) + i;
+  const f32x4 a = stream_load(y);
+  const f32x4 b = stream_load(reinterpret_cast<const f32x4*>(S.x) + i);
+  stream_store(y, a - s * b);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -162,46 +157,68 @@ struct RowSeg {
   const float* m;       // column means (b-step), [ld]
   double* colpart;      // [row_blocks][ld]
   int rows, ncols, ld;
+  int cw;               // float4 column groups per block row (power of two, <= 256)
   int col_blocks, row_blocks;
-  int blk0, nblk;
+  int blk0, nblk;       // blocks of the column-sum pass
   int layer;
 };
 
 // R <- R - T/theta and per-block column sums of the new R (b-update, Appendix A 'update b':
 // the minimiser over the broadcast bias subtracts the node-mean of W p + b - z).
+// A block covers kRowsPerBlock rows x (up to) 1024 columns: the 256 threads are laid out as
+// cw column groups (float4) x (256 / cw) rows, cw = the power of two >= ld/4 capped at 256, so that
+// one step of the block reads whole consecutive rows (a contiguous stream).
 __global__ __launch_bounds__(256) void resid_colsum_kernel(const RowSeg* __restrict__ segs, const BlockMap map,
                                                            const LayerScal* __restrict__ scal) {
-  __shared__ double sm[4][64][4];
+  __shared__ double sm[256][4];
   int local;
   const int si = find_group(map, blockIdx.x, &local);
   const RowSeg S = segs[si];
   const float inv = scal[S.layer].inv_theta;
   const int cb = local % S.col_blocks, rb = local / S.col_blocks;
-  const int cq = threadIdx.x & 63, ty = threadIdx.x >> 6;
-  const int col = (cb * 64 + cq) * 4;
+  const int cw = S.cw, rstep = 256 / cw;
+  const int cq = threadIdx.x & (cw - 1), ty = threadIdx.x / cw;
+  const int col = (cb * cw + cq) * 4;
   double a0 = 0, a1 = 0, a2 = 0, a3 = 0;
   if (col < S.ld) {
     const int rend = min(S.rows, (rb + 1) * kRowsPerBlock);
-    for (int r = rb * kRowsPerBlock + ty; r < rend; r += 4) {
-      const size_t i = (size_t)r * S.ld + col;
-      float4 v = *reinterpret_cast<const float4*>(S.R + i);
+    int r = rb * kRowsPerBlock + ty;
+    // two rows in flight per thread
+    for (; r + rstep < rend; r += 2 * rstep) {
+      const size_t i0 = (size_t)r * S.ld + col, i1 = i0 + (size_t)rstep * S.ld;
+      f32x4 v0 = stream_load(reinterpret_cast<const f32x4*>(S.R + i0));
+      f32x4 v1 = stream_load(reinterpret_cast<const f32x4*>(S.R + i1));
       if (inv != 0.0f) {
-        const float4 t = *reinterpret_cast<const float4*>(S.T + i);
-        v.x -= inv * t.x;
-        v.y -= inv * t.y;
-        v.z -= inv * t.z;
-        v.w -= inv * t.w;
-        *reinterpret_cast<float4*>(S.R + i) = v;
+        const f32x4 t0 = stream_load(reinterpret_cast<const f32x4*>(S.T + i0));
+        const f32x4 t1 = stream_load(reinterpret_cast<const f32x4*>(S.T + i1));
+        v0 -= inv * t0;
+        v1 -= inv * t1;
+        stream_store(reinterpret_cast<f32x4*>(S.R + i0), v0);
+        stream_store(reinterpret_cast<f32x4*>(S.R + i1), v1);
       }
-      a0 += v.x; a1 += v.y; a2 += v.z; a3 += v.w;
+      a0 += (double)v0.x + (double)v1.x; a1 += (double)v0.y + (double)v1.y;
+      a2 += (double)v0.z + (double)v1.z; a3 += (double)v0.w + (double)v1.w;
+    }
+    if (r < rend) {
+      const size_t i0 = (size_t)r * S.ld + col;
+      f32x4 v0 = stream_load(reinterpret_cast<const f32x4*>(S.R + i0));
+      if (inv != 0.0f) {
+        v0 -= inv * stream_load(reinterpret_cast<const f32x4*>(S.T + i0));
+        stream_store(reinterpret_cast<f32x4*>(S.R + i0), v0);
+      }
+      a0 += v0.x; a1 += v0.y; a2 += v0.z; a3 += v0.w;
     }
   }
-  sm[ty][cq][0] = a0; sm[ty][cq][1] = a1; sm[ty][cq][2] = a2; sm[ty][cq][3] = a3;
+  sm[threadIdx.x][0] = a0; sm[threadIdx.x][1] = a1; sm[threadIdx.x][2] = a2; sm[threadIdx.x][3] = a3;
   __syncthreads();
   if (ty == 0 && col < S.ld) {
     double* out = S.colpart + (size_t)rb * S.ld + col;
 #pragma unroll
-    for (int k = 0; k < 4; ++k) out[k] = sm[0][cq][k] + sm[1][cq][k] + sm[2][cq][k] + sm[3][cq][k];
+    for (int k = 0; k < 4; ++k) {
+      double t = 0.0;
+      for (int j = 0; j < rstep; ++j) t += sm[j * cw + cq][k];   // fixed order
+      out[k] = t;
+    }
   }
 }
 
@@ -255,42 +272,50 @@ __device__ __forceinline__ float z_closed_form(float s, float q) {
 // (Appendix A 'update z', 'update q', 'update u'):
 //   a = R - m + z_old; z = closed form; R <- a - z;
 //   q = (rho p_{l+1} + u + nu relu(z)) / (rho + nu); r = p_{l+1} - q; u <- u + rho r.
+constexpr int kZquUnroll = 2;   // float4 groups per thread
+
 __global__ __launch_bounds__(256) void zqu_kernel(const RowSeg* __restrict__ segs, const BlockMap map, float rho, float nu) {
   int local;
   const int si = find_group(map, blockIdx.x, &local);
   const RowSeg S = segs[si];
-  const int cb = local % S.col_blocks, rb = local / S.col_blocks;
-  const int cq = threadIdx.x & 63, ty = threadIdx.x >> 6;
-  const int col = (cb * 64 + cq) * 4;
   const float inv_rn = 1.0f / (rho + nu);
-  if (col < S.ld) {
-    const float4 mm = *reinterpret_cast<const float4*>(S.m + col);
-    const int rend = min(S.rows, (rb + 1) * kRowsPerBlock);
-    for (int r = rb * kRowsPerBlock + ty; r < rend; r += 4) {
-      const size_t i = (size_t)r * S.ld + col;
-      const float4 Rv = *reinterpret_cast<const float4*>(S.R + i);
-      const float4 zo = *reinterpret_cast<const float4*>(S.z + i);
-      const float4 qo = *reinterpret_cast<const float4*>(S.q + i);
-      const float4 pn = *reinterpret_cast<const float4*>(S.pnext + i);
-      const float4 uo = *reinterpret_cast<const float4*>(S.u + i);
-      float4 zn, Rn, qn, un;
-#define PDADMM_ZQU(c)                                                     \
-  {                                                                       \
-    const float a = Rv.c - mm.c + zo.c;                                   \
-    const float z = z_closed_form(a + zo.c, qo.c);                        \
-    zn.c = z;                                                             \
-    Rn.c = a - z;                                                         \
-    const float qq = (rho * pn.c + uo.c + nu * fmaxf(z, 0.0f)) * inv_rn;  \
-    const float rr = pn.c - qq;                                           \
-    qn.c = qq;                                                            \
-    un.c = uo.c + rho * rr;                                               \
+  // flat over the [rows, ld] arrays: a block owns 256*kZquUnroll consecutive float4 groups
+  const size_t n4 = (size_t)S.rows * (S.ld / 4);
+  const int ld4 = S.ld / 4;
+  const size_t base = (size_t)local * (256 * kZquUnroll) + threadIdx.x;
+  f32x4 Rv[kZquUnroll], zo[kZquUnroll], qo[kZquUnroll], pn[kZquUnroll], uo[kZquUnroll], mm[kZquUnroll];
+#pragma unroll
+  for (int k = 0; k < kZquUnroll; ++k) {
+    const size_t i = base + (size_t)k * 256;
+    if (i < n4) {
+      Rv[k] = stream_load(reinterpret_cast<const f32x4*>(S.R) + i);
+      zo[k] = stream_load(reinterpret_cast<const f32x4*>(S.z) + i);
+      qo[k] = stream_load(reinterpret_cast<const f32x4*>(S.q) + i);
+      pn[k] = stream_load(reinterpret_cast<const f32x4*>(S.pnext) + i);
+      uo[k] = stream_load(reinterpret_cast<const f32x4*>(S.u) + i);
+      mm[k] = reinterpret_cast<const f32x4*>(S.m)[i % ld4];
+    }
   }
-      PDADMM_ZQU(x) PDADMM_ZQU(y) PDADMM_ZQU(z) PDADMM_ZQU(w)
-#undef PDADMM_ZQU
-      *reinterpret_cast<float4*>(S.z + i) = zn;
-      *reinterpret_cast<float4*>(S.R + i) = Rn;
-      *reinterpret_cast<float4*>(S.q + i) = qn;
-      *reinterpret_cast<float4*>(S.u + i) = un;
+#pragma unroll
+  for (int k = 0; k < kZquUnroll; ++k) {
+    const size_t i = base + (size_t)k * 256;
+    if (i < n4) {
+      f32x4 zn, Rn, qn, un;
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        const float a = Rv[k][c] - mm[k][c] + zo[k][c];
+        const float z = z_closed_form(a + zo[k][c], qo[k][c]);
+        zn[c] = z;
+        Rn[c] = a - z;
+        const float qq = (rho * pn[k][c] + uo[k][c] + nu * fmaxf(z, 0.0f)) * inv_rn;
+        const float rr = pn[k][c] - qq;
+        qn[c] = qq;
+        un[c] = uo[k][c] + rho * rr;
+      }
+      stream_store(reinterpret_cast<f32x4*>(S.z) + i, zn);
+      stream_store(reinterpret_cast<f32x4*>(S.R) + i, Rn);
+      stream_store(reinterpret_cast<f32x4*>(S.q) + i, qn);
+      stream_store(reinterpret_cast<f32x4*>(S.u) + i, un);
     }
   }
 }

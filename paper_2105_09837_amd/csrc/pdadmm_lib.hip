@@ -40,6 +40,11 @@ struct Carver {
 
 inline int round4(int n) { return (n + 3) & ~3; }
 inline int cdiv(int a, int b) { return (a + b - 1) / b; }
+// blocks of a streaming kernel in which every thread owns `per_thread` float4 groups
+inline int chunk_blocks(size_t n4, int per_thread) {
+  const size_t per_block = (size_t)256 * per_thread;
+  return (int)std::max<size_t>((n4 + per_block - 1) / per_block, 1);
+}
 inline int flat_blocks(size_t n4) {
   size_t b = (n4 + 1023) / 1024;
   return (int)std::min<size_t>(std::max<size_t>(b, 1), 2048);
@@ -55,7 +60,7 @@ struct LayerBufs {
   double *part_a, *part_b, *part_c, *colpart, *pairpart;
   int splitk, k_chunk;
   int tiles_in, tiles_out;  // GEMM tiles of [N, n_in] and [N, n_out]
-  int row_blocks, col_blocks;
+  int row_blocks, col_blocks, cw;
 };
 
 // A descriptor table in device memory plus, for every launch chunk of at most kMaxGroup entries,
@@ -67,6 +72,11 @@ struct Group {
   std::vector<int> start;
   int count = 0;
   void build(T* table, const std::vector<T>& v, int n) {
+    build(table, v, n, [](const T& e) { return e.nblk; });
+  }
+  // `blocks_of` gives the number of blocks of an entry (tables shared by kernels of different shapes)
+  template <class F>
+  void build(T* table, const std::vector<T>& v, int n, F blocks_of) {
     dev = table;
     count = n;
     maps.clear();
@@ -77,7 +87,7 @@ struct Group {
       int b = 0;
       for (int j = 0; j < m.n; ++j) {
         m.blk0[j] = b;
-        b += v[s0 + j].nblk;
+        b += blocks_of(v[s0 + j]);
       }
       m.total = b;
       maps.push_back(m);
@@ -237,7 +247,9 @@ size_t plan(pdadmm_ctx* c, void* base) {
     b.tiles_in = cdiv(N, BM) * cdiv(b.n_in, BN);
     b.tiles_out = cdiv(N, BM) * cdiv(b.n_out, BN);
     b.row_blocks = cdiv(N, kRowsPerBlock);
-    b.col_blocks = cdiv(b.ld_out / 4, 64);
+    b.cw = 1;
+    while (b.cw < b.ld_out / 4 && b.cw < 256) b.cw <<= 1;
+    b.col_blocks = cdiv(b.ld_out / 4, b.cw);
     const size_t in_sz = (size_t)N * b.ld_in, out_sz = (size_t)N * b.ld_out;
     b.W = cv.take<float>((size_t)b.n_out * b.ld_in);
     b.Wt = cv.take<float>((size_t)b.n_in * b.ld_out);
@@ -360,10 +372,10 @@ pdadmm_status build_tables(pdadmm_ctx* c) {
       s.part_g = b.part_a; s.ng = P.nblk; s.part_t = b.part_b; s.nt = T.nblk; s.stride_t = 1; s.layer = i;
       sel_p.push_back(s);
       AxpySeg a{};
-      a.y = b.p; a.x = b.g; a.n4 = (size_t)N * b.ld_in / 4; a.nblk = flat_blocks(a.n4); a.layer = i;
+      a.y = b.p; a.x = b.g; a.n4 = (size_t)N * b.ld_in / 4; a.nblk = chunk_blocks(a.n4, 1); a.layer = i;
       a.which = kScaleInvTau;
       AxpySeg r{};
-      r.y = b.R; r.x = b.T; r.n4 = (size_t)N * b.ld_out / 4; r.nblk = flat_blocks(r.n4); r.layer = i;
+      r.y = b.R; r.x = b.T; r.n4 = (size_t)N * b.ld_out / 4; r.nblk = chunk_blocks(r.n4, 1); r.layer = i;
       r.which = kScaleInvTau;
       pstep.push_back(a);
       pstep.push_back(r);
@@ -420,7 +432,8 @@ pdadmm_status build_tables(pdadmm_ctx* c) {
     rs.pnext = i < L - 1 ? c->lay[i + 1].p : nullptr;
     rs.m = b.m; rs.colpart = b.colpart;
     rs.rows = N; rs.ncols = b.n_out; rs.ld = b.ld_out;
-    rs.col_blocks = b.col_blocks; rs.row_blocks = b.row_blocks; rs.nblk = b.col_blocks * b.row_blocks; rs.layer = i;
+    rs.cw = b.cw; rs.col_blocks = b.col_blocks; rs.row_blocks = b.row_blocks; rs.nblk = b.col_blocks * b.row_blocks;
+    rs.layer = i;
     rows.push_back(rs);
     BiasSeg bs{};
     bs.b = b.b; bs.m = b.m; bs.colpart = b.colpart; bs.ncols = b.n_out; bs.ld = b.ld_out;
@@ -450,7 +463,10 @@ pdadmm_status build_tables(pdadmm_ctx* c) {
   UP(c->g_pstep, pstep); UP(c->g_qapply_r, qapply_r);
   UP(c->g_w, wseg); UP(c->g_rows_all, rows); UP(c->g_bias, bias); UP(c->g_quant, quant); UP(c->g_pair, pair);
 #undef UP
-  c->g_rows_hidden.build(c->g_rows_all.dev, rows, L - 1);
+  // the fused z/q/u pass walks the same table flat: 256*kZquUnroll float4 groups per block
+  c->g_rows_hidden.build(c->g_rows_all.dev, rows, L - 1, [](const RowSeg& e) {
+    return chunk_blocks((size_t)e.rows * (e.ld / 4), kZquUnroll);
+  });
   if ((s = upload(c, c->sel_p, sel_p)) != PDADMM_OK) return s;
   if ((s = upload(c, c->sel_w, sel_w)) != PDADMM_OK) return s;
   if ((s = upload(c, c->sel_q, sel_q)) != PDADMM_OK) return s;

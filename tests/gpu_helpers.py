@@ -65,13 +65,39 @@ def round_state_to_fp32(st):
     return st
 
 
-def compare_state(ctx, st, tol, what=""):
-    """Element-wise comparison of every variable; returns the worst relative L2 error and a report."""
+def z_branch_flips(gz, z_ref, a_rows, q_old, z_old, what=""):
+    """Hidden-layer z-update: where the two ReLU candidates of the closed form have (almost) the same
+    subproblem value, rounding decides which one is taken and both are correct minimisers. Returns the
+    mask of elements where the GPU took the other candidate than the oracle, after checking that each
+    such element is such a near-tie (the GPU's value is a minimiser to rounding) and that they are rare.
+    a_rows(rows) must return W p + b (new values) for the given node indices."""
+    rms = float(np.sqrt(np.mean(np.square(z_ref))))
+    cand = np.abs(gz - z_ref) > 1e-3 * (np.abs(z_ref) + rms)
+    n = int(cand.sum())
+    if n == 0:
+        return cand, 0
+    assert n <= max(4, 5e-6 * z_ref.size), f"{what}: {n} of {z_ref.size} z elements far from the oracle"
+    rows, cols = np.nonzero(cand)
+    a = a_rows(rows)[np.arange(rows.size), cols]
+    qo, zo = q_old[rows, cols], z_old[rows, cols]
+    h_gpu = O.z_subproblem_value(gz[rows, cols].astype(F64), a, qo, zo)
+    h_ref = O.z_subproblem_value(z_ref[rows, cols], a, qo, zo)
+    assert np.all(h_gpu <= h_ref + 1e-4 * np.abs(h_ref) + 1e-30), \
+        f"{what}: a differing z element is not a tie of the two candidates: {h_gpu} vs {h_ref}"
+    return cand, n
+
+
+def compare_state(ctx, st, tol, what="", before=None):
+    """Element-wise comparison of every variable; returns the worst relative L2 error and a report.
+    With `before` (the oracle state one iteration earlier) the hidden-layer z, q, u comparisons leave out
+    the rare elements where the z-update hit a tie of its two candidates (see z_branch_flips)."""
     L = st.L
     worst, lines = 0.0, []
 
-    def chk(name, got, ref):
+    def chk(name, got, ref, skip=None):
         nonlocal worst
+        if skip is not None and skip.any():
+            got, ref = got[~skip], ref[~skip]
         e = rel_l2(got, ref)
         worst = max(worst, e)
         lines.append(f"{what} {name}: rel_l2={e:.3e}")
@@ -81,14 +107,19 @@ def compare_state(ctx, st, tol, what=""):
         l = i + 1
         chk(f"W{l}", P.pdadmm_get_var(ctx, P.VAR.W, l), st.W[i])
         chk(f"b{l}", P.pdadmm_get_var(ctx, P.VAR.B, l), st.b[i])
-        chk(f"z{l}", P.pdadmm_get_var(ctx, P.VAR.Z, l), st.z[i])
+        gz = P.pdadmm_get_var(ctx, P.VAR.Z, l)
+        skip = None
+        if before is not None and i < L - 1:
+            skip, n = z_branch_flips(gz, st.z[i], lambda rows: st.p[i][rows] @ st.W[i].T + st.b[i],
+                                     before.q[i], before.z[i], what=f"{what} z{l}")
+            if n:
+                lines.append(f"{what} z{l}: {n} tie elements left out")
+        chk(f"z{l}", gz, st.z[i], skip)
         if i >= 1:
             chk(f"p{l}", P.pdadmm_get_var(ctx, P.VAR.P, l), st.p[i])
         if i < L - 1:
-            chk(f"q{l}", P.pdadmm_get_var(ctx, P.VAR.Q, l), st.q[i])
-            # u is a small difference of O(1) quantities: measure it against the scale of rho*q
-            got_u = P.pdadmm_get_var(ctx, P.VAR.U, l)
-            chk(f"u{l}", got_u, st.u[i])
+            chk(f"q{l}", P.pdadmm_get_var(ctx, P.VAR.Q, l), st.q[i], skip)
+            chk(f"u{l}", P.pdadmm_get_var(ctx, P.VAR.U, l), st.u[i], skip)
     ok = worst <= tol
     return ok, worst, "\n".join(lines)
 

@@ -78,3 +78,44 @@ def perturb_state(w: Workload, z, q, quantizer=None, scale: float = 0.1):
             p_out.append(pl.astype(np.float32, copy=False))
             u_out.append(ul.astype(np.float32, copy=False))
     return z_out, q_out, p_out, u_out
+
+
+S_WINDOW = 100     # stream id base of the per-layer windows below (plus the layer number)
+
+
+def layer_window(w: Workload, layer: int, quantizer=None, scale: float = 0.5):
+    """Seeded generic (not forward-consistent) values for everything one iteration reads or writes
+    around layer l = `layer` (1-based): the layer's own variables, the q/u of the layer below and the
+    W/b/z/p of the layer above (whose p-update feeds this layer's q- and u-update). Plain noise with
+    plausible signs and magnitudes; `quantizer` (the caller's projection) is applied to every p.
+    Keys are named after the paper's variables; absent neighbours (l = 1, l = L) are left out."""
+    rng = stream_rng(w, S_WINDOW + layer)
+    dims, N, L = w.dims, w.n_nodes, w.n_layers
+    s = np.float32(scale)
+    nu = np.float32(w.nu)
+
+    def weights(n_out, n_in):
+        return rng.standard_normal((n_out, n_in), dtype=np.float32) * np.float32(np.sqrt(2.0 / n_in))
+
+    def act(n):          # non-negative, like an activation
+        a = np.abs(noise_like(rng, (N, n))) * s
+        return quantizer(a).astype(np.float32, copy=False) if quantizer is not None else a
+
+    out = {}
+    n_in, n_out = dims[layer - 1], dims[layer]
+    out["W"] = weights(n_out, n_in)
+    out["b"] = noise_like(rng, (n_out,)) * np.float32(0.1)
+    out["z"] = noise_like(rng, (N, n_out)) * s
+    if layer >= 2:
+        out["p"] = act(n_in)
+        out["q_prev"] = np.abs(noise_like(rng, (N, n_in))) * s
+        out["u_prev"] = noise_like(rng, (N, n_in)) * (np.float32(0.1) * nu)
+    if layer < L:
+        out["q"] = np.abs(noise_like(rng, (N, n_out))) * s
+        out["u"] = noise_like(rng, (N, n_out)) * (np.float32(0.1) * nu)
+        n_next = dims[layer + 1]
+        out["W_next"] = weights(n_next, n_out)
+        out["b_next"] = noise_like(rng, (n_next,)) * np.float32(0.1)
+        out["z_next"] = noise_like(rng, (N, n_next)) * s
+        out["p_next"] = act(n_out)
+    return out
