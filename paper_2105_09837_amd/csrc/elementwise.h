@@ -142,10 +142,9 @@ __global__ __launch_bounds__(256) void w_step_kernel(const WStepSeg* __restrict_
 }
 
 // ------------------------------------------------------------------------------------------
-// Row-structured passes over [rows, ld] arrays. A block covers 128 rows x 256 columns:
-// thread (ty = wave, cq = lane) owns one float4 column group and walks rows ty, ty+4, ...
+// Row-structured passes over [rows, ld] arrays (blocks of kRowsPerBlock rows).
 // ------------------------------------------------------------------------------------------
-constexpr int kRowsPerBlock = 128;
+constexpr int kRowsPerBlock = 32;
 
 struct RowSeg {
   float* R;             // carried residual W p + b - z
@@ -182,31 +181,29 @@ __global__ __launch_bounds__(256) void resid_colsum_kernel(const RowSeg* __restr
   double a0 = 0, a1 = 0, a2 = 0, a3 = 0;
   if (col < S.ld) {
     const int rend = min(S.rows, (rb + 1) * kRowsPerBlock);
-    int r = rb * kRowsPerBlock + ty;
-    // two rows in flight per thread
-    for (; r + rstep < rend; r += 2 * rstep) {
-      const size_t i0 = (size_t)r * S.ld + col, i1 = i0 + (size_t)rstep * S.ld;
-      f32x4 v0 = stream_load(reinterpret_cast<const f32x4*>(S.R + i0));
-      f32x4 v1 = stream_load(reinterpret_cast<const f32x4*>(S.R + i1));
-      if (inv != 0.0f) {
-        const f32x4 t0 = stream_load(reinterpret_cast<const f32x4*>(S.T + i0));
-        const f32x4 t1 = stream_load(reinterpret_cast<const f32x4*>(S.T + i1));
-        v0 -= inv * t0;
-        v1 -= inv * t1;
-        stream_store(reinterpret_cast<f32x4*>(S.R + i0), v0);
-        stream_store(reinterpret_cast<f32x4*>(S.R + i1), v1);
+    // four rows in flight per thread
+    for (int r = rb * kRowsPerBlock + ty; r < rend; r += 4 * rstep) {
+      f32x4 v[4], t[4];
+      bool on[4];
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        on[k] = r + k * rstep < rend;
+        const size_t i = (size_t)(r + k * rstep) * S.ld + col;
+        if (on[k]) {
+          v[k] = stream_load(reinterpret_cast<const f32x4*>(S.R + i));
+          if (inv != 0.0f) t[k] = stream_load(reinterpret_cast<const f32x4*>(S.T + i));
+        }
       }
-      a0 += (double)v0.x + (double)v1.x; a1 += (double)v0.y + (double)v1.y;
-      a2 += (double)v0.z + (double)v1.z; a3 += (double)v0.w + (double)v1.w;
-    }
-    if (r < rend) {
-      const size_t i0 = (size_t)r * S.ld + col;
-      f32x4 v0 = stream_load(reinterpret_cast<const f32x4*>(S.R + i0));
-      if (inv != 0.0f) {
-        v0 -= inv * stream_load(reinterpret_cast<const f32x4*>(S.T + i0));
-        stream_store(reinterpret_cast<f32x4*>(S.R + i0), v0);
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        if (on[k]) {
+          if (inv != 0.0f) {
+            v[k] -= inv * t[k];
+            stream_store(reinterpret_cast<f32x4*>(S.R + (size_t)(r + k * rstep) * S.ld + col), v[k]);
+          }
+          a0 += (double)v[k].x; a1 += (double)v[k].y; a2 += (double)v[k].z; a3 += (double)v[k].w;
+        }
       }
-      a0 += v0.x; a1 += v0.y; a2 += v0.z; a3 += v0.w;
     }
   }
   sm[threadIdx.x][0] = a0; sm[threadIdx.x][1] = a1; sm[threadIdx.x][2] = a2; sm[threadIdx.x][3] = a3;

@@ -231,7 +231,9 @@ __device__ __forceinline__ void gemm_body(const GemmProb& P, const int local) {
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
 
-  // MFMAs of one staged tile; the fragments of k-step kk+2 are fetched before the MFMAs of kk issue
+  // MFMAs of one staged tile. The fragments of k-step kk+2 are fetched from LDS before the MFMAs of
+  // k-step kk issue; the scheduling barriers keep that order (left alone, the compiler folds both
+  // fragment sets into one register set and waits for every LDS read right before its MFMAs).
   auto compute_tile = [&](int cur, auto&& mid) {
     float a[2][TM], b[2][TN];
 #pragma unroll
@@ -247,18 +249,24 @@ __device__ __forceinline__ void gemm_body(const GemmProb& P, const int local) {
 #pragma unroll
         for (int j = 0; j < TN; ++j) b[n][j] = Bs[cur][kk + 2 + lh][wn * (BN / Cfg::WN) + j * 32 + li];
       }
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[c][i], b[c][j], acc[i][j], 0, 0, 0);
       if (kk == (BK / 2 & ~1)) mid();   // LDS store of the next tile rides in the shadow of the MFMAs
+      __builtin_amdgcn_sched_barrier(0);
     }
   };
   auto nothing = [] {};
 
   // Main loop with two register sets: the global loads of tile t+2 are issued before the MFMAs of
   // tile t, the LDS store of tile t+1 (loaded one tile earlier) follows them, one barrier per tile.
+  // Loads and stores past the last tile are issued all the same (addresses are clamped into the
+  // matrix, out-of-range k is stored as zero, the buffer written is never read): with no branch
+  // around them the compiler knows exactly how many loads are in flight when a register set is
+  // consumed and waits for that set only, not for the loads it has just issued.
   auto main_loop = [&](auto fast_tag) {
     constexpr bool FAST = decltype(fast_tag)::value;
     f32x4 ra0[NVA], rb0[NVB], ra1[NVA], rb1[NVB];
@@ -273,18 +281,18 @@ __device__ __forceinline__ void gemm_body(const GemmProb& P, const int local) {
       store_operand<KCONTIG, FAST, BN, BK, LDB, NVB>(Bs[buf], rb, kb, kend, tid);
     };
     load_tile(0, ra0, rb0);
-    if (nkt > 1) load_tile(1, ra1, rb1);
+    load_tile(1, ra1, rb1);
     store_tile(0, 0, ra0, rb0);
     __syncthreads();
     int kt = 0;
     for (; kt + 1 < nkt; kt += 2) {
       // even tile: LDS buffer 0 is current, set 1 holds tile kt+1, set 0 is free
-      if (kt + 2 < nkt) load_tile(kt + 2, ra0, rb0);
+      load_tile(kt + 2, ra0, rb0);
       compute_tile(0, [&] { store_tile(kt + 1, 1, ra1, rb1); });
       __syncthreads();
       // odd tile: LDS buffer 1 is current, set 0 holds tile kt+2, set 1 is free
-      if (kt + 3 < nkt) load_tile(kt + 3, ra1, rb1);
-      compute_tile(1, [&] { if (kt + 2 < nkt) store_tile(kt + 2, 0, ra0, rb0); });
+      load_tile(kt + 3, ra1, rb1);
+      compute_tile(1, [&] { store_tile(kt + 2, 0, ra0, rb0); });
       __syncthreads();
     }
     if (kt < nkt) compute_tile(0, nothing);   // odd tile count: the last tile sits in buffer 0

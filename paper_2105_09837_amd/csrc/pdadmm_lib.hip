@@ -19,6 +19,9 @@ using namespace pdadmm;
 // Tile shape of the dense products (see gemm.h).
 using Tile = TileCfg<128, 128, 16, 2, 2>;
 constexpr int BM = Tile::BM, BN = Tile::BN, BK = Tile::BK;
+// Product blocks resident on the chip at once: 256 compute units x 3 blocks (one wave per SIMD each,
+// 164 registers per lane).
+constexpr int kGemmSlots = 256 * 3;
 
 namespace {
 
@@ -229,13 +232,34 @@ size_t plan(pdadmm_ctx* c, void* base) {
   const int N = c->N, L = c->L;
   const bool Q = c->cfg.quantize != 0;
   c->lay.assign(L, LayerBufs{});
-  // split-K plan for the W-gradient products: equal rows of nodes per block across layers
-  size_t tile_rows = 0;
-  for (int i = 0; i < L; ++i) tile_rows += (size_t)cdiv(c->dims[i + 1], BM) * cdiv(c->dims[i], BN) * N;
-  const size_t want_blocks = 1536;
-  int chunk = (int)std::max<size_t>(256, tile_rows / want_blocks);
-  chunk = std::min(chunk, N);
-  chunk = cdiv(chunk, BK) * BK;
+  // Split plan of the W-gradient products (contraction over the nodes): every 128x128 output tile of
+  // every layer is cut into the same number of node chunks, so all blocks of the grouped launch take
+  // the same time. The chip holds kGemmSlots product blocks at once (MI355X: 256 CUs x 3 blocks, set
+  // by the kernel's register use); the number of chunks is chosen so that the blocks fill whole
+  // rounds of that many as exactly as possible, while a block still runs long enough to amortise
+  // its start-up (about 1.6 k-tiles, measured).
+  size_t tiles_total = 0;
+  for (int i = 0; i < L; ++i) tiles_total += (size_t)cdiv(c->dims[i + 1], BM) * cdiv(c->dims[i], BN);
+  int chunk = cdiv(N, BK) * BK;
+  {
+    double best = -1.0;
+    for (int rounds = 1; rounds <= 12; ++rounds) {
+      const long want = (long)rounds * kGemmSlots / (long)tiles_total;
+      if (want < 1) continue;
+      const int sk = (int)std::min<long>(want, 64);
+      int ch = cdiv(cdiv(N, sk), BK) * BK;
+      ch = std::max(ch, std::min(256, cdiv(N, BK) * BK));
+      const int parts = cdiv(N, ch);
+      const double blocks = (double)tiles_total * parts;
+      const double fill = blocks / (std::ceil(blocks / kGemmSlots) * kGemmSlots);
+      const double nkt = (double)ch / BK;
+      const double eff = fill * nkt / (nkt + 1.6) - 1e-3 * parts;   // small bias towards fewer partial sums
+      if (eff > best) {
+        best = eff;
+        chunk = ch;
+      }
+    }
+  }
   for (int i = 0; i < L; ++i) {
     LayerBufs& b = c->lay[i];
     b.n_in = c->dims[i];

@@ -65,14 +65,16 @@ def round_state_to_fp32(st):
     return st
 
 
-def z_branch_flips(gz, z_ref, a_rows, q_old, z_old, what=""):
+def z_branch_flips(gz, z_ref, a_rows, q_old, z_old, what="", far=1e-3, h_tol=1e-4):
     """Hidden-layer z-update: where the two ReLU candidates of the closed form have (almost) the same
     subproblem value, rounding decides which one is taken and both are correct minimisers. Returns the
     mask of elements where the GPU took the other candidate than the oracle, after checking that each
     such element is such a near-tie (the GPU's value is a minimiser to rounding) and that they are rare.
-    a_rows(rows) must return W p + b (new values) for the given node indices."""
+    a_rows(rows) must return W p + b (new values) for the given node indices. `far` is the relative
+    distance from which an element counts as differing, `h_tol` the relative slack of the subproblem value
+    (both are widened for -Q, where a one-level flip in p shifts W p + b of a whole row slightly)."""
     rms = float(np.sqrt(np.mean(np.square(z_ref))))
-    cand = np.abs(gz - z_ref) > 1e-3 * (np.abs(z_ref) + rms)
+    cand = np.abs(gz - z_ref) > far * (np.abs(z_ref) + rms)
     n = int(cand.sum())
     if n == 0:
         return cand, 0
@@ -82,7 +84,7 @@ def z_branch_flips(gz, z_ref, a_rows, q_old, z_old, what=""):
     qo, zo = q_old[rows, cols], z_old[rows, cols]
     h_gpu = O.z_subproblem_value(gz[rows, cols].astype(F64), a, qo, zo)
     h_ref = O.z_subproblem_value(z_ref[rows, cols], a, qo, zo)
-    assert np.all(h_gpu <= h_ref + 1e-4 * np.abs(h_ref) + 1e-30), \
+    assert np.all(h_gpu <= h_ref + h_tol * np.abs(h_ref) + 1e-30), \
         f"{what}: a differing z element is not a tie of the two candidates: {h_gpu} vs {h_ref}"
     return cand, n
 

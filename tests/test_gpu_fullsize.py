@@ -246,7 +246,8 @@ def test_full_size_sampled_layer_one_iteration(env, say, name, layer):
         # elements where the two candidates of the closed form tie (both are minimisers) are left out
         skip, n_tie = H.z_branch_flips(P.pdadmm_get_var(ctx, V.Z, layer), st.z[i],
                                        lambda rows: st.p[i][rows] @ st.W[i].T + st.b[i], q_old, z_old,
-                                       what=f"{name} z_{layer}")
+                                       what=f"{name} z_{layer}", far=1e-3 if g is None else 2e-2,
+                                       h_tol=1e-4 if g is None else 1e-2)
         say(f"  z_{layer}: {n_tie} tie elements of {st.z[i].size} left out")
         check(f"z_{layer}", V.Z, layer, st.z[i], loose, skip)
         O.update_q(st, i)
