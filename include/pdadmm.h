@@ -175,6 +175,18 @@ pdadmm_status pdadmm_objective(pdadmm_ctx* ctx, pdadmm_objective_terms* out);
  * per-layer norms (HOST). Synchronises. */
 pdadmm_status pdadmm_residual(pdadmm_ctx* ctx, double* total, double* per_layer);
 
+/*
+ * Forward pass of the model with the current W_l, b_l (Problem 1, Section 3.1: p_1 = X,
+ * p_{l+1} = f(W_l p_l + b_l), output W_L p_L + b_L) and the class it predicts per node, the first
+ * maximum of the output row. The ADMM variables are not touched; the pass runs through the product
+ * scratch of the iteration, so it must not be called between the phases of pdadmm_step_phase.
+ *  pred:   DEVICE int32 [N] or NULL; logits: DEVICE fp32 [N, n_L] dense or NULL;
+ *  mask:   DEVICE uint8 [N] or NULL: nodes counted for the accuracy (NULL = every node);
+ *  accuracy: HOST or NULL: share of counted nodes whose prediction equals the label given at init.
+ * Synchronises.
+ */
+pdadmm_status pdadmm_predict(pdadmm_ctx* ctx, int32_t* pred, float* logits, const uint8_t* mask, double* accuracy);
+
 /* HOST outputs, each L entries or NULL: tau_l (entry 0 unused), theta_l, trials used by the last
  * p- and W-update. r_drift (or NULL): relative L2 distance between the carried and a freshly
  * computed W_l p_l + b_l - z_l over all layers. Synchronises. */

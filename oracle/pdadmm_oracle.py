@@ -386,6 +386,33 @@ def iterate(st: State, n_iters: int = 1) -> None:
 
 
 # --------------------------------------------------------------------------------------
+# The model itself (Section 3.1, Problem 1): used to score a trained W, b
+# --------------------------------------------------------------------------------------
+def forward(st: State) -> np.ndarray:
+    """Output layer of the GA-MLP for the current weights: p_1 = X, p_{l+1} = f(W_l p_l + b_l) for
+    l < L, result W_L p_L + b_L (node-major [|V|, n_L]). The ADMM variables p, z, q are not used."""
+    a = st.p[0]
+    for i in range(st.L):
+        z = a @ st.W[i].T + st.b[i]
+        a = relu(z)
+    return z
+
+
+def predict(st: State):
+    """Predicted class per node (first maximum of the output row) and the output layer."""
+    out = forward(st)
+    return np.argmax(out, axis=1).astype(np.int32), out
+
+
+def accuracy(pred, y, mask=None) -> float:
+    """Share of the counted nodes (mask, or all) whose prediction equals the label."""
+    hit = np.asarray(pred) == np.asarray(y)
+    if mask is not None:
+        hit = hit[np.asarray(mask, dtype=bool)]
+    return float(hit.mean()) if hit.size else 0.0
+
+
+# --------------------------------------------------------------------------------------
 # Objective and residual (Section 3.2, Algorithm 1)
 # --------------------------------------------------------------------------------------
 def objective(st: State) -> dict:

@@ -43,7 +43,7 @@ class _CObjective(C.Structure):
 
 EXPORTS = ["pdadmm_normalize_adj", "pdadmm_augment", "pdadmm_quantize", "pdadmm_gemm_nt", "pdadmm_gemm_tn",
            "pdadmm_workspace_bytes", "pdadmm_init", "pdadmm_set_var", "pdadmm_get_var", "pdadmm_iterate",
-           "pdadmm_step_phase", "pdadmm_sync", "pdadmm_objective", "pdadmm_residual", "pdadmm_stats",
+           "pdadmm_step_phase", "pdadmm_sync", "pdadmm_objective", "pdadmm_residual", "pdadmm_stats", "pdadmm_predict",
            "pdadmm_timing", "pdadmm_timing_read", "pdadmm_last_error", "pdadmm_destroy"]
 
 
@@ -83,6 +83,7 @@ def load_library():
     lib.pdadmm_objective.argtypes = [vp, C.POINTER(_CObjective)]
     lib.pdadmm_residual.argtypes = [vp, C.POINTER(C.c_double), vp]
     lib.pdadmm_stats.argtypes = [vp, vp, vp, vp, vp, vp]
+    lib.pdadmm_predict.argtypes = [vp, vp, vp, vp, vp]
     lib.pdadmm_timing.argtypes = [vp, C.c_uint32]
     lib.pdadmm_timing_read.argtypes = [vp, vp, vp, i32]
     lib.pdadmm_last_error.argtypes = [vp]
@@ -348,6 +349,22 @@ def pdadmm_stats(ctx: Context, drift: bool = False) -> dict:
     _check(load_library().pdadmm_stats(ctx.handle, tau.ctypes.data, theta.ctypes.data, pt.ctypes.data,
                                        wt.ctypes.data, C.addressof(d) if drift else None), "pdadmm_stats", ctx)
     return dict(tau=tau, theta=theta, p_trials=pt, w_trials=wt, r_drift=d.value if drift else None)
+
+
+def pdadmm_predict(ctx: Context, mask=None, want_logits: bool = False) -> dict:
+    """Forward pass with the current weights: predicted class per node (device int32 tensor), accuracy
+    over the nodes of `mask` (device uint8 tensor or None = all) and optionally the output layer."""
+    import torch
+    dev = ctx.workspace.device
+    pred = torch.empty(ctx.N, dtype=torch.int32, device=dev)
+    logits = torch.empty((ctx.N, ctx.dims[-1]), dtype=torch.float32, device=dev) if want_logits else None
+    acc = C.c_double(0.0)
+    if mask is not None and not (isinstance(mask, torch.Tensor) and mask.is_cuda and mask.dtype == torch.uint8
+                                 and mask.numel() == ctx.N and mask.is_contiguous()):
+        raise PdadmmError(1, "pdadmm_predict", "mask must be a contiguous uint8 device tensor of N entries")
+    _check(load_library().pdadmm_predict(ctx.handle, _ptr(pred), _ptr(logits), _ptr(mask), C.addressof(acc)),
+           "pdadmm_predict", ctx)
+    return dict(pred=pred, accuracy=acc.value, logits=logits)
 
 
 TIMING_CLASSES = ["gemm_pgrad", "gemm_trial", "gemm_wgrad", "splitk_reduce", "select", "p_step", "w_step",

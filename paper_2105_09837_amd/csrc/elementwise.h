@@ -612,4 +612,34 @@ __global__ __launch_bounds__(256) void risk_kernel(const float* __restrict__ z, 
   if (threadIdx.x == 0) part[blockIdx.x] = t;
 }
 
+// Predicted class per node = first maximum of the output layer's row; per block the number of
+// counted nodes (mask != 0, or all) and of those the number whose prediction equals the label.
+__global__ __launch_bounds__(256) void argmax_kernel(const float* __restrict__ z, int rows, int C, int ld,
+                                                     const int* __restrict__ y, const uint8_t* __restrict__ mask,
+                                                     int* __restrict__ pred, double* __restrict__ part) {
+  __shared__ double red[4];
+  const int node = blockIdx.x * 256 + threadIdx.x;
+  double counted = 0.0, correct = 0.0;
+  if (node < rows) {
+    const float* zr = z + (size_t)node * ld;
+    int best = 0;
+    float bv = zr[0];
+    for (int c = 1; c < C; ++c) {
+      const float v = zr[c];
+      if (v > bv) { bv = v; best = c; }
+    }
+    if (pred) pred[node] = best;
+    if (!mask || mask[node]) {
+      counted = 1.0;
+      correct = best == y[node] ? 1.0 : 0.0;
+    }
+  }
+  const double t0 = block_sum_256(counted, red);
+  const double t1 = block_sum_256(correct, red);
+  if (threadIdx.x == 0) {
+    part[2 * blockIdx.x] = t0;
+    part[2 * blockIdx.x + 1] = t1;
+  }
+}
+
 }  // namespace pdadmm

@@ -91,6 +91,15 @@ struct EpiForward {   // z = acc + b[col]; q = relu(z); p_next = relu(z) (projec
   }
 };
 
+struct EpiBiasAct {   // C = acc + b[col], passed through ReLU when beta != 0 (forward pass of the model, Problem 1)
+  static constexpr int NS = 0;
+  __device__ static __forceinline__ void apply(const GemmProb& P, float* C, int row, int col, float acc,
+                                               double&, double&) {
+    const float v = acc + P.e0[col];
+    ((float PD_GLOBAL*)C)[(size_t)row * P.ldc + col] = P.beta != 0.0f ? fmaxf(v, 0.0f) : v;
+  }
+};
+
 // Tile configuration: block tile BM x BN x BK, 4 waves arranged WM x WN, each wave owns
 // (BM/WM) x (BN/WN) as a grid of 32x32 MFMA blocks.
 template <int BM_, int BN_, int BK_, int WM_, int WN_>

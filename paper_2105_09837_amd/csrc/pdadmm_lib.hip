@@ -114,6 +114,7 @@ struct pdadmm_ctx {
   int* labels = nullptr;
   uint8_t* mask = nullptr;
   double* riskpart = nullptr;
+  double* predpart = nullptr;   // per block: counted nodes, correct predictions
   int risk_blocks = 0;
   QuantGrid grid{0.f, 0.f, 0};
   // descriptor tables in device memory, each with the block maps of its launches
@@ -128,6 +129,7 @@ struct pdadmm_ctx {
   Group<QuantSeg> g_quant;
   Group<PairSeg> g_pair;
   int panel = 4;              // tiles per die-local panel in the grouped product launches
+  int panel_tn = 16;          // the same for the W-gradient products (all tiles of one node chunk)
   bool dirty = true;
   long iter = 0;
   std::string msg;
@@ -310,6 +312,7 @@ size_t plan(pdadmm_ctx* c, void* base) {
   c->mask = cv.take<uint8_t>(N);
   c->risk_blocks = cdiv(N, 256);
   c->riskpart = cv.take<double>(c->risk_blocks);
+  c->predpart = cv.take<double>(2 * (size_t)c->risk_blocks);
   c->g_pgrad.dev = cv.take<GemmProb>(L);
   c->g_ptrial.dev = cv.take<GemmProb>(L);
   c->g_wgrad.dev = cv.take<GemmProb>(L);
@@ -475,6 +478,10 @@ pdadmm_status build_tables(pdadmm_ctx* c) {
     // node-major operand), clamped to 1..8
     const int typical = c->dims[std::min(1, L)];
     c->panel = std::max(1, std::min(8, cdiv(typical, BN)));
+    // W-gradient products: all output tiles of one node chunk read the same two operand panels, so the
+    // whole chunk goes to one die (its tiles run together and share the panels through that die's L2)
+    c->panel_tn = std::max(1, std::min(64, cdiv(typical, BM) * cdiv(typical, BN)));
+
   }
   pdadmm_status s;
 #define UP(group, v)                                                        \
@@ -510,11 +517,12 @@ void launch_group(pdadmm_ctx* c, const Group<T>& g, K kernel, Args... args) {
 
 template <bool KC, class Epi>
 void launch_gemm(pdadmm_ctx* c, const Group<GemmProb>& g, int predicated) {
+  const int panel = KC ? c->panel : c->panel_tn;
   for (size_t k = 0; k < g.maps.size(); ++k) {
     if (g.maps[k].total <= 0) continue;
-    hipLaunchKernelGGL((gemm_kernel<Tile, KC, Epi>), dim3(xcd_padded(g.maps[k].total, c->panel)), dim3(256), 0,
+    hipLaunchKernelGGL((gemm_kernel<Tile, KC, Epi>), dim3(xcd_padded(g.maps[k].total, panel)), dim3(256), 0,
                        c->stream, (const GemmProb*)(g.dev + g.start[k]), g.maps[k], (const LayerScal*)c->scal,
-                       predicated, c->panel);
+                       predicated, panel);
   }
 }
 
@@ -1084,6 +1092,42 @@ pdadmm_status pdadmm_stats(pdadmm_ctx* c, double* tau, double* theta, int32_t* p
     *r_drift = lin > 0 ? std::sqrt(drift / lin) : std::sqrt(drift);
   }
   return check_device_flags(c);
+}
+
+pdadmm_status pdadmm_predict(pdadmm_ctx* c, int32_t* pred, float* logits, const uint8_t* mask, double* accuracy) {
+  if (!c) return PDADMM_EINVAL;
+  const int N = c->N, L = c->L;
+  // forward pass through the current W_l, b_l; activations go through the per-layer product scratch
+  const float* in = c->lay[0].p;
+  int ld_in = c->lay[0].ld_in;
+  for (int i = 0; i < L; ++i) {
+    const LayerBufs& b = c->lay[i];
+    GemmProb F = make_nt(in, ld_in, b.W, b.ld_in, b.T, b.ld_out, N, b.n_out, b.n_in);
+    F.e0 = b.b;
+    F.beta = i < L - 1 ? 1.0f : 0.0f;   // ReLU on every layer but the output layer
+    hipLaunchKernelGGL((gemm_one_kernel<Tile, true, EpiBiasAct>), dim3(xcd_padded(F.nblk, c->panel)), dim3(256), 0,
+                       c->stream, F, c->panel);
+    LAUNCH_CHECK(c, "gemm predict");
+    in = b.T;
+    ld_in = b.ld_out;
+  }
+  const LayerBufs& bl = c->lay[L - 1];
+  hipLaunchKernelGGL(argmax_kernel, dim3(c->risk_blocks), dim3(256), 0, c->stream, (const float*)bl.T, N, bl.n_out,
+                     bl.ld_out, (const int*)c->labels, mask, pred, c->predpart);
+  LAUNCH_CHECK(c, "argmax");
+  if (logits)
+    HIP_TRY(c, hipMemcpy2DAsync(logits, (size_t)bl.n_out * 4, bl.T, (size_t)bl.ld_out * 4, (size_t)bl.n_out * 4, N,
+                                hipMemcpyDeviceToDevice, c->stream));
+  std::vector<double> h;
+  pdadmm_status s = sum_partials(c, c->predpart, 2 * (size_t)c->risk_blocks, &h);
+  if (s != PDADMM_OK) return s;
+  double counted = 0, correct = 0;
+  for (int k = 0; k < c->risk_blocks; ++k) {
+    counted += h[2 * k];
+    correct += h[2 * k + 1];
+  }
+  if (accuracy) *accuracy = counted > 0 ? correct / counted : 0.0;
+  return PDADMM_OK;
 }
 
 pdadmm_status pdadmm_timing(pdadmm_ctx* c, uint32_t class_mask) {

@@ -149,22 +149,3 @@ def oracle_phase(st, phase):
             O.update_q(st, i)
         for i in range(L - 1):
             O.update_u(st, i)
-
-
-def pull_state(ctx, like):
-    """Oracle State holding the GPU's current variables (fp32 values widened to fp64)."""
-    st = like.copy()
-    tau, theta, _, _ = step_sizes(ctx)
-    for i in range(st.L):
-        l = i + 1
-        st.W[i] = P.pdadmm_get_var(ctx, P.VAR.W, l).astype(F64)
-        st.b[i] = P.pdadmm_get_var(ctx, P.VAR.B, l).astype(F64)
-        st.z[i] = P.pdadmm_get_var(ctx, P.VAR.Z, l).astype(F64)
-        if i >= 1:
-            st.p[i] = P.pdadmm_get_var(ctx, P.VAR.P, l).astype(F64)
-            st.tau[i] = float(tau[i])
-        if i < st.L - 1:
-            st.q[i] = P.pdadmm_get_var(ctx, P.VAR.Q, l).astype(F64)
-            st.u[i] = P.pdadmm_get_var(ctx, P.VAR.U, l).astype(F64)
-        st.theta[i] = float(theta[i])
-    return st

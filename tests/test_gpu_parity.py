@@ -268,19 +268,21 @@ def test_trajectories(env, case, iters):
     assert s["r_drift"] < 1e-4
 
 
-def test_quantized_trajectory_every_step_is_an_oracle_step(env):
-    """pdADMM-G-Q over 20 iterations with the oracle shadowing the GPU: before each GPU iteration its state
-    is copied into the oracle, both take one iteration, and the results must agree (indices up to
-    isolated one-level flips at midpoints, step sizes exactly, objective and residual within 1e-3).
-    This shows that every step of the GPU's own trajectory is a valid step of the method."""
+def test_quantized_trajectory_step_by_step_along_the_oracle_run(env):
+    """pdADMM-G-Q over 20 iterations, one step at a time: the oracle runs its own trajectory (its state
+    rounded to fp32 after every iteration); before each iteration that state is copied to the GPU, both
+    take one iteration, and the results must agree (indices up to isolated one-level flips at midpoints,
+    step sizes exactly, objective and residual within 1e-3). Free-running -Q runs drift apart once a
+    flipped index changes a backtracking decision (see test_trajectories); this shows that every step of
+    the GPU is the oracle's step from the same starting values, all the way along the run."""
     torch, P, H = env
     w = CASES["C5-small"]()
     inp = oracle_inputs(w)
-    st0 = H.round_state_to_fp32(oracle_state(w, inp))
-    ctx = H.gpu_context(w, inp, st0)
+    st = H.round_state_to_fp32(oracle_state(w, inp))
+    ctx = H.gpu_context(w, inp, st)
     total_bad = 0
     for k in range(20):
-        st = H.pull_state(ctx, st0)
+        H.push_state(ctx, st)
         O.iterate(st)
         P.pdadmm_iterate(ctx, 1)
         P.pdadmm_sync(ctx)
@@ -288,7 +290,7 @@ def test_quantized_trajectory_every_step_is_an_oracle_step(env):
         total_bad += bad
         assert bad <= max(3, 3e-5 * total), (k, bad, total)
         _check_step_sizes(H, ctx, st)
-        ok, worst, rep = H.compare_state(ctx, st, 2e-3, what=f"shadow it {k + 1}")
+        ok, worst, rep = H.compare_state(ctx, st, 2e-3, what=f"step {k + 1}")
         assert ok, rep
         og, oo = P.pdadmm_objective(ctx), O.objective(st)
         rg, ro = P.pdadmm_residual(ctx)[0], O.residual(st)[0]
@@ -302,7 +304,39 @@ def test_quantized_trajectory_every_step_is_an_oracle_step(env):
             z = P.pdadmm_get_var(ctx, P.VAR.Z, l).astype(F64)
             ref = w.nu * (q - np.maximum(z, 0))
             assert np.max(np.abs(u - ref)) <= 1e-5 * w.nu * max(1.0, np.max(np.abs(q)))
-    _say(f"  shadowed -Q run: {total_bad} one-level index differences in 20 iterations")
+        H.round_state_to_fp32(st)
+    _say(f"  stepwise -Q run: {total_bad} one-level index differences in 20 iterations")
+
+
+@pytest.mark.parametrize("case", ["C1-full", "C5-small", "odd-widths", "one-layer"])
+def test_predict_matches_oracle_forward_pass(env, case):
+    """Inference with weights trained for a few iterations: output layer within 1e-5 (relative L2),
+    predicted classes equal wherever the two largest outputs are not within rounding of each other,
+    accuracy over all nodes and over a mask."""
+    torch, P, H = env
+    w = CASES[case]()
+    _say(f"predict {case}")
+    inp = oracle_inputs(w)
+    st = oracle_state(w, inp)
+    O.iterate(st, 3)                             # weights trained by the oracle ...
+    st = H.round_state_to_fp32(st)
+    ctx = H.gpu_context(w, inp, st)              # ... copied to the GPU bit for bit
+    mask = (np.arange(w.n_nodes) % 3 == 0)
+    ref_pred, ref_out = O.predict(st)
+    got = P.pdadmm_predict(ctx, mask=torch.from_numpy(mask.astype(np.uint8)).cuda(), want_logits=True)
+    out = got["logits"].cpu().numpy()
+    pred = got["pred"].cpu().numpy()
+    assert rel_l2(out, ref_out) <= 1e-5
+    top2 = np.sort(ref_out, axis=1)[:, -2:] if ref_out.shape[1] > 1 else np.zeros((w.n_nodes, 2))
+    clear = (top2[:, 1] - top2[:, 0]) > 1e-4 * (1.0 + np.abs(top2[:, 1]))
+    assert np.array_equal(pred[clear], ref_pred[clear]) and clear.mean() > 0.99
+    assert np.array_equal(pred, np.argmax(out, axis=1))            # the GPU's own argmax is a first maximum
+    assert abs(got["accuracy"] - O.accuracy(pred, inp["y"], mask)) < 1e-12
+    assert abs(P.pdadmm_predict(ctx)["accuracy"] - O.accuracy(pred, inp["y"])) < 1e-12
+    # the ADMM variables are untouched by the forward pass
+    before = P.pdadmm_objective(ctx)["L_rho"]
+    P.pdadmm_predict(ctx)
+    assert P.pdadmm_objective(ctx)["L_rho"] == before
 
 
 def test_iterate_is_bit_reproducible(env):

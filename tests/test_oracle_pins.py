@@ -429,3 +429,47 @@ def test_backtracking_schedule_convention():
             assert st.p_trials[i] >= 1 and st.tau[i] == tau0[i] / st.eta * st.eta ** (st.p_trials[i] - 1)
         for i in range(st.L):
             assert st.w_trials[i] >= 1 and st.theta[i] == th0[i] / st.eta * st.eta ** (st.w_trials[i] - 1)
+
+
+# ----------------------------------------------------------------------------- the model (Problem 1)
+def test_forward_pass_reproduces_a_network_with_a_known_function():
+    # Section 3.1 / Problem 1. Two layers built by hand: W_1 = [I; -I] splits x into (x+, x-),
+    # W_2 = [I, -I] recombines them, so the output is x itself; a third layer adds a known bias.
+    rng = np.random.default_rng(5)
+    n, d = 50, 6
+    X = rng.standard_normal((n, d))
+    I = np.eye(d)
+    W = [np.vstack([I, -I]), np.hstack([I, -I])]
+    b = [np.zeros(2 * d), np.zeros(d)]
+    y = rng.integers(0, d, n)
+    st = O.init_forward(X, W, b, y, 1.0, 1.0)
+    out = O.forward(st)
+    np.testing.assert_allclose(out, X, atol=1e-15)
+    pred, _ = O.predict(st)
+    assert np.array_equal(pred, np.argmax(X, axis=1))
+    # max(x_0, x_1) = x_1 + relu(x_0 - x_1): a one-hidden-layer network, checked node by node
+    W = [np.array([[1.0, -1.0], [0.0, 1.0], [0.0, -1.0]]), np.array([[1.0, 1.0, -1.0], [0.0, 0.0, 0.0]])]
+    b = [np.zeros(3), np.array([0.0, 0.25])]
+    X2 = rng.standard_normal((n, 2))
+    st = O.init_forward(X2, W, b, np.zeros(n, dtype=int), 1.0, 1.0)
+    out = O.forward(st)
+    for j in range(n):
+        assert abs(out[j, 0] - max(X2[j, 0], X2[j, 1])) < 1e-15 and out[j, 1] == 0.25
+    pred, _ = O.predict(st)
+    assert np.array_equal(pred, (np.maximum(X2[:, 0], X2[:, 1]) <= 0.25).astype(np.int32))
+    # accuracy counts masked nodes only
+    m = np.zeros(n, dtype=bool)
+    m[:10] = True
+    assert O.accuracy(pred, pred, m) == 1.0 and O.accuracy(pred, 1 - pred, m) == 0.0
+    assert abs(O.accuracy(pred, np.where(np.arange(n) < 5, 1 - pred, pred), m) - 0.5) < 1e-15
+
+
+def test_forward_pass_ignores_the_admm_variables():
+    # the perturbed p, z, q must not enter the prediction: only X, W, b do
+    w = small(n=120)
+    inp = oracle_inputs(w)
+    a = oracle_state(w, inp, perturbed=False)
+    b = oracle_state(w, inp, perturbed=True)
+    assert np.array_equal(O.forward(a), O.forward(b))
+    # at the forward-consistent start the ADMM variable z_L is the model's output
+    np.testing.assert_allclose(O.forward(a), a.z[-1], rtol=1e-6, atol=1e-6)
