@@ -61,7 +61,7 @@ def build_problem(w, device):
     torch.cuda.synchronize()
     aug_ms = e0.elapsed_time(e1)
     q = w.quant
-    cfg = P.Config(n_nodes=w.n_nodes, dims=list(w.dims), rho=w.rho, nu=w.nu, quantize=1 if q else 0,
+    cfg = P.Config(n_nodes=w.n_nodes, dims=list(w.dims), rho=w.rho, nu=w.nu, quantize=(2 if w.quant_q else 1) if q else 0,
                    q_lo=q[0] if q else -1.0, q_hi=q[1] if q else 1.0, q_levels=q[2] if q else 256)
     ctx = P.pdadmm_init(cfg, Xa, torch.from_numpy(y).to(device), [torch.from_numpy(a).to(device) for a in Ws],
                         [torch.from_numpy(a).to(device) for a in bs])
@@ -94,7 +94,7 @@ def cpu_baseline(w, host):
     arp, aci, av = O.normalize_adj(host["rowptr"], host["colidx"])
     Xa = O.augment(arp, aci, av, host["X"], w.hops)
     grid = O.Grid(*w.quant) if w.quant else None
-    st = O.init_forward(Xa, host["W"], host["b"], host["y"], w.rho, w.nu, grid=grid)
+    st = O.init_forward(Xa, host["W"], host["b"], host["y"], w.rho, w.nu, grid=grid, quantize_q=w.quant_q)
     quant = (lambda a: O.quantize(a, grid)[1]) if grid else None
     z, q, p, u = perturb_state(w, [a.astype(np.float32) for a in st.z], [a.astype(np.float32) for a in st.q],
                                quantizer=quant)
@@ -102,6 +102,8 @@ def cpu_baseline(w, host):
         st.z[i] = z[i].astype(np.float64)
         if i < st.L - 1:
             st.q[i], st.p[i + 1], st.u[i] = (a[i].astype(np.float64) for a in (q, p, u))
+            if w.quant_q:
+                st.q[i] = quant(q[i]).astype(np.float64)
     t0 = time.perf_counter()
     O.iterate(st, 1)
     dt = time.perf_counter() - t0
@@ -114,7 +116,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="C2", help="C1..C5 (default C2: the configuration the metric is quoted on)")
+    ap.add_argument("--workload", default="C2", help="C1..C5, C5pq (default C2: the configuration the metric is quoted on)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--all-classes", action="store_true", help="time every kernel class (adds event overhead)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -175,7 +177,7 @@ def main():
                config=dict(workload=f"{w.name}: N={w.n_nodes} {w.graph} graph, X {w.feat_dim}-dim, hops={w.hops} -> n0={w.n0}, "
                                     f"L={w.n_layers}, hidden={w.hidden}, classes={w.n_classes}, rho=nu={w.rho}"
                                     + (f", Delta={w.quant[2]} levels on [{w.quant[0]},{w.quant[1]}]" if w.quant else ""),
-                           variant="pdADMM-G-Q" if w.quant else "pdADMM-G"),
+                           variant=("pdADMM-G-Q (p and q on the grid)" if w.quant_q else "pdADMM-G-Q") if w.quant else "pdADMM-G"),
                gemm_tflops_whole_iteration=total_gemm_flops * args.steps / dt / 1e12,
                roofline=roofline,
                augment_ms=info["augment_ms"], objective_after=obj["L_rho"],

@@ -43,7 +43,8 @@ typedef struct {
   int32_t n_layers;        /* L >= 1 */
   const int32_t* dims;     /* HOST, dims[0..L] = n_0..n_L (read during the call only) */
   float rho, nu;           /* penalties of L_rho (Section 3.2), both > 0 */
-  int32_t quantize;        /* 0: pdADMM-G; 1: pdADMM-G-Q, p_l (l >= 2) restricted to Delta */
+  int32_t quantize;        /* 0: pdADMM-G; 1: pdADMM-G-Q, p_l (l >= 2) restricted to Delta; 2: the variant of
+                              Appendix B that also projects every updated q_l onto Delta */
   float q_lo, q_hi;        /* Delta = { q_lo + i*(q_hi-q_lo)/(q_levels-1) }, i = 0..q_levels-1 */
   int32_t q_levels;        /* 2..256 */
   int32_t fista_iters;     /* fixed number of FISTA steps for z_L (Appendix A); e.g. 20 */
@@ -137,7 +138,8 @@ size_t pdadmm_workspace_bytes(const pdadmm_config* cfg);
 
 /*
  * Create a context and the forward-consistent starting point of Algorithm 1:
- * p_1 = X_aug; z_l = W_l p_l + b_l; q_l = f(z_l); p_{l+1} = q_l (projected onto Delta for -Q);
+ * p_1 = X_aug; z_l = W_l p_l + b_l; q_l = f(z_l); p_{l+1} = q_l (projected onto Delta for -Q; with
+ * quantize = 2 q_l is projected as well);
  * u_l = 0; tau_l = tau0, theta_l = theta0.
  *  workspace: DEVICE, >= pdadmm_workspace_bytes(cfg), 256-byte aligned, owned by the caller and kept
  *             alive until pdadmm_destroy. X_aug [N, n_0], labels [N] int32 in [0, n_L),
@@ -153,7 +155,7 @@ pdadmm_status pdadmm_init(pdadmm_ctx** out, const pdadmm_config* cfg, void* work
 /*
  * Copy a variable in or out. `layer` is the paper's l. The buffer is dense (leading dimension =
  * width) and may be HOST or DEVICE memory, except TAU/THETA (HOST double). Both calls synchronise.
- * set_var of P in -Q mode projects the values onto Delta. After any set_var the carried residual
+ * set_var of P in -Q mode (and of Q with quantize = 2) projects the values onto Delta. After any set_var the carried residual
  * W_l p_l + b_l - z_l is recomputed from scratch at the next iteration.
  */
 pdadmm_status pdadmm_set_var(pdadmm_ctx* ctx, int32_t kind, int32_t layer, const void* src);

@@ -26,7 +26,8 @@ paper itself; the tests pin them only through the mathematical properties they i
   * FISTA for z_L: fixed number of steps, step 1/(nu + 1/2), start at z_L^k, risk = sum
     (not mean) of cross-entropy over labelled nodes; unlabelled nodes take z = W p + b;
   * Delta is a uniform grid (lo, hi, levels); the nearest-level decision is taken in fp32
-    (the precision of the stored p), ties to the even index.
+    (the precision of the stored p), ties to the even index;
+  * variant with p and q both on Delta (Appendix B, last paragraph): the start projects q_l too.
 """
 from __future__ import annotations
 
@@ -167,6 +168,7 @@ class State:
     fista_iters: int = 20
     p_trials: List[int] = field(default_factory=list)
     w_trials: List[int] = field(default_factory=list)
+    quantize_q: bool = False       # variant of Appendix B (last paragraph): q_l is projected onto Delta as well
 
     @property
     def L(self) -> int:
@@ -177,14 +179,14 @@ class State:
         return State(c(self.W), c(self.b), c(self.z), c(self.p), c(self.q), c(self.u), self.y,
                      self.mask, self.rho, self.nu, self.grid, list(self.tau), list(self.theta),
                      self.eta, self.bt_max_trials, self.fista_iters, list(self.p_trials),
-                     list(self.w_trials))
+                     list(self.w_trials), self.quantize_q)
 
 
 def init_forward(X_aug, W0, b0, y, rho, nu, grid: Optional[Grid] = None, mask=None,
-                 tau0: float = 1.0, theta0: float = 1.0, **kw) -> State:
+                 tau0: float = 1.0, theta0: float = 1.0, quantize_q: bool = False, **kw) -> State:
     """Forward-consistent start: z_l = W_l p_l + b_l, q_l = f(z_l), p_{l+1} = q_l (projected
-    onto Delta for -Q), u_l = 0. (The paper only says 'initialise'; its theorems hold from
-    any start.)"""
+    onto Delta for -Q; q_l too in the variant that keeps q on the grid), u_l = 0. (The paper only
+    says 'initialise'; its theorems hold from any start.)"""
     L = len(W0)
     W = [np.asarray(w, dtype=F64) for w in W0]
     b = [np.asarray(v, dtype=F64) for v in b0]
@@ -195,14 +197,17 @@ def init_forward(X_aug, W0, b0, y, rho, nu, grid: Optional[Grid] = None, mask=No
         z.append(zi)
         if i < L - 1:
             qi = relu(zi)
-            q.append(qi)
             nxt = qi
             if grid is not None:
                 nxt = quantize(qi, grid)[1].astype(F64)
+                if quantize_q:
+                    qi = nxt.copy()
+            q.append(qi)
             p.append(np.array(nxt, dtype=F64, copy=True))
             u.append(np.zeros_like(qi))
     return State(W, b, z, p, q, u, np.asarray(y), mask, float(rho), float(nu), grid,
-                 [tau0] * L, [theta0] * L, p_trials=[0] * L, w_trials=[0] * L, **kw)
+                 [tau0] * L, [theta0] * L, p_trials=[0] * L, w_trials=[0] * L,
+                 quantize_q=bool(quantize_q and grid is not None), **kw)
 
 
 def phi(st: State, i: int, p=None, W=None, b=None) -> float:
@@ -357,8 +362,12 @@ def update_z_last(st: State) -> None:
 
 
 def update_q(st: State, i: int) -> None:
-    """q_l <- (rho p_{l+1} + u_l + nu f(z_l)) / (rho + nu)."""
-    st.q[i] = (st.rho * st.p[i + 1] + st.u[i] + st.nu * relu(st.z[i])) / (st.rho + st.nu)
+    """q_l <- (rho p_{l+1} + u_l + nu f(z_l)) / (rho + nu) (Appendix A 'update q'); in the variant
+    that quantises q as well, the nearest member of Delta to that value (Appendix B, last paragraph)."""
+    q = (st.rho * st.p[i + 1] + st.u[i] + st.nu * relu(st.z[i])) / (st.rho + st.nu)
+    if st.quantize_q:
+        q = quantize(q, st.grid)[1].astype(F64)
+    st.q[i] = q
 
 
 def update_u(st: State, i: int) -> None:

@@ -269,9 +269,12 @@ __device__ __forceinline__ float z_closed_form(float s, float q) {
 // (Appendix A 'update z', 'update q', 'update u'):
 //   a = R - m + z_old; z = closed form; R <- a - z;
 //   q = (rho p_{l+1} + u + nu relu(z)) / (rho + nu); r = p_{l+1} - q; u <- u + rho r.
+// In the variant that keeps q on the grid as well (Appendix B, last paragraph) the closed-form q is
+// projected onto Delta before r and u are formed.
 constexpr int kZquUnroll = 2;   // float4 groups per thread
 
-__global__ __launch_bounds__(256) void zqu_kernel(const RowSeg* __restrict__ segs, const BlockMap map, float rho, float nu) {
+__global__ __launch_bounds__(256) void zqu_kernel(const RowSeg* __restrict__ segs, const BlockMap map, float rho, float nu,
+                                                  const QuantGrid qgrid) {
   int local;
   const int si = find_group(map, blockIdx.x, &local);
   const RowSeg S = segs[si];
@@ -304,7 +307,8 @@ __global__ __launch_bounds__(256) void zqu_kernel(const RowSeg* __restrict__ seg
         const float z = z_closed_form(a + zo[k][c], qo[k][c]);
         zn[c] = z;
         Rn[c] = a - z;
-        const float qq = (rho * pn[k][c] + uo[k][c] + nu * fmaxf(z, 0.0f)) * inv_rn;
+        float qq = (rho * pn[k][c] + uo[k][c] + nu * fmaxf(z, 0.0f)) * inv_rn;
+        if (qgrid.levels > 0) qq = quant_value(quant_index(qq, qgrid), qgrid);   // variant with q on the grid
         const float rr = pn[k][c] - qq;
         qn[c] = qq;
         un[c] = uo[k][c] + rho * rr;

@@ -76,7 +76,7 @@ struct EpiResid {     // r = acc + b[col] - z; s0 += r^2; s1 += (r - carried)^2 
     }
   }
 };
-struct EpiForward {   // z = acc + b[col]; q = relu(z); p_next = relu(z) (projected onto the grid in -Q)
+struct EpiForward {   // z = acc + b[col]; q = relu(z); p_next = relu(z) (projected onto the grid in -Q; q too if beta != 0)
   static constexpr int NS = 0;
   __device__ static __forceinline__ void apply(const GemmProb& P, float* C, int row, int col, float acc,
                                                double&, double&) {
@@ -85,8 +85,9 @@ struct EpiForward {   // z = acc + b[col]; q = relu(z); p_next = relu(z) (projec
     C[i] = z;
     if (P.o1) {
       const float a = fmaxf(z, 0.0f);
-      P.o1[i] = a;
-      P.o2[i] = P.grid.levels > 0 ? quant_value(quant_index(a, P.grid), P.grid) : a;
+      const float aq = P.grid.levels > 0 ? quant_value(quant_index(a, P.grid), P.grid) : a;
+      P.o1[i] = P.beta != 0.0f ? aq : a;    // beta != 0: q is kept on the grid as well
+      P.o2[i] = aq;
     }
   }
 };

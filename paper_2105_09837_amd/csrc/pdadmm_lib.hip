@@ -207,7 +207,7 @@ bool config_ok(const pdadmm_config* c, std::string* why) {
     if (c->dims[i] < 1) return bad("a layer width is < 1");
   if (c->dims[c->n_layers] > 1024) return bad("n_L > 1024 classes is not supported");
   if (!(c->rho > 0.f) || !(c->nu > 0.f)) return bad("rho and nu must be > 0");
-  if (c->quantize != 0 && c->quantize != 1) return bad("quantize must be 0 or 1");
+  if (c->quantize < 0 || c->quantize > 2) return bad("quantize must be 0, 1 or 2");
   if (c->quantize) {
     if (c->q_levels < 2 || c->q_levels > 256) return bad("q_levels must be in 2..256");
     if (!(c->q_hi > c->q_lo)) return bad("q_hi must exceed q_lo");
@@ -452,6 +452,7 @@ pdadmm_status build_tables(pdadmm_ctx* c) {
     Fw.e0 = b.b;
     if (i < L - 1) { Fw.o1 = b.q; Fw.o2 = c->lay[i + 1].p; }
     Fw.grid = Q ? c->grid : QuantGrid{0.f, 0.f, 0};
+    Fw.beta = c->cfg.quantize == 2 ? 1.0f : 0.0f;
     Fw.blk0 = 0;
     fwd.push_back(Fw);
     RowSeg rs{};
@@ -625,7 +626,8 @@ pdadmm_status phase_bzqu(pdadmm_ctx* c) {
   { TIMED(c, kClsBias); launch_group(c, c->g_bias, bias_step_kernel); }
   LAUNCH_CHECK(c, "bias step");
   if (L > 1) {
-    { TIMED(c, kClsZqu); launch_group(c, c->g_rows_hidden, zqu_kernel, g.rho, g.nu); }
+    { TIMED(c, kClsZqu); launch_group(c, c->g_rows_hidden, zqu_kernel, g.rho, g.nu,
+                                      g.quantize == 2 ? c->grid : QuantGrid{0.f, 0.f, 0}); }
     LAUNCH_CHECK(c, "zqu");
   }
   return launch_fista(c);
@@ -915,6 +917,13 @@ pdadmm_status pdadmm_set_var(pdadmm_ctx* c, int32_t kind, int32_t layer, const v
   if (s != PDADMM_OK) return s;
   HIP_TRY(c, hipMemcpy2DAsync(v.ptr, (size_t)v.ld * v.elem, src, (size_t)v.cols * v.elem, (size_t)v.cols * v.elem,
                               v.rows, hipMemcpyDefault, c->stream));
+  if (kind == PDADMM_VAR_Q && c->cfg.quantize == 2) {
+    const LayerBufs& b = c->lay[layer - 1];
+    const size_t n4 = (size_t)c->N * b.ld_out / 4;
+    hipLaunchKernelGGL(quantize_kernel, dim3(flat_blocks(n4)), dim3(256), 0, c->stream, b.q, n4, b.n_out, b.ld_out,
+                       c->grid, (uint8_t*)nullptr, b.q);
+    LAUNCH_CHECK(c, "quantize set_var q");
+  }
   if (kind == PDADMM_VAR_P && c->cfg.quantize) {
     const LayerBufs& b = c->lay[layer - 1];
     const size_t n4 = (size_t)c->N * b.ld_in / 4;

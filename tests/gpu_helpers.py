@@ -10,7 +10,7 @@ from tests.helpers import F32, F64, grid_of, rel_l2
 
 def config_of(w, **kw) -> P.Config:
     q = w.quant
-    base = dict(n_nodes=w.n_nodes, dims=list(w.dims), rho=w.rho, nu=w.nu, quantize=1 if q else 0,
+    base = dict(n_nodes=w.n_nodes, dims=list(w.dims), rho=w.rho, nu=w.nu, quantize=(2 if w.quant_q else 1) if q else 0,
                 q_lo=q[0] if q else -1.0, q_hi=q[1] if q else 1.0, q_levels=q[2] if q else 256)
     base.update(kw)
     return P.Config(**base)

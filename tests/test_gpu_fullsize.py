@@ -125,7 +125,7 @@ class _Problem:
         Ws, bs = make_weights(w)
         self.y = make_labels(w)
         q = w.quant
-        cfg = P.Config(n_nodes=w.n_nodes, dims=list(w.dims), rho=w.rho, nu=w.nu, quantize=1 if q else 0,
+        cfg = P.Config(n_nodes=w.n_nodes, dims=list(w.dims), rho=w.rho, nu=w.nu, quantize=(2 if w.quant_q else 1) if q else 0,
                        q_lo=q[0] if q else -1.0, q_hi=q[1] if q else 1.0, q_levels=q[2] if q else 256)
         self.ctx = P.pdadmm_init(cfg, Xa, torch.from_numpy(self.y).to(dev), [torch.from_numpy(a).to(dev) for a in Ws],
                                  [torch.from_numpy(a).to(dev) for a in bs])

@@ -154,6 +154,7 @@ CASES = {
     "C3-small": lambda: scaled_workload("C3", 2100, hidden=200, n_layers=3, feat_dim=16),
     "C4-small": lambda: scaled_workload("C4", 600, hidden=36, n_layers=12, feat_dim=12),
     "C5-small": lambda: scaled_workload("C5", 1300, hidden=136, n_layers=4, feat_dim=20),
+    "C5pq-small": lambda: dataclasses.replace(scaled_workload("C5", 900, hidden=72, n_layers=4, feat_dim=12), quant_q=True),
     "odd-widths": lambda: dataclasses.replace(scaled_workload("C2", 333, hidden=50, n_layers=3, feat_dim=5),
                                               n_classes=5, hidden=37),
     "one-layer": lambda: scaled_workload("C2", 400, hidden=10, n_layers=1, feat_dim=6),
@@ -268,7 +269,8 @@ def test_trajectories(env, case, iters):
     assert s["r_drift"] < 1e-4
 
 
-def test_quantized_trajectory_step_by_step_along_the_oracle_run(env):
+@pytest.mark.parametrize("case", ["C5-small", "C5pq-small"])
+def test_quantized_trajectory_step_by_step_along_the_oracle_run(env, case):
     """pdADMM-G-Q over 20 iterations, one step at a time: the oracle runs its own trajectory (its state
     rounded to fp32 after every iteration); before each iteration that state is copied to the GPU, both
     take one iteration, and the results must agree (indices up to isolated one-level flips at midpoints,
@@ -276,7 +278,7 @@ def test_quantized_trajectory_step_by_step_along_the_oracle_run(env):
     flipped index changes a backtracking decision (see test_trajectories); this shows that every step of
     the GPU is the oracle's step from the same starting values, all the way along the run."""
     torch, P, H = env
-    w = CASES["C5-small"]()
+    w = CASES[case]()
     inp = oracle_inputs(w)
     st = H.round_state_to_fp32(oracle_state(w, inp))
     ctx = H.gpu_context(w, inp, st)
@@ -298,12 +300,17 @@ def test_quantized_trajectory_step_by_step_along_the_oracle_run(env):
         assert abs(og["F"] - oo["F"]) <= TOL_TRAJ * abs(oo["F"])
         assert abs(rg - ro) <= TOL_TRAJ * ro
         # Lemma (q optimality): u = nu (q - f(z)) after every iteration, on the GPU's own state
-        for l in range(1, st.L):
+        # (not in the variant that projects q: there q is no longer the minimiser of its subproblem)
+        for l in range(1, st.L if not w.quant_q else 1):
             u = P.pdadmm_get_var(ctx, P.VAR.U, l).astype(F64)
             q = P.pdadmm_get_var(ctx, P.VAR.Q, l).astype(F64)
             z = P.pdadmm_get_var(ctx, P.VAR.Z, l).astype(F64)
             ref = w.nu * (q - np.maximum(z, 0))
             assert np.max(np.abs(u - ref)) <= 1e-5 * w.nu * max(1.0, np.max(np.abs(q)))
+        if w.quant_q:                                   # q stays in Delta, bit for bit
+            mem = st.grid.members()
+            for l in range(1, st.L):
+                assert np.isin(P.pdadmm_get_var(ctx, P.VAR.Q, l), mem).all()
         H.round_state_to_fp32(st)
     _say(f"  stepwise -Q run: {total_bad} one-level index differences in 20 iterations")
 

@@ -61,7 +61,7 @@ def test_workspace_size_and_config_validation(lib):
     import dataclasses
     for bad in (dict(rho=0.0), dict(nu=-1.0), dict(n_nodes=0), dict(bt_eta=1.0), dict(dims=[5, 0, 3]),
                 dict(quantize=1, q_levels=1), dict(quantize=1, q_levels=300), dict(quantize=1, q_lo=1.0, q_hi=1.0),
-                dict(quantize=2), dict(bt_max_trials=0), dict(tau0=0.0)):
+                dict(quantize=3), dict(quantize=-1), dict(bt_max_trials=0), dict(tau0=0.0)):
         assert P.pdadmm_workspace_bytes(dataclasses.replace(good, **bad)) == 0, bad
     q = dataclasses.replace(good, quantize=1)
     assert P.pdadmm_workspace_bytes(q) > nbytes

@@ -473,3 +473,45 @@ def test_forward_pass_ignores_the_admm_variables():
     assert np.array_equal(O.forward(a), O.forward(b))
     # at the forward-consistent start the ADMM variable z_L is the model's output
     np.testing.assert_allclose(O.forward(a), a.z[-1], rtol=1e-6, atol=1e-6)
+
+
+def test_variant_with_p_and_q_on_the_grid():
+    # Appendix B, last paragraph: q_l <- nearest member of Delta to the closed-form q.
+    w = dataclasses.replace(small("C5", n=200, hidden=16, n_layers=4, feat_dim=6), quant_q=True)
+    inp = oracle_inputs(w)
+    st = oracle_state(w, inp)
+    assert st.quantize_q
+    mem = st.grid.members().astype(F64)
+    ref = st.copy()
+    ref.quantize_q = False
+    for k in range(3):
+        # one iteration of both; up to the q-update they see the same state
+        for i in range(1, st.L):
+            O.update_p(st, i); O.update_p(ref, i)
+        for i in range(st.L):
+            O.update_W(st, i); O.update_W(ref, i)
+        for i in range(st.L):
+            O.update_b(st, i); O.update_b(ref, i)
+        for i in range(st.L - 1):
+            O.update_z_hidden(st, i); O.update_z_hidden(ref, i)
+        O.update_z_last(st); O.update_z_last(ref)
+        for i in range(st.L - 1):
+            O.update_q(st, i); O.update_q(ref, i)
+            assert np.isin(st.q[i], mem).all()                       # q in Delta
+            # it is the nearest member to the unquantised closed form (brute force over Delta), except
+            # where that value sits within fp32 rounding of a midpoint
+            v = ref.q[i]
+            brute = mem[np.argmin(np.abs(v[..., None] - mem), axis=-1)]
+            differ = st.q[i] != brute
+            if differ.any():
+                gap = np.abs(np.abs(v[differ] - st.q[i][differ]) - np.abs(v[differ] - brute[differ]))
+                assert np.all(gap <= 1e-6)
+            assert differ.sum() <= max(2, 1e-4 * differ.size)
+        for i in range(st.L - 1):
+            O.update_u(st, i); O.update_u(ref, i)
+            # dual ascent with the projected q
+            assert np.all(np.isfinite(st.u[i]))
+        # continue both from the variant's state
+        ref = st.copy()
+        ref.quantize_q = False
+    assert all(np.isin(st.p[i], mem).all() for i in range(1, st.L))

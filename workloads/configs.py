@@ -28,6 +28,7 @@ class Workload:
     nu: float
     iters: int
     quant: Optional[Tuple[float, float, int]] = None   # (lo, hi, levels) of the uniform grid
+    quant_q: bool = False                               # q_l is kept on the grid as well (needs quant)
 
     @property
     def n0(self) -> int:
@@ -50,6 +51,8 @@ WORKLOADS = {
     "C5": Workload("C5", 5, 100_000, "pa", (5,), 256, "normal", 3, 1000, 16, 20, 1e-3, 1e-3, 20,
                    quant=(-1.0, 1.0, 256)),
 }
+# C5 with p and q both on the grid (the variant at the end of Appendix B)
+WORKLOADS["C5pq"] = replace(WORKLOADS["C5"], name="C5pq", quant_q=True)
 
 
 def get_workload(name: str) -> Workload:
