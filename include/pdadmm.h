@@ -52,6 +52,8 @@ typedef struct {
   float tau0, theta0;      /* initial tau_l, theta_l, e.g. 1 */
   int32_t bt_max_trials;   /* cap per update, e.g. 64 */
   int32_t refresh_every;   /* recompute W_l p_l + b_l - z_l from scratch every k iterations; 0 = never */
+  float leaky_slope;       /* activation f(z) = z (z > 0), leaky_slope * z otherwise; 0 = ReLU (Section 5.1);
+                              in [0, 1): leaky ReLU (named in Section 4 as satisfying the assumption) */
 } pdadmm_config;
 
 /* Terms of the augmented Lagrangian L_rho (Section 3.2). */

@@ -146,6 +146,12 @@ def relu(x):
     return np.maximum(x, 0.0)
 
 
+def act(x, slope: float = 0.0):
+    """Activation f: x for x > 0, slope*x otherwise (slope = 0: ReLU, Section 5.1; 0 < slope < 1:
+    leaky ReLU, which Section 4 names as satisfying the assumption)."""
+    return np.where(x > 0, x, slope * x)
+
+
 @dataclass
 class State:
     """All variables of Problem 2 plus the duals and the backtracking parameters.
@@ -169,6 +175,7 @@ class State:
     p_trials: List[int] = field(default_factory=list)
     w_trials: List[int] = field(default_factory=list)
     quantize_q: bool = False       # variant of Appendix B (last paragraph): q_l is projected onto Delta as well
+    slope: float = 0.0             # negative-side slope of the activation (0 = ReLU)
 
     @property
     def L(self) -> int:
@@ -179,11 +186,12 @@ class State:
         return State(c(self.W), c(self.b), c(self.z), c(self.p), c(self.q), c(self.u), self.y,
                      self.mask, self.rho, self.nu, self.grid, list(self.tau), list(self.theta),
                      self.eta, self.bt_max_trials, self.fista_iters, list(self.p_trials),
-                     list(self.w_trials), self.quantize_q)
+                     list(self.w_trials), self.quantize_q, self.slope)
 
 
 def init_forward(X_aug, W0, b0, y, rho, nu, grid: Optional[Grid] = None, mask=None,
-                 tau0: float = 1.0, theta0: float = 1.0, quantize_q: bool = False, **kw) -> State:
+                 tau0: float = 1.0, theta0: float = 1.0, quantize_q: bool = False, slope: float = 0.0,
+                 **kw) -> State:
     """Forward-consistent start: z_l = W_l p_l + b_l, q_l = f(z_l), p_{l+1} = q_l (projected
     onto Delta for -Q; q_l too in the variant that keeps q on the grid), u_l = 0. (The paper only
     says 'initialise'; its theorems hold from any start.)"""
@@ -196,7 +204,7 @@ def init_forward(X_aug, W0, b0, y, rho, nu, grid: Optional[Grid] = None, mask=No
         zi = p[i] @ W[i].T + b[i]
         z.append(zi)
         if i < L - 1:
-            qi = relu(zi)
+            qi = act(zi, slope)
             nxt = qi
             if grid is not None:
                 nxt = quantize(qi, grid)[1].astype(F64)
@@ -207,7 +215,7 @@ def init_forward(X_aug, W0, b0, y, rho, nu, grid: Optional[Grid] = None, mask=No
             u.append(np.zeros_like(qi))
     return State(W, b, z, p, q, u, np.asarray(y), mask, float(rho), float(nu), grid,
                  [tau0] * L, [theta0] * L, p_trials=[0] * L, w_trials=[0] * L,
-                 quantize_q=bool(quantize_q and grid is not None), **kw)
+                 quantize_q=bool(quantize_q and grid is not None), slope=float(slope), **kw)
 
 
 def phi(st: State, i: int, p=None, W=None, b=None) -> float:
@@ -302,20 +310,23 @@ def update_b(st: State, i: int) -> None:
     st.b[i] = st.b[i] - grad_b(st, i) / (st.nu * n_nodes)
 
 
-def z_subproblem_value(z, a, q, z_old):
+def z_subproblem_value(z, a, q, z_old, slope: float = 0.0):
     """(z-a)^2 + (q - f(z))^2 + (z - z_old)^2: the z-subproblem for l < L without nu/2."""
-    return (z - a) ** 2 + (q - relu(z)) ** 2 + (z - z_old) ** 2
+    return (z - a) ** 2 + (q - act(z, slope)) ** 2 + (z - z_old) ** 2
 
 
 def update_z_hidden(st: State, i: int) -> None:
-    """Closed-form ReLU z-update for l < L (Appendix A 'update z'): two candidates,
-    min((a+z_old)/2, 0) and max((a+q+z_old)/3, 0); keep the better one, ties to the first."""
+    """Closed-form z-update for l < L (Appendix A 'update z'). ReLU: the two candidates printed
+    there, min((a+z_old)/2, 0) and max((a+q+z_old)/3, 0). For f(z) = slope*z on z < 0 the same
+    derivation (minimise the quadratic on each half-line, clamp at 0) gives
+    min((a + z_old + slope*q)/(2 + slope^2), 0) for the non-positive side; the positive side is
+    unchanged. Keep the candidate with the smaller subproblem value, ties to the non-positive one."""
     a = st.p[i] @ st.W[i].T + st.b[i]
-    z_old, q = st.z[i], st.q[i]
-    z_neg = np.minimum((a + z_old) / 2.0, 0.0)
+    z_old, q, sl = st.z[i], st.q[i], st.slope
+    z_neg = np.minimum((a + z_old + sl * q) / (2.0 + sl * sl), 0.0)
     z_pos = np.maximum((a + q + z_old) / 3.0, 0.0)
-    h_neg = z_subproblem_value(z_neg, a, q, z_old)
-    h_pos = z_subproblem_value(z_pos, a, q, z_old)
+    h_neg = z_subproblem_value(z_neg, a, q, z_old, sl)
+    h_pos = z_subproblem_value(z_pos, a, q, z_old, sl)
     st.z[i] = np.where(h_pos < h_neg, z_pos, z_neg)
 
 
@@ -364,7 +375,7 @@ def update_z_last(st: State) -> None:
 def update_q(st: State, i: int) -> None:
     """q_l <- (rho p_{l+1} + u_l + nu f(z_l)) / (rho + nu) (Appendix A 'update q'); in the variant
     that quantises q as well, the nearest member of Delta to that value (Appendix B, last paragraph)."""
-    q = (st.rho * st.p[i + 1] + st.u[i] + st.nu * relu(st.z[i])) / (st.rho + st.nu)
+    q = (st.rho * st.p[i + 1] + st.u[i] + st.nu * act(st.z[i], st.slope)) / (st.rho + st.nu)
     if st.quantize_q:
         q = quantize(q, st.grid)[1].astype(F64)
     st.q[i] = q
@@ -403,7 +414,7 @@ def forward(st: State) -> np.ndarray:
     a = st.p[0]
     for i in range(st.L):
         z = a @ st.W[i].T + st.b[i]
-        a = relu(z)
+        a = act(z, st.slope)
     return z
 
 
@@ -429,11 +440,11 @@ def objective(st: State) -> dict:
     sum <u, p_{l+1} - q_l>, (rho/2) sum ||p_{l+1} - q_l||^2; F = first three; L_rho = all."""
     L = st.L
     lin = sum(float(np.sum((st.z[i] - st.p[i] @ st.W[i].T - st.b[i]) ** 2)) for i in range(L))
-    act = sum(float(np.sum((st.q[i] - relu(st.z[i])) ** 2)) for i in range(L - 1))
+    actp = sum(float(np.sum((st.q[i] - act(st.z[i], st.slope)) ** 2)) for i in range(L - 1))
     dl = sum(float(np.sum(st.u[i] * (st.p[i + 1] - st.q[i]))) for i in range(L - 1))
     dq = sum(float(np.sum((st.p[i + 1] - st.q[i]) ** 2)) for i in range(L - 1))
     out = dict(risk=risk(st.z[L - 1], st.y, st.mask), lin_pen=0.5 * st.nu * lin,
-               act_pen=0.5 * st.nu * act, dual_lin=dl, dual_quad=0.5 * st.rho * dq)
+               act_pen=0.5 * st.nu * actp, dual_lin=dl, dual_quad=0.5 * st.rho * dq)
     out["F"] = out["risk"] + out["lin_pen"] + out["act_pen"]
     out["L_rho"] = out["F"] + out["dual_lin"] + out["dual_quad"]
     return out

@@ -34,7 +34,8 @@ class _CConfig(C.Structure):
                 ("rho", C.c_float), ("nu", C.c_float), ("quantize", C.c_int32),
                 ("q_lo", C.c_float), ("q_hi", C.c_float), ("q_levels", C.c_int32),
                 ("fista_iters", C.c_int32), ("bt_eta", C.c_float), ("tau0", C.c_float),
-                ("theta0", C.c_float), ("bt_max_trials", C.c_int32), ("refresh_every", C.c_int32)]
+                ("theta0", C.c_float), ("bt_max_trials", C.c_int32), ("refresh_every", C.c_int32),
+                ("leaky_slope", C.c_float)]
 
 
 class _CObjective(C.Structure):
@@ -113,13 +114,14 @@ class Config:
     theta0: float = 1.0
     bt_max_trials: int = 64
     refresh_every: int = 0
+    leaky_slope: float = 0.0
 
     def to_c(self):
         dims = (C.c_int32 * len(self.dims))(*[int(d) for d in self.dims])
         cc = _CConfig(int(self.n_nodes), len(self.dims) - 1, C.cast(dims, C.POINTER(C.c_int32)),
                       float(self.rho), float(self.nu), int(self.quantize), float(self.q_lo), float(self.q_hi),
                       int(self.q_levels), int(self.fista_iters), float(self.bt_eta), float(self.tau0),
-                      float(self.theta0), int(self.bt_max_trials), int(self.refresh_every))
+                      float(self.theta0), int(self.bt_max_trials), int(self.refresh_every), float(self.leaky_slope))
         cc._keep = dims
         return cc
 

@@ -98,6 +98,10 @@ struct LayerScal {
   int pad;
 };
 
+// Activation f (Section 4: ReLU and leaky ReLU satisfy the assumption): f(z) = z for z > 0, slope*z
+// otherwise; slope = 0 is ReLU.
+__device__ __forceinline__ float act_fn(float z, float slope) { return z > 0.0f ? z : slope * z; }
+
 struct QuantGrid {
   float lo, step;
   int levels;

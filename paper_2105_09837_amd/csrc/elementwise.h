@@ -252,29 +252,34 @@ __global__ __launch_bounds__(256) void bias_step_kernel(const BiasSeg* __restric
   }
 }
 
-// Closed-form ReLU z-update (Appendix A 'update z', l < L) on one element.
-// a = W p + b (new), s = a + z_old. Candidates min(s/2, 0) and max((s+q)/3, 0); the better one
-// in the subproblem objective (z-a)^2 + (q-relu(z))^2 + (z-z_old)^2 is: the positive candidate if
-// s >= 0; the non-positive one if s + q <= 0; otherwise the positive one iff (s+q)^2/3 > s^2/2.
-__device__ __forceinline__ float z_closed_form(float s, float q) {
-  const float sq = s + q;
-  const float zneg = fminf(0.5f * s, 0.0f);
-  const float zpos = fmaxf(sq / 3.0f, 0.0f);
-  if (s >= 0.0f) return zpos;
-  if (sq <= 0.0f) return zneg;
-  return (sq * sq) / 3.0f > (s * s) * 0.5f ? zpos : zneg;
+// Closed-form z-update (Appendix A 'update z', l < L) on one element, for f(z) = z (z >= 0), slope*z
+// (z < 0); slope = 0 is the ReLU case printed in the paper. a = W p + b (new), s = a + z_old.
+// On z >= 0 the subproblem (z-a)^2 + (q-f(z))^2 + (z-z_old)^2 is 3 z^2 - 2 z (s+q) + const, on z <= 0 it
+// is (2+slope^2) z^2 - 2 z (s + slope q) + const. Candidates: max((s+q)/3, 0) and
+// min((s + slope q)/(2 + slope^2), 0); a candidate clamped to 0 gains nothing over z = 0, an interior
+// one lowers the value by (s+q)^2/3 resp. (s + slope q)^2/(2 + slope^2): the larger gain wins, a tie
+// goes to the non-positive candidate.
+__device__ __forceinline__ float z_closed_form(float s, float q, float slope) {
+  const float tp = s + q;
+  const float tn = s + slope * q;
+  const float dn = 2.0f + slope * slope;
+  const float zpos = fmaxf(tp / 3.0f, 0.0f);
+  const float zneg = fminf(tn / dn, 0.0f);
+  const float gain_pos = tp > 0.0f ? (tp * tp) / 3.0f : 0.0f;
+  const float gain_neg = tn < 0.0f ? (tn * tn) / dn : 0.0f;
+  return gain_pos > gain_neg ? zpos : zneg;
 }
 
 // Fused b-shift, z-update, q-update, residual and dual update for layers l < L
 // (Appendix A 'update z', 'update q', 'update u'):
 //   a = R - m + z_old; z = closed form; R <- a - z;
-//   q = (rho p_{l+1} + u + nu relu(z)) / (rho + nu); r = p_{l+1} - q; u <- u + rho r.
+//   q = (rho p_{l+1} + u + nu f(z)) / (rho + nu); r = p_{l+1} - q; u <- u + rho r.
 // In the variant that keeps q on the grid as well (Appendix B, last paragraph) the closed-form q is
 // projected onto Delta before r and u are formed.
 constexpr int kZquUnroll = 2;   // float4 groups per thread
 
 __global__ __launch_bounds__(256) void zqu_kernel(const RowSeg* __restrict__ segs, const BlockMap map, float rho, float nu,
-                                                  const QuantGrid qgrid) {
+                                                  float slope, const QuantGrid qgrid) {
   int local;
   const int si = find_group(map, blockIdx.x, &local);
   const RowSeg S = segs[si];
@@ -304,10 +309,10 @@ __global__ __launch_bounds__(256) void zqu_kernel(const RowSeg* __restrict__ seg
 #pragma unroll
       for (int c = 0; c < 4; ++c) {
         const float a = Rv[k][c] - mm[k][c] + zo[k][c];
-        const float z = z_closed_form(a + zo[k][c], qo[k][c]);
+        const float z = z_closed_form(a + zo[k][c], qo[k][c], slope);
         zn[c] = z;
         Rn[c] = a - z;
-        float qq = (rho * pn[k][c] + uo[k][c] + nu * fmaxf(z, 0.0f)) * inv_rn;
+        float qq = (rho * pn[k][c] + uo[k][c] + nu * act_fn(z, slope)) * inv_rn;
         if (qgrid.levels > 0) qq = quant_value(quant_index(qq, qgrid), qgrid);   // variant with q on the grid
         const float rr = pn[k][c] - qq;
         qn[c] = qq;
@@ -553,7 +558,7 @@ __global__ __launch_bounds__(256) void quantize_scalar_kernel(const float* __res
 
 // ------------------------------------------------------------------------------------------
 // Reductions behind the objective (Section 3.2, L_rho) and the residual (Algorithm 1).
-// Per block three partials: sum (q - relu(z))^2, sum u (p_next - q), sum (p_next - q)^2.
+// Per block three partials: sum (q - f(z))^2, sum u (p_next - q), sum (p_next - q)^2.
 // ------------------------------------------------------------------------------------------
 struct PairSeg {
   const float* z;
@@ -565,7 +570,8 @@ struct PairSeg {
   int blk0, nblk;
 };
 
-__global__ __launch_bounds__(256) void pair_reduce_kernel(const PairSeg* __restrict__ segs, const BlockMap map) {
+__global__ __launch_bounds__(256) void pair_reduce_kernel(const PairSeg* __restrict__ segs, const BlockMap map,
+                                                          float slope) {
   __shared__ double red[4];
   int local;
   const int si = find_group(map, blockIdx.x, &local);
@@ -579,7 +585,7 @@ __global__ __launch_bounds__(256) void pair_reduce_kernel(const PairSeg* __restr
     const float4 p = reinterpret_cast<const float4*>(S.pnext)[i];
 #define PDADMM_PR(c)                                              \
   {                                                               \
-    const double a = (double)q.c - (double)fmaxf(z.c, 0.0f);      \
+    const double a = (double)q.c - (double)act_fn(z.c, slope);    \
     const double r = (double)p.c - (double)q.c;                   \
     s_act += a * a;                                               \
     s_dl += (double)u.c * r;                                      \

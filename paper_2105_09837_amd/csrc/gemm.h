@@ -33,6 +33,7 @@ struct GemmProb {
   float* o2;
   double* part;       // per-block partial sums, NS doubles per block
   float alpha, beta;
+  float slope;        // negative-side slope of the activation (epilogues that apply f)
   QuantGrid grid;     // used by the forward epilogue in -Q mode (levels = 0: off)
 };
 
@@ -76,7 +77,7 @@ struct EpiResid {     // r = acc + b[col] - z; s0 += r^2; s1 += (r - carried)^2 
     }
   }
 };
-struct EpiForward {   // z = acc + b[col]; q = relu(z); p_next = relu(z) (projected onto the grid in -Q; q too if beta != 0)
+struct EpiForward {   // z = acc + b[col]; q = f(z); p_next = f(z) (projected onto the grid in -Q; q too if beta != 0)
   static constexpr int NS = 0;
   __device__ static __forceinline__ void apply(const GemmProb& P, float* C, int row, int col, float acc,
                                                double&, double&) {
@@ -84,7 +85,7 @@ struct EpiForward {   // z = acc + b[col]; q = relu(z); p_next = relu(z) (projec
     const float z = acc + P.e0[col];
     C[i] = z;
     if (P.o1) {
-      const float a = fmaxf(z, 0.0f);
+      const float a = act_fn(z, P.slope);
       const float aq = P.grid.levels > 0 ? quant_value(quant_index(a, P.grid), P.grid) : a;
       P.o1[i] = P.beta != 0.0f ? aq : a;    // beta != 0: q is kept on the grid as well
       P.o2[i] = aq;
@@ -92,12 +93,12 @@ struct EpiForward {   // z = acc + b[col]; q = relu(z); p_next = relu(z) (projec
   }
 };
 
-struct EpiBiasAct {   // C = acc + b[col], passed through ReLU when beta != 0 (forward pass of the model, Problem 1)
+struct EpiBiasAct {   // C = acc + b[col], passed through f when beta != 0 (forward pass of the model, Problem 1)
   static constexpr int NS = 0;
   __device__ static __forceinline__ void apply(const GemmProb& P, float* C, int row, int col, float acc,
                                                double&, double&) {
     const float v = acc + P.e0[col];
-    ((float PD_GLOBAL*)C)[(size_t)row * P.ldc + col] = P.beta != 0.0f ? fmaxf(v, 0.0f) : v;
+    ((float PD_GLOBAL*)C)[(size_t)row * P.ldc + col] = P.beta != 0.0f ? act_fn(v, P.slope) : v;
   }
 };
 

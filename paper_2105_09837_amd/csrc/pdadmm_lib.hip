@@ -217,6 +217,7 @@ bool config_ok(const pdadmm_config* c, std::string* why) {
   if (!(c->tau0 > 0.f) || !(c->theta0 > 0.f)) return bad("tau0/theta0 must be > 0");
   if (c->bt_max_trials < 1) return bad("bt_max_trials < 1");
   if (c->refresh_every < 0) return bad("refresh_every < 0");
+  if (!(c->leaky_slope >= 0.f) || !(c->leaky_slope < 1.f)) return bad("leaky_slope must be in [0, 1)");
   return true;
 }
 
@@ -349,6 +350,7 @@ GemmProb make_nt(const float* A, int lda, const float* B, int ldb, float* C, int
   P.vecB = (ldb % 4 == 0) && aligned16(B);
   P.alpha = 1.f;
   P.beta = 0.f;
+  P.slope = 0.f;
   P.layer = 0;
   return P;
 }
@@ -453,6 +455,7 @@ pdadmm_status build_tables(pdadmm_ctx* c) {
     if (i < L - 1) { Fw.o1 = b.q; Fw.o2 = c->lay[i + 1].p; }
     Fw.grid = Q ? c->grid : QuantGrid{0.f, 0.f, 0};
     Fw.beta = c->cfg.quantize == 2 ? 1.0f : 0.0f;
+    Fw.slope = c->cfg.leaky_slope;
     Fw.blk0 = 0;
     fwd.push_back(Fw);
     RowSeg rs{};
@@ -626,7 +629,7 @@ pdadmm_status phase_bzqu(pdadmm_ctx* c) {
   { TIMED(c, kClsBias); launch_group(c, c->g_bias, bias_step_kernel); }
   LAUNCH_CHECK(c, "bias step");
   if (L > 1) {
-    { TIMED(c, kClsZqu); launch_group(c, c->g_rows_hidden, zqu_kernel, g.rho, g.nu,
+    { TIMED(c, kClsZqu); launch_group(c, c->g_rows_hidden, zqu_kernel, g.rho, g.nu, g.leaky_slope,
                                       g.quantize == 2 ? c->grid : QuantGrid{0.f, 0.f, 0}); }
     LAUNCH_CHECK(c, "zqu");
   }
@@ -1005,7 +1008,7 @@ static pdadmm_status pair_sums(pdadmm_ctx* c, std::vector<double>* act, std::vec
   dl->assign(L, 0.0);
   dq->assign(L, 0.0);
   if (L < 2) return PDADMM_OK;
-  launch_group(c, c->g_pair, pair_reduce_kernel);
+  launch_group(c, c->g_pair, pair_reduce_kernel, c->cfg.leaky_slope);
   LAUNCH_CHECK(c, "pair reduce");
   std::vector<double> h;
   for (int i = 0; i < L - 1; ++i) {
@@ -1113,7 +1116,8 @@ pdadmm_status pdadmm_predict(pdadmm_ctx* c, int32_t* pred, float* logits, const 
     const LayerBufs& b = c->lay[i];
     GemmProb F = make_nt(in, ld_in, b.W, b.ld_in, b.T, b.ld_out, N, b.n_out, b.n_in);
     F.e0 = b.b;
-    F.beta = i < L - 1 ? 1.0f : 0.0f;   // ReLU on every layer but the output layer
+    F.beta = i < L - 1 ? 1.0f : 0.0f;   // f on every layer but the output layer
+    F.slope = c->cfg.leaky_slope;
     hipLaunchKernelGGL((gemm_one_kernel<Tile, true, EpiBiasAct>), dim3(xcd_padded(F.nblk, c->panel)), dim3(256), 0,
                        c->stream, F, c->panel);
     LAUNCH_CHECK(c, "gemm predict");

@@ -11,7 +11,8 @@ from tests.helpers import F32, F64, grid_of, rel_l2
 def config_of(w, **kw) -> P.Config:
     q = w.quant
     base = dict(n_nodes=w.n_nodes, dims=list(w.dims), rho=w.rho, nu=w.nu, quantize=(2 if w.quant_q else 1) if q else 0,
-                q_lo=q[0] if q else -1.0, q_hi=q[1] if q else 1.0, q_levels=q[2] if q else 256)
+                q_lo=q[0] if q else -1.0, q_hi=q[1] if q else 1.0, q_levels=q[2] if q else 256,
+                leaky_slope=w.slope)
     base.update(kw)
     return P.Config(**base)
 
@@ -65,7 +66,7 @@ def round_state_to_fp32(st):
     return st
 
 
-def z_branch_flips(gz, z_ref, a_rows, q_old, z_old, what="", far=1e-3, h_tol=1e-4):
+def z_branch_flips(gz, z_ref, a_rows, q_old, z_old, what="", far=1e-3, h_tol=1e-4, slope=0.0):
     """Hidden-layer z-update: where the two ReLU candidates of the closed form have (almost) the same
     subproblem value, rounding decides which one is taken and both are correct minimisers. Returns the
     mask of elements where the GPU took the other candidate than the oracle, after checking that each
@@ -82,8 +83,8 @@ def z_branch_flips(gz, z_ref, a_rows, q_old, z_old, what="", far=1e-3, h_tol=1e-
     rows, cols = np.nonzero(cand)
     a = a_rows(rows)[np.arange(rows.size), cols]
     qo, zo = q_old[rows, cols], z_old[rows, cols]
-    h_gpu = O.z_subproblem_value(gz[rows, cols].astype(F64), a, qo, zo)
-    h_ref = O.z_subproblem_value(z_ref[rows, cols], a, qo, zo)
+    h_gpu = O.z_subproblem_value(gz[rows, cols].astype(F64), a, qo, zo, slope)
+    h_ref = O.z_subproblem_value(z_ref[rows, cols], a, qo, zo, slope)
     assert np.all(h_gpu <= h_ref + h_tol * np.abs(h_ref) + 1e-30), \
         f"{what}: a differing z element is not a tie of the two candidates: {h_gpu} vs {h_ref}"
     return cand, n
@@ -113,7 +114,7 @@ def compare_state(ctx, st, tol, what="", before=None):
         skip = None
         if before is not None and i < L - 1:
             skip, n = z_branch_flips(gz, st.z[i], lambda rows: st.p[i][rows] @ st.W[i].T + st.b[i],
-                                     before.q[i], before.z[i], what=f"{what} z{l}")
+                                     before.q[i], before.z[i], what=f"{what} z{l}", slope=st.slope)
             if n:
                 lines.append(f"{what} z{l}: {n} tie elements left out")
         chk(f"z{l}", gz, st.z[i], skip)

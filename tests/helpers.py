@@ -30,7 +30,7 @@ def oracle_state(w, inp=None, perturbed=True, **kw):
     """Forward-consistent oracle state, optionally perturbed (all arrays fp32-representable)."""
     inp = oracle_inputs(w) if inp is None else inp
     g = grid_of(w)
-    st = O.init_forward(inp["X_aug"], inp["W"], inp["b"], inp["y"], w.rho, w.nu, grid=g, quantize_q=w.quant_q, **kw)
+    st = O.init_forward(inp["X_aug"], inp["W"], inp["b"], inp["y"], w.rho, w.nu, grid=g, quantize_q=w.quant_q, slope=w.slope, **kw)
     if perturbed:
         quant = (lambda a: O.quantize(a, g)[1]) if g is not None else None
         z, q, p, u = perturb_state(w, [a.astype(F32) for a in st.z], [a.astype(F32) for a in st.q],

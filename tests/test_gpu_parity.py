@@ -155,6 +155,7 @@ CASES = {
     "C4-small": lambda: scaled_workload("C4", 600, hidden=36, n_layers=12, feat_dim=12),
     "C5-small": lambda: scaled_workload("C5", 1300, hidden=136, n_layers=4, feat_dim=20),
     "C5pq-small": lambda: dataclasses.replace(scaled_workload("C5", 900, hidden=72, n_layers=4, feat_dim=12), quant_q=True),
+    "leaky-small": lambda: dataclasses.replace(scaled_workload("C2", 1100, hidden=90, n_layers=4, feat_dim=14), slope=0.05),
     "odd-widths": lambda: dataclasses.replace(scaled_workload("C2", 333, hidden=50, n_layers=3, feat_dim=5),
                                               n_classes=5, hidden=37),
     "one-layer": lambda: scaled_workload("C2", 400, hidden=10, n_layers=1, feat_dim=6),
@@ -229,7 +230,7 @@ def _same_step_sizes(H, ctx, st):
 
 
 @pytest.mark.parametrize("case,iters", [("C1-full", 10), ("C2-small", 20), ("C3-small", 20), ("C4-small", 20),
-                                        ("C5-small", 20)])
+                                        ("C5-small", 20), ("leaky-small", 20)])
 def test_trajectories(env, case, iters):
     """Free-running trajectories of objective and residual. pdADMM-G: within 1e-3 at every iteration and
     identical step-size decisions. pdADMM-G-Q: rounding noise flips single quantisation indices, the
@@ -315,7 +316,7 @@ def test_quantized_trajectory_step_by_step_along_the_oracle_run(env, case):
     _say(f"  stepwise -Q run: {total_bad} one-level index differences in 20 iterations")
 
 
-@pytest.mark.parametrize("case", ["C1-full", "C5-small", "odd-widths", "one-layer"])
+@pytest.mark.parametrize("case", ["C1-full", "C5-small", "leaky-small", "odd-widths", "one-layer"])
 def test_predict_matches_oracle_forward_pass(env, case):
     """Inference with weights trained for a few iterations: output layer within 1e-5 (relative L2),
     predicted classes equal wherever the two largest outputs are not within rounding of each other,
@@ -360,6 +361,46 @@ def test_iterate_is_bit_reproducible(env):
                     [P.pdadmm_get_var(ctx, P.VAR.W, l + 1) for l in range(st.L)])
     for a, b in zip(*outs):
         assert np.array_equal(a.view(np.uint32), b.view(np.uint32))
+
+
+@pytest.mark.parametrize("case", ["C2-small", "C5-small"])
+def test_checkpoint_and_resume(env, case):
+    """All state read out with get_var after 3 iterations (variables, tau, theta) and written into a fresh
+    context continues the run: 2 more iterations agree with 5 iterations in one go. (The carried
+    W p + b - z is rebuilt from the variables on resume, so agreement is to rounding, not to the bit.)"""
+    torch, P, H = env
+    w = CASES[case]()
+    inp = oracle_inputs(w)
+    st = H.round_state_to_fp32(oracle_state(w, inp))
+    a = H.gpu_context(w, inp, st)
+    P.pdadmm_iterate(a, 3)
+    P.pdadmm_sync(a)
+    L = w.n_layers
+    snap = {}
+    for l in range(1, L + 1):
+        for kind in (P.VAR.W, P.VAR.B, P.VAR.Z, P.VAR.THETA):
+            snap[(kind, l)] = P.pdadmm_get_var(a, kind, l)
+        if l >= 2:
+            snap[(P.VAR.P, l)] = P.pdadmm_get_var(a, P.VAR.P, l)
+            snap[(P.VAR.TAU, l)] = P.pdadmm_get_var(a, P.VAR.TAU, l)
+        if l < L:
+            snap[(P.VAR.Q, l)] = P.pdadmm_get_var(a, P.VAR.Q, l)
+            snap[(P.VAR.U, l)] = P.pdadmm_get_var(a, P.VAR.U, l)
+    b = H.gpu_context(w, inp)                      # fresh context, forward-consistent start
+    for (kind, l), v in snap.items():
+        P.pdadmm_set_var(b, kind, l, v)
+    P.pdadmm_iterate(a, 2)
+    P.pdadmm_iterate(b, 2)
+    P.pdadmm_sync(a)
+    P.pdadmm_sync(b)
+    sa, sb = P.pdadmm_stats(a), P.pdadmm_stats(b)
+    assert np.array_equal(sa["tau"][1:], sb["tau"][1:]) and np.array_equal(sa["theta"], sb["theta"])
+    tol = 1e-5 if w.quant is None else 2e-3
+    for l in range(1, L + 1):
+        for kind in (P.VAR.W, P.VAR.B, P.VAR.Z):
+            assert rel_l2(P.pdadmm_get_var(b, kind, l), P.pdadmm_get_var(a, kind, l)) <= tol, (kind, l)
+    oa, ob = P.pdadmm_objective(a), P.pdadmm_objective(b)
+    assert abs(oa["L_rho"] - ob["L_rho"]) <= 1e-5 * abs(oa["L_rho"])
 
 
 def test_forward_consistent_start_moves_only_last_layer(env):
