@@ -403,6 +403,45 @@ def test_checkpoint_and_resume(env, case):
     assert abs(oa["L_rho"] - ob["L_rho"]) <= 1e-5 * abs(oa["L_rho"])
 
 
+def test_training_learns_planted_labels_then_grows_greedily(env):
+    """End to end on a learnable task (labels planted by a random linear teacher on the augmented
+    features): 40 iterations from the forward-consistent start lift the training accuracy well above
+    chance, on the GPU as in the oracle, with matching accuracy. Then the greedy layer-wise schedule of
+    Section 3.2: the trained hidden layers start a deeper model (fresh layers in between, trained output
+    layer kept) which trains on."""
+    torch, P, H = env
+    from workloads import planted_labels, make_weights
+    w = dataclasses.replace(scaled_workload("C2", 600, hidden=32, n_layers=3, feat_dim=8))
+    inp = oracle_inputs(w)
+    inp["y"] = planted_labels(w, inp["X_aug"])
+    st = O.init_forward(inp["X_aug"], inp["W"], inp["b"], inp["y"], w.rho, w.nu)
+    ctx = H.gpu_context(w, inp)                   # the library's own forward-consistent start
+    chance = 1.0 / w.n_classes
+    acc0 = P.pdadmm_predict(ctx)["accuracy"]
+    O.iterate(st, 40)
+    P.pdadmm_iterate(ctx, 40)
+    P.pdadmm_sync(ctx)
+    acc_gpu = P.pdadmm_predict(ctx)["accuracy"]
+    acc_cpu = O.accuracy(O.predict(st)[0], inp["y"])
+    _say(f"  planted task: accuracy start {acc0:.3f} -> GPU {acc_gpu:.3f}, oracle {acc_cpu:.3f} (chance {chance:.3f})")
+    assert acc_cpu > chance + 0.3 and acc_gpu > chance + 0.3
+    assert abs(acc_gpu - acc_cpu) <= 0.02
+    # greedy growth: 3 -> 5 layers
+    deep = dataclasses.replace(w, n_layers=5, name="deep")
+    Wn, bn = make_weights(deep)
+    Wt = [P.pdadmm_get_var(ctx, P.VAR.W, l) for l in (1, 2, 3)]
+    bt = [P.pdadmm_get_var(ctx, P.VAR.B, l) for l in (1, 2, 3)]
+    inp2 = dict(inp, W=[Wt[0], Wt[1], Wn[2], Wn[3], Wt[2]], b=[bt[0], bt[1], bn[2], bn[3], bt[2]])
+    ctx2 = H.gpu_context(deep, inp2)
+    obj = [P.pdadmm_objective(ctx2)["F"]]
+    for _ in range(3):
+        P.pdadmm_iterate(ctx2, 10)
+        obj.append(P.pdadmm_objective(ctx2)["F"])
+    acc2 = P.pdadmm_predict(ctx2)["accuracy"]
+    _say(f"  grown to 5 layers: F {obj[0]:.4f} -> {obj[-1]:.4f}, accuracy {acc2:.3f}")
+    assert obj[-1] < obj[0] and acc2 > chance + 0.2
+
+
 def test_forward_consistent_start_moves_only_last_layer(env):
     torch, P, H = env
     w = small("C1", n=500, hidden=24, n_layers=4, feat_dim=8)

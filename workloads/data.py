@@ -119,3 +119,13 @@ def layer_window(w: Workload, layer: int, quantizer=None, scale: float = 0.5):
         out["z_next"] = noise_like(rng, (N, n_next)) * s
         out["p_next"] = act(n_out)
     return out
+
+
+S_TEACHER = 5
+
+
+def planted_labels(w: Workload, X_aug: np.ndarray) -> np.ndarray:
+    """Learnable labels for end-to-end checks: class = argmax of a seeded random linear map of the
+    augmented features the caller passes in (the uniform labels of make_labels carry no signal)."""
+    T = stream_rng(w, S_TEACHER).standard_normal((X_aug.shape[1], w.n_classes))
+    return np.argmax(X_aug.astype(np.float64) @ T, axis=1).astype(np.int32)
