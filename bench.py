@@ -34,7 +34,22 @@ def gemm_flops_per_iteration(dims, n_nodes):
     per = [2.0 * dims[i + 1] * dims[i] * n_nodes for i in range(L)]
     return dict(gemm_pgrad=sum(per[1:]),            # W^T r          (l >= 2)
                 gemm_trial=sum(per[1:]) + sum(per),  # W g (l >= 2) and G p (all l): two launches
-                gemm_wgrad=sum(per))                 # r p^T          (all l)
+                gemm_wgrad=sum(per),                 # r p^T          (all l)
+                p_trial_launch=sum(per[1:]))         # one more W d launch per extra -Q backtracking round
+
+
+def elementwise_bytes_per_iteration(dims, n_nodes, quant):
+    """Algorithmic HBM bytes of the streaming kernels of one iteration (fp32 arrays of N x n, each counted
+    once per read and once per write): p-step 3 passes over [N, n_{l-1}] and 3 over [N, n_l] (l >= 2);
+    residual update + column sums 3 passes over [N, n_l] (all l); fused z/q/u 5 reads + 4 writes over
+    [N, n_l] (l < L). The -Q projection kernels are left out (they run a data-dependent number of times)."""
+    L = len(dims) - 1
+    e = 4.0 * n_nodes
+    out = dict(resid_colsum=sum(3 * e * dims[i + 1] for i in range(L)),
+               zqu=sum(9 * e * dims[i + 1] for i in range(L - 1)))
+    if not quant:
+        out["p_step"] = sum(3 * e * (dims[i] + dims[i + 1]) for i in range(1, L))
+    return out
 
 
 def build_problem(w, device):
@@ -118,7 +133,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="C2", help="C1..C5, C5pq (default C2: the configuration the metric is quoted on)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--all-classes", action="store_true", help="time every kernel class (adds event overhead)")
+    ap.add_argument("--dominant-only", action="store_true",
+                    help="record HIP events around the dominant kernel class only (default: every class)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy (reference point for FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
@@ -147,7 +163,7 @@ def main():
     P.pdadmm_iterate(ctx, args.warmup)
     P.pdadmm_sync(ctx)
     dominant = "gemm_trial"
-    mask = (1 << len(P.TIMING_CLASSES)) - 1 if args.all_classes else 1 << P.TIMING_CLASSES.index(dominant)
+    mask = 1 << P.TIMING_CLASSES.index(dominant) if args.dominant_only else (1 << len(P.TIMING_CLASSES)) - 1
     P.pdadmm_timing(ctx, mask)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -163,14 +179,16 @@ def main():
     flops = gemm_flops_per_iteration(w.dims, w.n_nodes)
     ms, launches = timing[dominant]
     launches_per_iter = launches / max(args.steps, 1)
-    flops_per_launch = flops[dominant] / launches_per_iter if launches_per_iter else 0.0
+    # pdADMM-G: two launches per iteration; -Q: one W d launch per backtracking round plus the G p launch
+    trial_flops = flops["gemm_trial"] + max(launches_per_iter - 2.0, 0.0) * flops["p_trial_launch"]
+    flops_per_launch = trial_flops / launches_per_iter if launches_per_iter else 0.0
     avg_ms = ms / launches if launches else float("nan")
     achieved = flops_per_launch / (avg_ms * 1e-3) / 1e12 if launches else float("nan")
     roofline = dict(bound="mfma", kernel="gemm_kernel<true, EpiStoreNorm> (fp32 MFMA 32x32x2; W g / G p products)",
                     achieved=achieved, peak=MFMA_FP32_PEAK_TFLOPS, unit="TFLOP/s", frac=achieved / MFMA_FP32_PEAK_TFLOPS,
                     traffic=MEASURED_TRAFFIC_BYTES.get(w.name), avg_launch_ms=avg_ms, launches=launches,
                     flop_per_launch=flops_per_launch)
-    total_gemm_flops = sum(flops.values())
+    total_gemm_flops = flops["gemm_pgrad"] + flops["gemm_wgrad"] + trial_flops
     out = dict(metric="ADMM iterations/sec (all layers)", value=args.steps / dt, unit="iterations/s", n_gpus=1,
                steps=args.steps, warmup=args.warmup, ms_per_step=dt / args.steps * 1e3, higher_is_better=True,
                scaling="weak", vs_baseline=None, dtype="f32", data="synthetic",
@@ -182,8 +200,19 @@ def main():
                roofline=roofline,
                augment_ms=info["augment_ms"], objective_after=obj["L_rho"],
                p_trials=[int(x) for x in stats["p_trials"]], w_trials=[int(x) for x in stats["w_trials"]])
-    if args.all_classes:
-        out["class_ms_per_step"] = {k: v[0] / args.steps for k, v in timing.items() if v[1]}
+    if not args.dominant_only:
+        cls = {k: v[0] / args.steps for k, v in timing.items() if v[1]}
+        out["class_ms_per_step"] = cls
+        gemm_ms = sum(cls.get(k, 0.0) for k in ("gemm_pgrad", "gemm_trial", "gemm_wgrad", "splitk_reduce"))
+        launched = total_gemm_flops
+        eb = elementwise_bytes_per_iteration(w.dims, w.n_nodes, w.quant)
+        ew_ms = sum(cls.get(k, 0.0) for k in eb)
+        out["phases"] = dict(
+            gemm=dict(ms=gemm_ms, tflops=launched / (gemm_ms * 1e-3) / 1e12 if gemm_ms else None,
+                      frac_of_mfma_peak=launched / (gemm_ms * 1e-3) / 1e12 / MFMA_FP32_PEAK_TFLOPS if gemm_ms else None),
+            elementwise=dict(ms=ew_ms, gbs=sum(eb.values()) / (ew_ms * 1e-3) / 1e9 if ew_ms else None,
+                             frac_of_hbm_peak=sum(eb.values()) / (ew_ms * 1e-3) / 1e9 / HBM_PEAK_GBS if ew_ms else None,
+                             per_kernel_gbs={k: eb[k] / (cls[k] * 1e-3) / 1e9 for k in eb if cls.get(k)}))
     if not args.no_cpu_baseline:
         del ctx
         torch.cuda.empty_cache()
