@@ -206,6 +206,14 @@ bool config_ok(const pdadmm_config* c, std::string* why) {
   for (int i = 0; i <= c->n_layers; ++i)
     if (c->dims[i] < 1) return bad("a layer width is < 1");
   if (c->dims[c->n_layers] > 1024) return bad("n_L > 1024 classes is not supported");
+  {
+    // a grouped streaming launch covers up to kMaxGroup layers with one block per 256 float4 groups:
+    // the block count must fit the 31-bit grid size
+    int widest = 0;
+    for (int i = 0; i <= c->n_layers; ++i) widest = std::max(widest, c->dims[i]);
+    const double blocks = (double)c->n_nodes * ((widest + 3) / 4) / 256.0 * std::min(c->n_layers * 2, 2 * kMaxGroup);
+    if (blocks > 2.0e9) return bad("n_nodes x layer width is too large for one grouped launch");
+  }
   if (!(c->rho > 0.f) || !(c->nu > 0.f)) return bad("rho and nu must be > 0");
   if (c->quantize < 0 || c->quantize > 2) return bad("quantize must be 0, 1 or 2");
   if (c->quantize) {
@@ -1178,7 +1186,7 @@ const char* pdadmm_last_error(const pdadmm_ctx* c) { return c ? c->msg.c_str() :
 
 void pdadmm_destroy(pdadmm_ctx* c) {
   if (!c) return;
-  if (c->stream || true) (void)hipStreamSynchronize(c->stream);
+  (void)hipStreamSynchronize(c->stream);
   if (c->h_flags) (void)hipHostFree(c->h_flags);
   for (auto& t : c->timed) {
     (void)hipEventDestroy(t.a);

@@ -8,6 +8,11 @@
 
 namespace pdadmm {
 
+// The sum over a row is sequential by definition (fp32, CSR order), but the gathers are independent:
+// they are issued in batches of kSpmmBatch edges before the ordered multiply-adds consume them, so a
+// hub row of a power-law graph (thousands of entries) costs a few memory round trips, not one per entry.
+constexpr int kSpmmBatch = 16;
+
 template <int VEC>
 __global__ __launch_bounds__(256) void spmm_hop_kernel(int n, const int* __restrict__ rowptr,
                                                        const int* __restrict__ colidx,
@@ -23,7 +28,40 @@ __global__ __launch_bounds__(256) void spmm_hop_kernel(int n, const int* __restr
   const int beg = rowptr[row], end = rowptr[row + 1];
   if (VEC == 4) {
     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-    for (int e = beg; e < end; ++e) {
+    int e = beg;
+    for (; e + kSpmmBatch <= end; e += kSpmmBatch) {
+      float a[kSpmmBatch];
+      float4 x[kSpmmBatch];
+#pragma unroll
+      for (int k = 0; k < kSpmmBatch; ++k) {
+        a[k] = vals[e + k];
+        x[k] = *reinterpret_cast<const float4*>(src + (size_t)colidx[e + k] * ld + c0);
+      }
+#pragma unroll
+      for (int k = 0; k < kSpmmBatch; ++k) {
+        acc.x = add_rn(acc.x, mul_rn(a[k], x[k].x));
+        acc.y = add_rn(acc.y, mul_rn(a[k], x[k].y));
+        acc.z = add_rn(acc.z, mul_rn(a[k], x[k].z));
+        acc.w = add_rn(acc.w, mul_rn(a[k], x[k].w));
+      }
+    }
+    for (; e + 4 <= end; e += 4) {
+      float a[4];
+      float4 x[4];
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        a[k] = vals[e + k];
+        x[k] = *reinterpret_cast<const float4*>(src + (size_t)colidx[e + k] * ld + c0);
+      }
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        acc.x = add_rn(acc.x, mul_rn(a[k], x[k].x));
+        acc.y = add_rn(acc.y, mul_rn(a[k], x[k].y));
+        acc.z = add_rn(acc.z, mul_rn(a[k], x[k].z));
+        acc.w = add_rn(acc.w, mul_rn(a[k], x[k].w));
+      }
+    }
+    for (; e < end; ++e) {
       const float a = vals[e];
       const float4 x = *reinterpret_cast<const float4*>(src + (size_t)colidx[e] * ld + c0);
       acc.x = add_rn(acc.x, mul_rn(a, x.x));
@@ -34,7 +72,18 @@ __global__ __launch_bounds__(256) void spmm_hop_kernel(int n, const int* __restr
     *reinterpret_cast<float4*>(dst + (size_t)row * ld + c0) = acc;
   } else {
     float acc = 0.f;
-    for (int e = beg; e < end; ++e)
+    int e = beg;
+    for (; e + 8 <= end; e += 8) {
+      float a[8], x[8];
+#pragma unroll
+      for (int k = 0; k < 8; ++k) {
+        a[k] = vals[e + k];
+        x[k] = src[(size_t)colidx[e + k] * ld + c0];
+      }
+#pragma unroll
+      for (int k = 0; k < 8; ++k) acc = add_rn(acc, mul_rn(a[k], x[k]));
+    }
+    for (; e < end; ++e)
       acc = add_rn(acc, mul_rn(vals[e], src[(size_t)colidx[e] * ld + c0]));
     dst[(size_t)row * ld + c0] = acc;
   }
