@@ -34,8 +34,7 @@ def gemm_flops_per_iteration(dims, n_nodes):
     per = [2.0 * dims[i + 1] * dims[i] * n_nodes for i in range(L)]
     return dict(gemm_pgrad=sum(per[1:]),            # W^T r          (l >= 2)
                 gemm_trial=sum(per[1:]) + sum(per),  # W g (l >= 2) and G p (all l): two launches
-                gemm_wgrad=sum(per),                 # r p^T          (all l)
-                p_trial_launch=sum(per[1:]))         # one more W d launch per extra -Q backtracking round
+                gemm_wgrad=sum(per))                 # r p^T          (all l)
 
 
 def elementwise_bytes_per_iteration(dims, n_nodes, quant):
@@ -165,6 +164,7 @@ def main():
     dominant = "gemm_trial"
     mask = 1 << P.TIMING_CLASSES.index(dominant) if args.dominant_only else (1 << len(P.TIMING_CLASSES)) - 1
     P.pdadmm_timing(ctx, mask)
+    products_before = P.pdadmm_stats(ctx)["p_products"]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     P.pdadmm_iterate(ctx, args.steps)
@@ -179,8 +179,13 @@ def main():
     flops = gemm_flops_per_iteration(w.dims, w.n_nodes)
     ms, launches = timing[dominant]
     launches_per_iter = launches / max(args.steps, 1)
-    # pdADMM-G: two launches per iteration; -Q: one W d launch per backtracking round plus the G p launch
-    trial_flops = flops["gemm_trial"] + max(launches_per_iter - 2.0, 0.0) * flops["p_trial_launch"]
+    # step-direction products actually computed (pdADMM-G: one per layer l >= 2 and iteration; -Q: one per
+    # backtracking trial of the layer; layers whose search has ended sit out the later launches) plus the
+    # G p products of all layers
+    n_products = stats["p_products"] - products_before
+    per_layer = [2.0 * w.dims[i + 1] * w.dims[i] * w.n_nodes for i in range(w.n_layers)]
+    trial_flops = (sum(float(n_products[i]) * per_layer[i] for i in range(w.n_layers)) / max(args.steps, 1)
+                   + sum(per_layer))
     flops_per_launch = trial_flops / launches_per_iter if launches_per_iter else 0.0
     avg_ms = ms / launches if launches else float("nan")
     achieved = flops_per_launch / (avg_ms * 1e-3) / 1e12 if launches else float("nan")

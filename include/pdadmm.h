@@ -193,9 +193,11 @@ pdadmm_status pdadmm_predict(pdadmm_ctx* ctx, int32_t* pred, float* logits, cons
 
 /* HOST outputs, each L entries or NULL: tau_l (entry 0 unused), theta_l, trials used by the last
  * p- and W-update. r_drift (or NULL): relative L2 distance between the carried and a freshly
- * computed W_l p_l + b_l - z_l over all layers. Synchronises. */
+ * computed W_l p_l + b_l - z_l over all layers. p_products (or NULL, L entries): number of
+ * step-direction products W_l g / W_l d computed for layer l since init (one per iteration for
+ * pdADMM-G, one per backtracking trial for -Q). Synchronises. */
 pdadmm_status pdadmm_stats(pdadmm_ctx* ctx, double* tau, double* theta, int32_t* p_trials,
-                           int32_t* w_trials, double* r_drift);
+                           int32_t* w_trials, double* r_drift, int64_t* p_products);
 
 /*
  * Per-launch timing with HIP events recorded on the context's stream around the launches of the

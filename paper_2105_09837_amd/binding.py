@@ -83,7 +83,7 @@ def load_library():
     lib.pdadmm_sync.argtypes = [vp]
     lib.pdadmm_objective.argtypes = [vp, C.POINTER(_CObjective)]
     lib.pdadmm_residual.argtypes = [vp, C.POINTER(C.c_double), vp]
-    lib.pdadmm_stats.argtypes = [vp, vp, vp, vp, vp, vp]
+    lib.pdadmm_stats.argtypes = [vp, vp, vp, vp, vp, vp, vp]
     lib.pdadmm_predict.argtypes = [vp, vp, vp, vp, vp]
     lib.pdadmm_timing.argtypes = [vp, C.c_uint32]
     lib.pdadmm_timing_read.argtypes = [vp, vp, vp, i32]
@@ -348,9 +348,11 @@ def pdadmm_stats(ctx: Context, drift: bool = False) -> dict:
     pt = np.zeros(L, dtype=np.int32)
     wt = np.zeros(L, dtype=np.int32)
     d = C.c_double(0.0)
+    pp = np.zeros(L, dtype=np.int64)
     _check(load_library().pdadmm_stats(ctx.handle, tau.ctypes.data, theta.ctypes.data, pt.ctypes.data,
-                                       wt.ctypes.data, C.addressof(d) if drift else None), "pdadmm_stats", ctx)
-    return dict(tau=tau, theta=theta, p_trials=pt, w_trials=wt, r_drift=d.value if drift else None)
+                                       wt.ctypes.data, C.addressof(d) if drift else None, pp.ctypes.data),
+           "pdadmm_stats", ctx)
+    return dict(tau=tau, theta=theta, p_trials=pt, w_trials=wt, r_drift=d.value if drift else None, p_products=pp)
 
 
 def pdadmm_predict(ctx: Context, mask=None, want_logits: bool = False) -> dict:

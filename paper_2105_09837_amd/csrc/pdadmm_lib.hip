@@ -132,6 +132,7 @@ struct pdadmm_ctx {
   int panel_tn = 16;          // the same for the W-gradient products (all tiles of one node chunk)
   bool dirty = true;
   long iter = 0;
+  std::vector<long long> p_products;   // per layer: step-direction products (W g / W d) computed since init
   std::string msg;
   // optional per-launch timing with HIP events on the context's stream
   struct TimedLaunch { int cls; hipEvent_t a, b; };
@@ -557,6 +558,7 @@ pdadmm_status phase_p(pdadmm_ctx* c) {
   if (!g.quantize) {
     { TIMED(c, kClsGemmTrial); launch_gemm<true, EpiStoreNorm>(c, c->g_ptrial, 0); }
     LAUNCH_CHECK(c, "gemm ptrial");
+    for (int i = 1; i < L; ++i) ++c->p_products[i];
     { TIMED(c, kClsSelect); hipLaunchKernelGGL(select_step_kernel, dim3(L - 1), dim3(256), 0, c->stream, c->sel_p, c->scal, 0, g.rho, g.nu,
                        g.bt_eta, g.bt_max_trials, c->err); }
     LAUNCH_CHECK(c, "select tau");
@@ -572,7 +574,12 @@ pdadmm_status phase_p(pdadmm_ctx* c) {
     HIP_TRY(c, hipMemcpyAsync(c->h_flags, c->flags, sizeof(int) * L, hipMemcpyDeviceToHost, c->stream));
     HIP_TRY(c, hipStreamSynchronize(c->stream));
     bool any = false;
-    for (int i = 1; i < L; ++i) any = any || c->h_flags[i] != 0;
+    for (int i = 1; i < L; ++i) {
+      if (c->h_flags[i] != 0) {
+        any = true;
+        ++c->p_products[i];      // this layer's trial product runs in the launch below
+      }
+    }
     if (!any) break;
     { TIMED(c, kClsQuantTrial); launch_group(c, c->g_quant, quant_trial_kernel, (const LayerScal*)c->scal, c->grid); }
     LAUNCH_CHECK(c, "quant trial");
@@ -855,6 +862,7 @@ pdadmm_status pdadmm_init(pdadmm_ctx** out, const pdadmm_config* cfg, void* work
   c->L = cfg->n_layers;
   c->dims.assign(cfg->dims, cfg->dims + cfg->n_layers + 1);
   c->cfg.dims = c->dims.data();
+  c->p_products.assign(cfg->n_layers, 0);
   c->stream = static_cast<hipStream_t>(stream);
   if (cfg->quantize) c->grid = make_grid(cfg->q_lo, cfg->q_hi, cfg->q_levels);
   const size_t need = plan(c, nullptr);
@@ -1094,7 +1102,7 @@ pdadmm_status pdadmm_residual(pdadmm_ctx* c, double* total, double* per_layer) {
 }
 
 pdadmm_status pdadmm_stats(pdadmm_ctx* c, double* tau, double* theta, int32_t* p_trials, int32_t* w_trials,
-                           double* r_drift) {
+                           double* r_drift, int64_t* p_products) {
   if (!c) return PDADMM_EINVAL;
   std::vector<LayerScal> hs(c->L);
   HIP_TRY(c, hipMemcpyAsync(hs.data(), c->scal, sizeof(LayerScal) * c->L, hipMemcpyDeviceToHost, c->stream));
@@ -1104,6 +1112,7 @@ pdadmm_status pdadmm_stats(pdadmm_ctx* c, double* tau, double* theta, int32_t* p
     if (theta) theta[i] = hs[i].theta;
     if (p_trials) p_trials[i] = hs[i].p_trials;
     if (w_trials) w_trials[i] = hs[i].w_trials;
+    if (p_products) p_products[i] = c->p_products[i];
   }
   if (r_drift) {
     double lin = 0, drift = 0;
