@@ -162,6 +162,32 @@ CASES = {
 }
 
 
+def test_output_layer_wide_and_partly_labelled(env):
+    """z_L-update (FISTA) and risk with many classes (several classes per lane) and with a training mask
+    (unlabelled nodes take z_L = W_L p_L + b_L; only labelled nodes enter the risk)."""
+    torch, P, H = env
+    for n_classes, n in ((130, 300), (1000, 150), (70, 257)):
+        w = dataclasses.replace(scaled_workload("C2", n, hidden=24, n_layers=2, feat_dim=6), n_classes=n_classes)
+        _say(f"wide output layer: {n_classes} classes, {n} nodes")
+        inp = oracle_inputs(w)
+        mask = stream_rng(w, 9).random(n) < 0.6
+        st = H.round_state_to_fp32(oracle_state(w, inp, mask=mask))
+        assert st.mask is not None
+        ctx = H.gpu_context(w, inp, st)
+        for k in range(2):
+            O.iterate(st)
+            P.pdadmm_iterate(ctx, 1)
+            P.pdadmm_sync(ctx)
+            ok, worst, rep = H.compare_state(ctx, st, TOL_STATE, what=f"C={n_classes} it {k + 1}")
+            assert ok, rep
+            og, oo = P.pdadmm_objective(ctx), O.objective(st)
+            assert abs(og["risk"] - oo["risk"]) <= TOL_TRAJ * abs(oo["risk"])
+            assert abs(og["L_rho"] - oo["L_rho"]) <= TOL_TRAJ * abs(oo["L_rho"])
+        # unlabelled nodes: z_L equals the linear output exactly as carried (residual row = 0)
+        r = P.pdadmm_get_var(ctx, P.VAR.RESID, 2)
+        assert np.max(np.abs(r[~mask])) <= 1e-5 * max(1.0, np.max(np.abs(st.z[1])))
+
+
 def _check_step_sizes(H, ctx, st):
     tau, theta, pt, wt = H.step_sizes(ctx)
     for i in range(st.L):
