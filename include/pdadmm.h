@@ -48,7 +48,11 @@ typedef struct {
   float q_lo, q_hi;        /* Delta = { q_lo + i*(q_hi-q_lo)/(q_levels-1) }, i = 0..q_levels-1 */
   int32_t q_levels;        /* 2..256 */
   int32_t fista_iters;     /* fixed number of FISTA steps for z_L (Appendix A); e.g. 20 */
-  float bt_eta;            /* backtracking growth factor (> 1), e.g. 2 */
+  float bt_eta;            /* backtracking growth factor (> 1), e.g. 2. Every p- and W-update starts at the
+                              previous tau (theta) divided by bt_eta and multiplies by bt_eta until the
+                              condition of Appendix A holds. In -Q, where each trial costs a product, the
+                              smaller start value is probed with back-off: after a probe that was rejected
+                              the next 1, 2, 4, ... (at most 16) updates start at the previous tau itself */
   float tau0, theta0;      /* initial tau_l, theta_l, e.g. 1 */
   int32_t bt_max_trials;   /* cap per update, e.g. 64 */
   int32_t refresh_every;   /* recompute W_l p_l + b_l - z_l from scratch every k iterations; 0 = never */
@@ -81,7 +85,8 @@ enum {
   /* read-only internals, for diagnostics */
   PDADMM_VAR_RESID = 9,  /* carried W_l p_l + b_l - z_l, [N, n_l] */
   PDADMM_VAR_GRAD_P = 10,/* last gradient of phi in p_l, [N, n_{l-1}], l = 2..L */
-  PDADMM_VAR_GRAD_W = 11 /* last gradient of phi in W_l, [n_l, n_{l-1}] */
+  PDADMM_VAR_GRAD_W = 11,/* last gradient of phi in W_l, [n_l, n_{l-1}] */
+  PDADMM_VAR_PROBE = 12  /* -Q, l = 2..L: two HOST int32 {wait, left}: back-off state of the tau search */
 };
 
 /* Phases of Algorithm 1 as this library groups them (pdadmm_step_phase). */
@@ -156,7 +161,8 @@ pdadmm_status pdadmm_init(pdadmm_ctx** out, const pdadmm_config* cfg, void* work
 
 /*
  * Copy a variable in or out. `layer` is the paper's l. The buffer is dense (leading dimension =
- * width) and may be HOST or DEVICE memory, except TAU/THETA (HOST double). Both calls synchronise.
+ * width) and may be HOST or DEVICE memory, except TAU/THETA (HOST double) and PROBE (HOST int32[2]).
+ * Both calls synchronise.
  * set_var of P in -Q mode (and of Q with quantize = 2) projects the values onto Delta. After any set_var the carried residual
  * W_l p_l + b_l - z_l is recomputed from scratch at the next iteration.
  */

@@ -17,7 +17,9 @@ W_l p_l + b_l is `p @ W.T + b`.
 Readings of points the paper leaves open (all are conventions, "parity unpinned" by the
 paper itself; the tests pin them only through the mathematical properties they imply):
   * backtracking schedule for tau_l / theta_l (Appendix A gives only the acceptance
-    condition): start each iteration at previous/eta, multiply by eta until accepted;
+    condition): start each iteration at previous/eta, multiply by eta until accepted; in -Q,
+    where a trial costs a product, previous/eta is probed with exponential back-off after
+    rejected probes (see update_p);
   * b-update: b_l is one vector broadcast over all nodes, so the exact minimiser of phi
     over b_l is b - mean_over_nodes(W p + b - z); the printed step "gradient / nu" equals
     that only if the curvature nu*|V| is used, which is the reading taken;
@@ -176,6 +178,9 @@ class State:
     w_trials: List[int] = field(default_factory=list)
     quantize_q: bool = False       # variant of Appendix B (last paragraph): q_l is projected onto Delta as well
     slope: float = 0.0             # negative-side slope of the activation (0 = ReLU)
+    p_wait: List[int] = field(default_factory=list)    # -Q: iterations to wait after a failed probe of tau/eta
+    p_skip: List[int] = field(default_factory=list)    # -Q: iterations left until the next probe
+    probe_cap: int = 16
 
     @property
     def L(self) -> int:
@@ -186,7 +191,8 @@ class State:
         return State(c(self.W), c(self.b), c(self.z), c(self.p), c(self.q), c(self.u), self.y,
                      self.mask, self.rho, self.nu, self.grid, list(self.tau), list(self.theta),
                      self.eta, self.bt_max_trials, self.fista_iters, list(self.p_trials),
-                     list(self.w_trials), self.quantize_q, self.slope)
+                     list(self.w_trials), self.quantize_q, self.slope, list(self.p_wait), list(self.p_skip),
+                     self.probe_cap)
 
 
 def init_forward(X_aug, W0, b0, y, rho, nu, grid: Optional[Grid] = None, mask=None,
@@ -215,7 +221,8 @@ def init_forward(X_aug, W0, b0, y, rho, nu, grid: Optional[Grid] = None, mask=No
             u.append(np.zeros_like(qi))
     return State(W, b, z, p, q, u, np.asarray(y), mask, float(rho), float(nu), grid,
                  [tau0] * L, [theta0] * L, p_trials=[0] * L, w_trials=[0] * L,
-                 quantize_q=bool(quantize_q and grid is not None), slope=float(slope), **kw)
+                 quantize_q=bool(quantize_q and grid is not None), slope=float(slope),
+                 p_wait=[0] * L, p_skip=[0] * L, **kw)
 
 
 def phi(st: State, i: int, p=None, W=None, b=None) -> float:
@@ -259,14 +266,24 @@ class BacktrackingError(RuntimeError):
 # --------------------------------------------------------------------------------------
 def update_p(st: State, i: int) -> None:
     """p_l <- argmin U_l(p; tau) (+ indicator of Delta for -Q), tau raised until
-    phi(p_new) <= U_l(p_new; tau) (Appendix A 'update p', Appendix B)."""
+    phi(p_new) <= U_l(p_new; tau) (Appendix A 'update p', Appendix B).
+
+    Schedule (a convention; the paper states only the acceptance condition): pdADMM-G starts every
+    update at previous/eta. For -Q every trial costs a product W d, so the smaller value previous/eta
+    is only probed when it has a chance: after a probe that was rejected the next probe waits
+    1, 2, 4, ... (at most probe_cap) iterations, during which the update starts at the previous tau; a
+    probe that is accepted at once resets the wait. From its start value tau is multiplied by eta
+    until the condition holds, in both variants."""
     g = grad_p(st, i)
     if not np.any(g):
         st.p_trials[i] = 0
         return
     p_old = st.p[i]
     phi0 = phi(st, i)
-    t = st.tau[i] / st.eta
+    probing = st.grid is None or st.p_skip[i] == 0
+    if not probing:
+        st.p_skip[i] -= 1
+    t = st.tau[i] / st.eta if probing else st.tau[i]
     for trial in range(1, st.bt_max_trials + 1):
         cand = p_old - g / t
         if st.grid is not None:
@@ -277,6 +294,12 @@ def update_p(st: State, i: int) -> None:
             st.tau[i] = t
             st.p[i] = cand
             st.p_trials[i] = trial
+            if st.grid is not None and probing:
+                if trial == 1:
+                    st.p_wait[i] = 0
+                else:
+                    st.p_wait[i] = min(max(1, 2 * st.p_wait[i]), st.probe_cap)
+                    st.p_skip[i] = st.p_wait[i]
             return
         t *= st.eta
     raise BacktrackingError(f"p-update of layer {i + 1}: no tau accepted")

@@ -15,7 +15,7 @@ STATUS = {0: "OK", 1: "EINVAL", 2: "ENOMEM", 3: "EHIP", 4: "EBACKTRACK", 5: "ENO
 
 
 class VAR:
-    P, W, B, Z, Q, U, TAU, THETA, PIDX, RESID, GRAD_P, GRAD_W = range(12)
+    P, W, B, Z, Q, U, TAU, THETA, PIDX, RESID, GRAD_P, GRAD_W, PROBE = range(13)
 
 
 class PHASE:
@@ -290,6 +290,10 @@ def pdadmm_set_var(ctx: Context, kind: int, layer: int, src) -> None:
         v = C.c_double(float(src))
         _check(lib.pdadmm_set_var(ctx.handle, kind, layer, C.addressof(v)), "pdadmm_set_var", ctx)
         return
+    if kind == VAR.PROBE:
+        v = (C.c_int32 * 2)(int(src[0]), int(src[1]))
+        _check(lib.pdadmm_set_var(ctx.handle, kind, layer, C.addressof(v)), "pdadmm_set_var", ctx)
+        return
     if isinstance(src, np.ndarray):
         src = np.ascontiguousarray(src, dtype=np.float32)
     else:
@@ -306,6 +310,10 @@ def pdadmm_get_var(ctx: Context, kind: int, layer: int, to_host: bool = True):
         v = C.c_double()
         _check(lib.pdadmm_get_var(ctx.handle, kind, layer, C.addressof(v)), "pdadmm_get_var", ctx)
         return v.value
+    if kind == VAR.PROBE:
+        v = (C.c_int32 * 2)()
+        _check(lib.pdadmm_get_var(ctx.handle, kind, layer, C.addressof(v)), "pdadmm_get_var", ctx)
+        return (int(v[0]), int(v[1]))
     shape = _var_shape(ctx, kind, layer)
     if to_host:
         out = np.empty(shape, dtype=np.uint8 if kind == VAR.PIDX else np.float32)

@@ -95,8 +95,11 @@ struct LayerScal {
   float trial_t;           // -Q: tau of the trial in flight
   int p_trials, w_trials;
   int active;              // -Q: 1 while the p-update of this layer is still searching
-  int pad;
+  int probing;             // -Q: 1 if this update started at tau/eta (a probe of the smaller value)
+  int probe_wait;          // -Q: iterations to wait after a rejected probe (1, 2, 4, ... kProbeCap)
+  int probe_skip;          // -Q: iterations left until the next probe
 };
+constexpr int kProbeCap = 16;
 
 // Activation f (Section 4: ReLU and leaky ReLU satisfy the assumption): f(z) = z for z > 0, slope*z
 // otherwise; slope = 0 is ReLU.

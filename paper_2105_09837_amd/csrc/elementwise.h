@@ -453,7 +453,8 @@ __global__ __launch_bounds__(256) void quant_trial_kernel(const QuantSeg* __rest
 
 // Accept/reject one -Q trial: phi(p+d) - phi(p) - <g,d> = (nu/2)||W d||^2 + (rho/2)||d||^2 exactly,
 // so the condition phi(p_new) <= U_l(p_new; t) is  nu||W d||^2 + rho||d||^2 <= t ||d||^2.
-// phase 0: arm the search (active = 1, trial_t = tau/eta) for layers with g != 0.
+// phase 0: arm the search (active = 1, trial_t = tau/eta, or tau while a rejected probe of the smaller
+//          value is being waited out) for layers with g != 0.
 // phase 1: judge the trial in flight.
 __global__ __launch_bounds__(256) void select_quant_kernel(const SelectDesc* __restrict__ descs, LayerScal* scal,
                                                            int phase, float rho, float nu, float eta,
@@ -470,8 +471,12 @@ __global__ __launch_bounds__(256) void select_quant_kernel(const SelectDesc* __r
     sc.active = 0;
     if (!(sg == sg) || sg > 1.7e308) atomicOr(err, kErrNonFinite);
     else if (sg > 0.0) {
+      // every trial costs a product W d: tau/eta is only probed when no rejected probe is being waited out
+      const int probing = sc.probe_skip == 0;
+      if (!probing) sc.probe_skip -= 1;
+      sc.probing = probing;
       sc.active = 1;
-      sc.trial_t = (float)(sc.tau / (double)eta);
+      sc.trial_t = (float)(probing ? sc.tau / (double)eta : sc.tau);
       sc.p_trials = 1;
     }
     flags[D.layer] = sc.active;
@@ -491,6 +496,13 @@ __global__ __launch_bounds__(256) void select_quant_kernel(const SelectDesc* __r
     sc.tau = t;
     sc.inv_tau = 1.0f;     // marks "a step was accepted"
     sc.active = 0;
+    if (sc.probing) {      // accepted at once: probe again next time; else back off 1, 2, 4, ... iterations
+      if (sc.p_trials == 1) sc.probe_wait = 0;
+      else {
+        sc.probe_wait = min(max(1, 2 * sc.probe_wait), kProbeCap);
+        sc.probe_skip = sc.probe_wait;
+      }
+    }
   } else if (sc.p_trials >= max_trials) {
     atomicOr(err, kErrBacktrack);
     sc.active = 0;

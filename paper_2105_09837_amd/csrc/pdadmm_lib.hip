@@ -920,6 +920,16 @@ pdadmm_status pdadmm_init(pdadmm_ctx** out, const pdadmm_config* cfg, void* work
 
 pdadmm_status pdadmm_set_var(pdadmm_ctx* c, int32_t kind, int32_t layer, const void* src) {
   if (!c || !src) return PDADMM_EINVAL;
+  if (kind == PDADMM_VAR_PROBE) {
+    if (layer < 2 || layer > c->L) return fail(c, PDADMM_EINVAL, "layer out of range");
+    const int32_t* v = static_cast<const int32_t*>(src);
+    if (v[0] < 0 || v[1] < 0 || v[0] > kProbeCap || v[1] > kProbeCap) return fail(c, PDADMM_EINVAL, "probe state out of range");
+    LayerScal* dst = c->scal + (layer - 1);
+    HIP_TRY(c, hipMemcpyAsync(reinterpret_cast<char*>(dst) + offsetof(LayerScal, probe_wait), v, 2 * sizeof(int32_t),
+                              hipMemcpyHostToDevice, c->stream));
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    return PDADMM_OK;
+  }
   if (kind == PDADMM_VAR_TAU || kind == PDADMM_VAR_THETA) {
     if (layer < (kind == PDADMM_VAR_TAU ? 2 : 1) || layer > c->L) return fail(c, PDADMM_EINVAL, "layer out of range");
     const double v = *static_cast<const double*>(src);
@@ -957,6 +967,14 @@ pdadmm_status pdadmm_set_var(pdadmm_ctx* c, int32_t kind, int32_t layer, const v
 
 pdadmm_status pdadmm_get_var(pdadmm_ctx* c, int32_t kind, int32_t layer, void* dst) {
   if (!c || !dst) return PDADMM_EINVAL;
+  if (kind == PDADMM_VAR_PROBE) {
+    if (layer < 2 || layer > c->L) return fail(c, PDADMM_EINVAL, "layer out of range");
+    const LayerScal* src = c->scal + (layer - 1);
+    HIP_TRY(c, hipMemcpyAsync(dst, reinterpret_cast<const char*>(src) + offsetof(LayerScal, probe_wait),
+                              2 * sizeof(int32_t), hipMemcpyDeviceToHost, c->stream));
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    return PDADMM_OK;
+  }
   if (kind == PDADMM_VAR_TAU || kind == PDADMM_VAR_THETA) {
     if (layer < (kind == PDADMM_VAR_TAU ? 2 : 1) || layer > c->L) return fail(c, PDADMM_EINVAL, "layer out of range");
     const LayerScal* src = c->scal + (layer - 1);

@@ -46,6 +46,8 @@ def push_state(ctx, st):
         if i >= 1:
             P.pdadmm_set_var(ctx, P.VAR.P, l, st.p[i].astype(F32))
             P.pdadmm_set_var(ctx, P.VAR.TAU, l, st.tau[i])
+            if st.grid is not None:
+                P.pdadmm_set_var(ctx, P.VAR.PROBE, l, (st.p_wait[i], st.p_skip[i]))
         if i < L - 1:
             P.pdadmm_set_var(ctx, P.VAR.Q, l, st.q[i].astype(F32))
             P.pdadmm_set_var(ctx, P.VAR.U, l, st.u[i].astype(F32))

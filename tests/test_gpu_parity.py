@@ -287,7 +287,12 @@ def test_trajectories(env, case, iters):
             _say(f"  step-size decisions differ from iteration {first_flip} on")
         if first_flip is None:
             worst_obj, worst_res = max(worst_obj, eo, ef), max(worst_res, er)
-            assert eo <= TOL_TRAJ and ef <= TOL_TRAJ and er <= TOL_TRAJ, (k, eo, ef, er)
+            # -Q: single flipped indices (values at a rounding distance from a midpoint of Delta) multiply from
+            # iteration to iteration; the residual ||p - q||, a norm of differences of grid values, feels them
+            # first. Free-running, it is held to 1e-3 for the first half of the run and to 1e-2 after; the
+            # step-by-step test below holds every single iteration to 1e-3.
+            tol_res = TOL_TRAJ if (w.quant is None or k < iters // 2) else 10 * TOL_TRAJ
+            assert eo <= TOL_TRAJ and ef <= TOL_TRAJ and er <= tol_res, (k, eo, ef, er)
         else:
             assert eo <= 0.25 and np.isfinite(rg), (k, eo, er)   # two valid paths of the same problem
     assert first_flip is None or first_flip > iters // 2
@@ -319,6 +324,8 @@ def test_quantized_trajectory_step_by_step_along_the_oracle_run(env, case):
         total_bad += bad
         assert bad <= max(3, 3e-5 * total), (k, bad, total)
         _check_step_sizes(H, ctx, st)
+        for l in range(2, st.L + 1):
+            assert P.pdadmm_get_var(ctx, P.VAR.PROBE, l) == (st.p_wait[l - 1], st.p_skip[l - 1])
         ok, worst, rep = H.compare_state(ctx, st, 2e-3, what=f"step {k + 1}")
         assert ok, rep
         og, oo = P.pdadmm_objective(ctx), O.objective(st)
@@ -409,6 +416,8 @@ def test_checkpoint_and_resume(env, case):
         if l >= 2:
             snap[(P.VAR.P, l)] = P.pdadmm_get_var(a, P.VAR.P, l)
             snap[(P.VAR.TAU, l)] = P.pdadmm_get_var(a, P.VAR.TAU, l)
+            if w.quant is not None:
+                snap[(P.VAR.PROBE, l)] = P.pdadmm_get_var(a, P.VAR.PROBE, l)
         if l < L:
             snap[(P.VAR.Q, l)] = P.pdadmm_get_var(a, P.VAR.Q, l)
             snap[(P.VAR.U, l)] = P.pdadmm_get_var(a, P.VAR.U, l)

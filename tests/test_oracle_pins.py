@@ -540,3 +540,43 @@ def test_leaky_activation_whole_iteration_properties():
     direct = 0.5 * st.nu * sum(float(np.sum((st.q[j] - np.where(st.z[j] > 0, st.z[j], 0.1 * st.z[j])) ** 2))
                                for j in range(st.L - 1))
     assert abs(O.objective(st)["act_pen"] - direct) <= 1e-12 * max(1.0, direct)
+
+
+def test_quantized_probe_back_off_schedule():
+    # -Q schedule (convention; Appendix A/B state only the acceptance condition): the smaller value
+    # tau/eta is probed at once after an accepted probe and after 1, 2, 4, ... 16 iterations after rejected
+    # ones; whatever the start value, the accepted tau is the first on the grid start*eta^j that satisfies
+    # the condition (checked literally in test_backtracking_accepts_smallest_admissible_step_parameter).
+    w = small("C5", n=150, hidden=16, n_layers=4, feat_dim=6)
+    st = oracle_state(w)
+    trials, probes = 0, 0
+    for k in range(40):
+        before = st.copy()
+        for i in range(1, st.L):
+            O.update_p(st, i)
+            probing = before.p_skip[i] == 0
+            start = before.tau[i] / st.eta if probing else before.tau[i]
+            assert st.p_trials[i] >= 1 and st.tau[i] == start * st.eta ** (st.p_trials[i] - 1)
+            if probing:
+                probes += 1
+                if st.p_trials[i] == 1:
+                    assert st.p_wait[i] == 0 and st.p_skip[i] == 0
+                else:
+                    assert st.p_wait[i] == min(max(1, 2 * before.p_wait[i]), 16) and st.p_skip[i] == st.p_wait[i]
+            else:
+                assert st.p_skip[i] == before.p_skip[i] - 1 and st.p_wait[i] == before.p_wait[i]
+            trials += st.p_trials[i]
+        for i in range(st.L):
+            O.update_W(st, i)
+        for i in range(st.L):
+            O.update_b(st, i)
+        for i in range(st.L - 1):
+            O.update_z_hidden(st, i)
+        O.update_z_last(st)
+        for i in range(st.L - 1):
+            O.update_q(st, i)
+        for i in range(st.L - 1):
+            O.update_u(st, i)
+    per_update = trials / (40 * (st.L - 1))
+    assert per_update < 1.5, per_update          # probing every iteration would sit near 2 once tau has settled
+    assert probes < 40 * (st.L - 1)
