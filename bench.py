@@ -121,8 +121,15 @@ def cpu_baseline(w, host):
     t0 = time.perf_counter()
     O.iterate(st, 1)
     dt = time.perf_counter() - t0
+    model = ""
+    try:
+        with open("/proc/cpuinfo") as f:
+            model = next((ln.split(":", 1)[1].strip() for ln in f if ln.startswith("model name")), "")
+    except OSError:
+        pass
     return dict(value=1.0 / dt, unit="iterations/s", cores=int(threads), kind="oracle",
-                sample=f"1 iteration of {w.name} (all {st.L} layers, fp64 numpy), {dt:.1f} s")
+                sample=f"1 iteration of {w.name} (all {st.L} layers, fp64 numpy), {dt:.1f} s",
+                cpu_model=model, os_cpu_count=os.cpu_count())
 
 
 def main():
