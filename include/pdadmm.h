@@ -154,6 +154,9 @@ size_t pdadmm_workspace_bytes(const pdadmm_config* cfg);
  *             b0[l-1] [n_l]: all DEVICE, copied during the call (the caller may free them afterwards).
  *  W0, b0: HOST arrays of L DEVICE pointers. stream: hipStream_t or NULL.
  * The call synchronises the stream before returning.
+ * Errors: EINVAL (bad config, NULL pointer, unaligned workspace) and ENOMEM (workspace too small) leave
+ * *out = NULL. A HIP failure after the context exists returns EHIP with *out set: read
+ * pdadmm_last_error(*out), then pdadmm_destroy(*out).
  */
 pdadmm_status pdadmm_init(pdadmm_ctx** out, const pdadmm_config* cfg, void* workspace, size_t workspace_bytes,
                           const float* X_aug, const int32_t* labels, const uint8_t* train_mask,
@@ -163,8 +166,10 @@ pdadmm_status pdadmm_init(pdadmm_ctx** out, const pdadmm_config* cfg, void* work
  * Copy a variable in or out. `layer` is the paper's l. The buffer is dense (leading dimension =
  * width) and may be HOST or DEVICE memory, except TAU/THETA (HOST double) and PROBE (HOST int32[2]).
  * Both calls synchronise.
- * set_var of P in -Q mode (and of Q with quantize = 2) projects the values onto Delta. After any set_var the carried residual
- * W_l p_l + b_l - z_l is recomputed from scratch at the next iteration.
+ * set_var of P in -Q mode (and of Q with quantize = 2) projects the values onto Delta. After any
+ * set_var the carried residual W_l p_l + b_l - z_l is recomputed from scratch at the next iteration.
+ * A checkpoint is every P (l >= 2), W, B, Z, Q, U, TAU, THETA (and PROBE in -Q); written into a fresh
+ * context of the same configuration it continues the run (to rounding: the carried residual is rebuilt).
  */
 pdadmm_status pdadmm_set_var(pdadmm_ctx* ctx, int32_t kind, int32_t layer, const void* src);
 pdadmm_status pdadmm_get_var(pdadmm_ctx* ctx, int32_t kind, int32_t layer, void* dst);
