@@ -56,6 +56,8 @@ inline int flat_blocks(size_t n4) {
 struct LayerBufs {
   int n_in, n_out, ld_in, ld_out;
   float *W, *Wt, *b, *z, *R, *T, *G, *m, *Gpart;
+  float* Tpart;             // small problems: partial products of G p over chunks of n_in
+  int wt_split, wt_chunk;   // number of such chunks (1 = the product is not split) and their length
   float* p;                 // input of the layer, [N, ld_in]
   float *g, *d;             // l >= 2: gradient of phi in p, -Q trial direction
   uint8_t* pidx;            // l >= 2, -Q
@@ -120,7 +122,8 @@ struct pdadmm_ctx {
   // descriptor tables in device memory, each with the block maps of its launches
   Group<GemmProb> g_pgrad, g_ptrial, g_wgrad, g_wtrial, g_resid, g_resid_obj;
   std::vector<GemmProb> fwd;          // forward pass of the starting point: one by-value launch per layer
-  Group<ReduceProb> g_red;
+  Group<ReduceProb> g_red, g_tred;
+  bool small_wtrial = false;  // the G p launch has too few tiles to fill the chip: split its contraction
   Group<AxpySeg> g_pstep, g_qapply_r;
   SelectDesc *sel_p = nullptr, *sel_w = nullptr, *sel_q = nullptr;
   Group<WStepSeg> g_w;
@@ -272,6 +275,12 @@ size_t plan(pdadmm_ctx* c, void* base) {
       }
     }
   }
+  // The products T = p G^T of all layers form one launch. When that launch has fewer tiles than half the
+  // resident blocks (small models), the long contractions in it (n_in >> 128) are cut into chunks whose
+  // partial products are summed, in a fixed order, by the kernel that also takes the norm.
+  size_t wt_tiles = 0;
+  for (int i = 0; i < L; ++i) wt_tiles += (size_t)cdiv(N, BM) * cdiv(c->dims[i + 1], BN);
+  c->small_wtrial = wt_tiles * 2 <= (size_t)kGemmSlots;
   for (int i = 0; i < L; ++i) {
     LayerBufs& b = c->lay[i];
     b.n_in = c->dims[i];
@@ -291,6 +300,15 @@ size_t plan(pdadmm_ctx* c, void* base) {
     b.Wt = cv.take<float>((size_t)b.n_in * b.ld_out);
     b.G = cv.take<float>((size_t)b.n_out * b.ld_in);
     b.Gpart = cv.take<float>((size_t)b.splitk * b.n_out * b.ld_in);
+    b.wt_split = 1;
+    b.wt_chunk = b.n_in;
+    b.Tpart = nullptr;
+    if (c->small_wtrial) {
+      const int want = (int)std::min<size_t>(kGemmSlots / wt_tiles, 32);
+      b.wt_chunk = std::max(8 * BK, cdiv(cdiv(b.n_in, std::max(want, 1)), BK) * BK);
+      b.wt_split = cdiv(b.n_in, b.wt_chunk);
+      b.Tpart = cv.take<float>((size_t)b.wt_split * N * b.ld_out);
+    }
     b.b = cv.take<float>(b.ld_out);
     b.m = cv.take<float>(b.ld_out);
     b.z = cv.take<float>(out_sz);
@@ -330,6 +348,7 @@ size_t plan(pdadmm_ctx* c, void* base) {
   c->g_resid.dev = cv.take<GemmProb>(L);
   c->g_resid_obj.dev = cv.take<GemmProb>(L);
   c->g_red.dev = cv.take<ReduceProb>(L);
+  c->g_tred.dev = cv.take<ReduceProb>(L);
   c->g_pstep.dev = cv.take<AxpySeg>(2 * L);
   c->g_qapply_r.dev = cv.take<AxpySeg>(L);
   c->sel_p = cv.take<SelectDesc>(L);
@@ -386,7 +405,7 @@ pdadmm_status build_tables(pdadmm_ctx* c) {
   const float rho = c->cfg.rho, nu = c->cfg.nu;
   const bool Q = c->cfg.quantize != 0;
   std::vector<GemmProb> pgrad, ptrial, wgrad, wtrial, resid, resid_obj, fwd;
-  std::vector<ReduceProb> red;
+  std::vector<ReduceProb> red, tred;
   std::vector<AxpySeg> pstep, qapply_r;
   std::vector<SelectDesc> sel_p, sel_w, sel_q;
   std::vector<WStepSeg> wseg;
@@ -443,9 +462,23 @@ pdadmm_status build_tables(pdadmm_ctx* c) {
     // image of G under p: T = p G^T
     GemmProb Wt_ = make_nt(b.p, b.ld_in, b.G, b.ld_in, b.T, b.ld_out, N, b.n_out, b.n_in);
     Wt_.part = b.part_b; Wt_.layer = i;
+    int t_partials = Wt_.nblk;
+    if (c->small_wtrial) {
+      // partial products into Tpart[chunk][N][ld_out]; tred sums them into T and takes ||T||^2
+      Wt_.C = b.Tpart;
+      Wt_.splitk = b.wt_split;
+      Wt_.k_chunk = b.wt_chunk;
+      Wt_.nblk = Wt_.tiles_m * Wt_.tiles_n * b.wt_split;
+      ReduceProb tr{};
+      tr.part = b.Tpart; tr.G = b.T; tr.norm_part = b.part_b; tr.M = N; tr.N = b.n_out; tr.ld = b.ld_out;
+      tr.splitk = b.wt_split; tr.alpha = 1.0f;
+      tr.nblk = std::min(2048, std::max(1, cdiv(N * b.ld_out, 1024)));
+      tred.push_back(tr);
+      t_partials = tr.nblk;
+    }
     wtrial.push_back(Wt_);
     SelectDesc sw{};
-    sw.part_g = b.part_a; sw.ng = rp.nblk; sw.part_t = b.part_b; sw.nt = Wt_.nblk; sw.stride_t = 1; sw.layer = i;
+    sw.part_g = b.part_a; sw.ng = rp.nblk; sw.part_t = b.part_b; sw.nt = t_partials; sw.stride_t = 1; sw.layer = i;
     sel_w.push_back(sw);
     WStepSeg ws{};
     ws.W = b.W; ws.Wt = b.Wt; ws.G = b.G; ws.n_out = b.n_out; ws.n_in = b.n_in; ws.ld_in = b.ld_in;
@@ -503,7 +536,7 @@ pdadmm_status build_tables(pdadmm_ctx* c) {
     group.build(group.dev, v, (int)v.size());                               \
   } while (0)
   UP(c->g_pgrad, pgrad); UP(c->g_ptrial, ptrial); UP(c->g_wgrad, wgrad); UP(c->g_wtrial, wtrial);
-  UP(c->g_resid, resid); UP(c->g_resid_obj, resid_obj); UP(c->g_red, red);
+  UP(c->g_resid, resid); UP(c->g_resid_obj, resid_obj); UP(c->g_red, red); UP(c->g_tred, tred);
   UP(c->g_pstep, pstep); UP(c->g_qapply_r, qapply_r);
   UP(c->g_w, wseg); UP(c->g_rows_all, rows); UP(c->g_bias, bias); UP(c->g_quant, quant); UP(c->g_pair, pair);
 #undef UP
@@ -603,8 +636,15 @@ pdadmm_status phase_w(pdadmm_ctx* c) {
   LAUNCH_CHECK(c, "gemm wgrad");
   { TIMED(c, kClsSplitkReduce); launch_group(c, c->g_red, splitk_reduce_kernel); }
   LAUNCH_CHECK(c, "splitk reduce");
-  { TIMED(c, kClsGemmTrial); launch_gemm<true, EpiStoreNorm>(c, c->g_wtrial, 0); }
-  LAUNCH_CHECK(c, "gemm wtrial");
+  if (c->small_wtrial) {
+    { TIMED(c, kClsGemmTrial); launch_gemm<true, EpiStore>(c, c->g_wtrial, 0); }
+    LAUNCH_CHECK(c, "gemm wtrial (chunks)");
+    { TIMED(c, kClsSplitkReduce); launch_group(c, c->g_tred, splitk_reduce_kernel); }
+    LAUNCH_CHECK(c, "wtrial chunk sum");
+  } else {
+    { TIMED(c, kClsGemmTrial); launch_gemm<true, EpiStoreNorm>(c, c->g_wtrial, 0); }
+    LAUNCH_CHECK(c, "gemm wtrial");
+  }
   { TIMED(c, kClsSelect); hipLaunchKernelGGL(select_step_kernel, dim3(L), dim3(256), 0, c->stream, c->sel_w, c->scal, 1, g.rho, g.nu,
                      g.bt_eta, g.bt_max_trials, c->err); }
   LAUNCH_CHECK(c, "select theta");
