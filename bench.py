@@ -51,7 +51,7 @@ def elementwise_bytes_per_iteration(dims, n_nodes, quant):
     return out
 
 
-def build_problem(w, device):
+def build_problem(w, device, use_graph=0):
     """Inputs -> HBM -> context with a perturbed (generic) state. Uses only the HIP library."""
     import numpy as np
     import torch
@@ -76,7 +76,8 @@ def build_problem(w, device):
     aug_ms = e0.elapsed_time(e1)
     q = w.quant
     cfg = P.Config(n_nodes=w.n_nodes, dims=list(w.dims), rho=w.rho, nu=w.nu, quantize=(2 if w.quant_q else 1) if q else 0,
-                   q_lo=q[0] if q else -1.0, q_hi=q[1] if q else 1.0, q_levels=q[2] if q else 256)
+                   q_lo=q[0] if q else -1.0, q_hi=q[1] if q else 1.0, q_levels=q[2] if q else 256,
+                   use_graph=use_graph)
     ctx = P.pdadmm_init(cfg, Xa, torch.from_numpy(y).to(device), [torch.from_numpy(a).to(device) for a in Ws],
                         [torch.from_numpy(a).to(device) for a in bs])
     # perturb the forward-consistent start (otherwise most layers sit at a fixed point for many iterations)
@@ -141,6 +142,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--dominant-only", action="store_true",
                     help="record HIP events around the dominant kernel class only (default: every class)")
+    ap.add_argument("--graph", action="store_true",
+                    help="replay the iteration as a HIP graph (pdADMM-G only; per-class timing is then off)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy (reference point for FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
@@ -158,7 +161,7 @@ def main():
     P.load_library()
     device = torch.device("cuda:0")
     w = get_workload(args.workload)
-    ctx, info, host = build_problem(w, device)
+    ctx, info, host = build_problem(w, device, use_graph=1 if args.graph else 0)
 
     if args.copy_calibration:
         src = torch.ones(1 << 28, dtype=torch.float32, device=device)      # 1 GiB
@@ -170,6 +173,8 @@ def main():
     P.pdadmm_sync(ctx)
     dominant = "gemm_trial"
     mask = 1 << P.TIMING_CLASSES.index(dominant) if args.dominant_only else (1 << len(P.TIMING_CLASSES)) - 1
+    if args.graph:
+        mask = 0                       # events around single launches would break the replay up
     P.pdadmm_timing(ctx, mask)
     products_before = P.pdadmm_stats(ctx)["p_products"]
     torch.cuda.synchronize()
@@ -194,10 +199,11 @@ def main():
     trial_flops = (sum(float(n_products[i]) * per_layer[i] for i in range(w.n_layers)) / max(args.steps, 1)
                    + sum(per_layer))
     flops_per_launch = trial_flops / launches_per_iter if launches_per_iter else 0.0
-    avg_ms = ms / launches if launches else float("nan")
-    achieved = flops_per_launch / (avg_ms * 1e-3) / 1e12 if launches else float("nan")
+    avg_ms = ms / launches if launches else None
+    achieved = flops_per_launch / (avg_ms * 1e-3) / 1e12 if launches else None
     roofline = dict(bound="mfma", kernel="gemm_kernel<true, EpiStoreNorm> (fp32 MFMA 32x32x2; W g / G p products)",
-                    achieved=achieved, peak=MFMA_FP32_PEAK_TFLOPS, unit="TFLOP/s", frac=achieved / MFMA_FP32_PEAK_TFLOPS,
+                    achieved=achieved, peak=MFMA_FP32_PEAK_TFLOPS, unit="TFLOP/s",
+                    frac=achieved / MFMA_FP32_PEAK_TFLOPS if achieved else None,
                     traffic=MEASURED_TRAFFIC_BYTES.get(w.name), avg_launch_ms=avg_ms, launches=launches,
                     flop_per_launch=flops_per_launch)
     total_gemm_flops = flops["gemm_pgrad"] + flops["gemm_wgrad"] + trial_flops
@@ -212,7 +218,7 @@ def main():
                roofline=roofline,
                augment_ms=info["augment_ms"], objective_after=obj["L_rho"],
                p_trials=[int(x) for x in stats["p_trials"]], w_trials=[int(x) for x in stats["w_trials"]])
-    if not args.dominant_only:
+    if not args.dominant_only and not args.graph:
         cls = {k: v[0] / args.steps for k, v in timing.items() if v[1]}
         out["class_ms_per_step"] = cls
         gemm_ms = sum(cls.get(k, 0.0) for k in ("gemm_pgrad", "gemm_trial", "gemm_wgrad", "splitk_reduce"))

@@ -58,6 +58,10 @@ typedef struct {
   int32_t refresh_every;   /* recompute W_l p_l + b_l - z_l from scratch every k iterations; 0 = never */
   float leaky_slope;       /* activation f(z) = z (z > 0), leaky_slope * z otherwise; 0 = ReLU (Section 5.1);
                               in [0, 1): leaky ReLU (named in Section 4 as satisfying the assumption) */
+  int32_t use_graph;       /* 1: pdADMM-G iterations are captured once as a HIP graph and replayed on a stream
+                              of the library's own, ordered against `stream` by events (helps small,
+                              launch-bound models). Ignored for -Q, while pdadmm_timing is on and when
+                              refresh_every > 0 */
 } pdadmm_config;
 
 /* Terms of the augmented Lagrangian L_rho (Section 3.2). */

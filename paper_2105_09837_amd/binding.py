@@ -35,7 +35,7 @@ class _CConfig(C.Structure):
                 ("q_lo", C.c_float), ("q_hi", C.c_float), ("q_levels", C.c_int32),
                 ("fista_iters", C.c_int32), ("bt_eta", C.c_float), ("tau0", C.c_float),
                 ("theta0", C.c_float), ("bt_max_trials", C.c_int32), ("refresh_every", C.c_int32),
-                ("leaky_slope", C.c_float)]
+                ("leaky_slope", C.c_float), ("use_graph", C.c_int32)]
 
 
 class _CObjective(C.Structure):
@@ -115,13 +115,14 @@ class Config:
     bt_max_trials: int = 64
     refresh_every: int = 0
     leaky_slope: float = 0.0
+    use_graph: int = 0
 
     def to_c(self):
         dims = (C.c_int32 * len(self.dims))(*[int(d) for d in self.dims])
         cc = _CConfig(int(self.n_nodes), len(self.dims) - 1, C.cast(dims, C.POINTER(C.c_int32)),
                       float(self.rho), float(self.nu), int(self.quantize), float(self.q_lo), float(self.q_hi),
                       int(self.q_levels), int(self.fista_iters), float(self.bt_eta), float(self.tau0),
-                      float(self.theta0), int(self.bt_max_trials), int(self.refresh_every), float(self.leaky_slope))
+                      float(self.theta0), int(self.bt_max_trials), int(self.refresh_every), float(self.leaky_slope), int(self.use_graph))
         cc._keep = dims
         return cc
 

@@ -135,6 +135,11 @@ struct pdadmm_ctx {
   int panel_tn = 16;          // the same for the W-gradient products (all tiles of one node chunk)
   bool dirty = true;
   long iter = 0;
+  // optional replay of one pdADMM-G iteration as a HIP graph (launch-bound small models)
+  hipStream_t gstream = nullptr;       // capture/replay stream, ordered against `stream` by events
+  hipGraph_t graph = nullptr;
+  hipGraphExec_t graph_exec = nullptr;
+  hipEvent_t ev_in = nullptr, ev_out = nullptr;
   std::vector<long long> p_products;   // per layer: step-direction products (W g / W d) computed since init
   std::string msg;
   // optional per-launch timing with HIP events on the context's stream
@@ -230,6 +235,7 @@ bool config_ok(const pdadmm_config* c, std::string* why) {
   if (c->bt_max_trials < 1) return bad("bt_max_trials < 1");
   if (c->refresh_every < 0) return bad("refresh_every < 0");
   if (!(c->leaky_slope >= 0.f) || !(c->leaky_slope < 1.f)) return bad("leaky_slope must be in [0, 1)");
+  if (c->use_graph != 0 && c->use_graph != 1) return bad("use_graph must be 0 or 1");
   return true;
 }
 
@@ -955,6 +961,11 @@ pdadmm_status pdadmm_init(pdadmm_ctx** out, const pdadmm_config* cfg, void* work
   }
   c->dirty = true;
   HIP_TRY(c, hipStreamSynchronize(c->stream));
+  if (cfg->use_graph && !cfg->quantize) {
+    HIP_TRY(c, hipStreamCreateWithFlags(&c->gstream, hipStreamNonBlocking));
+    HIP_TRY(c, hipEventCreateWithFlags(&c->ev_in, hipEventDisableTiming));
+    HIP_TRY(c, hipEventCreateWithFlags(&c->ev_out, hipEventDisableTiming));
+  }
   return PDADMM_OK;
 }
 
@@ -1048,9 +1059,44 @@ pdadmm_status pdadmm_step_phase(pdadmm_ctx* c, int32_t phase) {
   }
 }
 
+// One pdADMM-G iteration is a fixed sequence of kernel launches with no host decision in between
+// (tau and theta are chosen on the device), so it can be captured once and replayed. The graph runs on
+// a stream of its own that is ordered after and before the caller's stream by events. Not used for -Q
+// (the host reads the search flags), while launches are being timed, or when a refresh is due.
+static pdadmm_status iterate_graph(pdadmm_ctx* c, int32_t n_iters) {
+  pdadmm_status s;
+  if (c->dirty && (s = refresh_residual(c)) != PDADMM_OK) return s;
+  HIP_TRY(c, hipEventRecord(c->ev_in, c->stream));
+  HIP_TRY(c, hipStreamWaitEvent(c->gstream, c->ev_in, 0));
+  if (!c->graph_exec) {
+    hipStream_t user = c->stream;
+    HIP_TRY(c, hipStreamBeginCapture(c->gstream, hipStreamCaptureModeThreadLocal));
+    c->stream = c->gstream;
+    s = phase_p(c);
+    if (s == PDADMM_OK) s = phase_w(c);
+    if (s == PDADMM_OK) s = phase_bzqu(c);
+    c->stream = user;
+    const hipError_t e = hipStreamEndCapture(c->gstream, &c->graph);
+    if (s != PDADMM_OK) return s;
+    if (e != hipSuccess) return fail(c, PDADMM_EHIP, std::string("hipStreamEndCapture: ") + hipGetErrorString(e));
+    HIP_TRY(c, hipGraphInstantiate(&c->graph_exec, c->graph, nullptr, nullptr, 0));
+    // capture recorded the launches without running them: the product counters were advanced once
+    for (int i = 1; i < c->L; ++i) --c->p_products[i];
+  }
+  for (int it = 0; it < n_iters; ++it) {
+    HIP_TRY(c, hipGraphLaunch(c->graph_exec, c->gstream));
+    for (int i = 1; i < c->L; ++i) ++c->p_products[i];
+    ++c->iter;
+  }
+  HIP_TRY(c, hipEventRecord(c->ev_out, c->gstream));
+  HIP_TRY(c, hipStreamWaitEvent(c->stream, c->ev_out, 0));
+  return PDADMM_OK;
+}
+
 pdadmm_status pdadmm_iterate(pdadmm_ctx* c, int32_t n_iters) {
   if (!c || n_iters < 0) return PDADMM_EINVAL;
   pdadmm_status s;
+  if (c->gstream && n_iters > 0 && c->timing_mask == 0 && c->cfg.refresh_every == 0) return iterate_graph(c, n_iters);
   for (int it = 0; it < n_iters; ++it) {
     const bool periodic = c->cfg.refresh_every > 0 && c->iter > 0 && c->iter % c->cfg.refresh_every == 0;
     if ((c->dirty || periodic) && (s = refresh_residual(c)) != PDADMM_OK) return s;
@@ -1254,6 +1300,12 @@ const char* pdadmm_last_error(const pdadmm_ctx* c) { return c ? c->msg.c_str() :
 void pdadmm_destroy(pdadmm_ctx* c) {
   if (!c) return;
   (void)hipStreamSynchronize(c->stream);
+  if (c->gstream) (void)hipStreamSynchronize(c->gstream);
+  if (c->graph_exec) (void)hipGraphExecDestroy(c->graph_exec);
+  if (c->graph) (void)hipGraphDestroy(c->graph);
+  if (c->ev_in) (void)hipEventDestroy(c->ev_in);
+  if (c->ev_out) (void)hipEventDestroy(c->ev_out);
+  if (c->gstream) (void)hipStreamDestroy(c->gstream);
   if (c->h_flags) (void)hipHostFree(c->h_flags);
   for (auto& t : c->timed) {
     (void)hipEventDestroy(t.a);

@@ -502,6 +502,46 @@ def test_training_learns_planted_labels_then_grows_greedily(env):
     assert obj[-1] < obj[0] and acc2 > chance + 0.2
 
 
+@pytest.mark.parametrize("case", ["C1-full", "C4-small"])
+def test_graph_replay_equals_eager_launches(env, case):
+    """use_graph = 1: the captured iteration is replayed several times, with eager work of the library
+    (objective, residual, get_var, set_var) and synchronisations between the replays; every replay must
+    give bit for bit what the eager launches give."""
+    torch, P, H = env
+    w = CASES[case]()
+    inp = oracle_inputs(w)
+    st = H.round_state_to_fp32(oracle_state(w, inp))
+    eager = H.gpu_context(w, inp, st)
+    graph = H.gpu_context(w, inp, st, use_graph=1)
+    L = w.n_layers
+
+    def same():
+        for l in range(1, L + 1):
+            for kind in (P.VAR.W, P.VAR.Z, P.VAR.B):
+                a, b = P.pdadmm_get_var(eager, kind, l), P.pdadmm_get_var(graph, kind, l)
+                assert np.array_equal(a.view(np.uint32), b.view(np.uint32)), (kind, l)
+        assert P.pdadmm_objective(eager) == P.pdadmm_objective(graph)
+        assert P.pdadmm_residual(eager)[0] == P.pdadmm_residual(graph)[0]
+
+    for k in range(4):
+        P.pdadmm_iterate(eager, 1)
+        P.pdadmm_iterate(graph, 1)
+        same()
+    P.pdadmm_iterate(eager, 3)
+    P.pdadmm_iterate(graph, 3)          # three replays back to back
+    same()
+    # a set_var between replays (forces the rebuild of the carried residual outside the graph)
+    z1 = P.pdadmm_get_var(eager, P.VAR.Z, 1) * np.float32(1.01)
+    P.pdadmm_set_var(eager, P.VAR.Z, 1, z1)
+    P.pdadmm_set_var(graph, P.VAR.Z, 1, z1)
+    P.pdadmm_iterate(eager, 2)
+    P.pdadmm_iterate(graph, 2)
+    same()
+    se, sg = P.pdadmm_stats(eager), P.pdadmm_stats(graph)
+    assert np.array_equal(se["tau"], sg["tau"]) and np.array_equal(se["theta"], sg["theta"])
+    assert np.array_equal(se["p_products"], sg["p_products"])
+
+
 def test_forward_consistent_start_moves_only_last_layer(env):
     torch, P, H = env
     w = small("C1", n=500, hidden=24, n_layers=4, feat_dim=8)
