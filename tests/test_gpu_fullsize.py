@@ -154,7 +154,7 @@ def _window_state(w, layer, win, X_aug, y):
     none = [None] * n
     st = O.State(W=list(none), b=list(none), z=list(none), p=list(none), q=[None] * (n - 1), u=[None] * (n - 1),
                  y=y, mask=None, rho=float(w.rho), nu=float(w.nu), grid=grid_of(w), tau=[1.0] * n, theta=[1.0] * n,
-                 p_trials=[0] * n, w_trials=[0] * n)
+                 p_trials=[0] * n, w_trials=[0] * n, p_wait=[0] * n, p_skip=[0] * n)
     d64 = lambda a: np.asarray(a, dtype=F64)
     st.W[i], st.b[i], st.z[i] = d64(win["W"]), d64(win["b"]), d64(win["z"])
     st.p[i] = d64(win["p"]) if has_prev else d64(X_aug)
@@ -186,12 +186,16 @@ def test_full_size_sampled_layer_one_iteration(env, say, name, layer):
     P.pdadmm_set_var(ctx, V.Z, layer, win["z"]); P.pdadmm_set_var(ctx, V.THETA, layer, 1.0)
     if layer >= 2:
         P.pdadmm_set_var(ctx, V.P, layer, win["p"]); P.pdadmm_set_var(ctx, V.TAU, layer, 1.0)
+        if g is not None:
+            P.pdadmm_set_var(ctx, V.PROBE, layer, (0, 0))
         P.pdadmm_set_var(ctx, V.Q, layer - 1, win["q_prev"]); P.pdadmm_set_var(ctx, V.U, layer - 1, win["u_prev"])
     if layer < L:
         P.pdadmm_set_var(ctx, V.Q, layer, win["q"]); P.pdadmm_set_var(ctx, V.U, layer, win["u"])
         P.pdadmm_set_var(ctx, V.W, layer + 1, win["W_next"]); P.pdadmm_set_var(ctx, V.B, layer + 1, win["b_next"])
         P.pdadmm_set_var(ctx, V.Z, layer + 1, win["z_next"]); P.pdadmm_set_var(ctx, V.P, layer + 1, win["p_next"])
         P.pdadmm_set_var(ctx, V.TAU, layer + 1, 1.0)
+        if g is not None:
+            P.pdadmm_set_var(ctx, V.PROBE, layer + 1, (0, 0))
     # ... and to the oracle
     X_aug = None
     if layer == 1:
