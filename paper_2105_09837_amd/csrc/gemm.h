@@ -37,68 +37,84 @@ struct GemmProb {
   QuantGrid grid;     // used by the forward epilogue in -Q mode (levels = 0: off)
 };
 
-// ---- epilogues: apply(P, row, col, acc, s0, s1) is called once per in-range output element
+// ---- epilogues. For one in-range output element (flat index i = row*ldc + col): load(P, i, col) fetches
+// the element's extra inputs, apply(P, C, i, col, acc, in, s0, s1) forms and stores the result. The
+// tile epilogue calls load for a batch of elements before any apply, so the loads of a batch are in
+// flight together (a store between two loads would order them: the compiler cannot rule out aliasing).
+struct NoIn {};
 struct EpiStore {     // C = alpha * acc
-  static constexpr int NS = 0;
-  __device__ static __forceinline__ void apply(const GemmProb& P, float* C, int row, int col, float acc,
-                                               double&, double&) {
-    ((float PD_GLOBAL*)C)[(size_t)row * P.ldc + col] = P.alpha * acc;
+  static constexpr int NS = 0, kBatch = 1;
+  typedef NoIn In;
+  __device__ static __forceinline__ In load(const GemmProb&, size_t, int) { return In{}; }
+  __device__ static __forceinline__ void apply(const GemmProb& P, float* C, size_t i, int, float acc,
+                                               const In&, double&, double&) {
+    ((float PD_GLOBAL*)C)[i] = P.alpha * acc;
   }
 };
 struct EpiStoreNorm { // C = acc, s0 += acc^2
-  static constexpr int NS = 1;
-  __device__ static __forceinline__ void apply(const GemmProb& P, float* C, int row, int col, float acc,
-                                               double& s0, double&) {
-    ((float PD_GLOBAL*)C)[(size_t)row * P.ldc + col] = acc;
+  static constexpr int NS = 1, kBatch = 1;
+  typedef NoIn In;
+  __device__ static __forceinline__ In load(const GemmProb&, size_t, int) { return In{}; }
+  __device__ static __forceinline__ void apply(const GemmProb&, float* C, size_t i, int, float acc,
+                                               const In&, double& s0, double&) {
+    ((float PD_GLOBAL*)C)[i] = acc;
     s0 += (double)acc * (double)acc;
   }
 };
 struct EpiPGrad {     // g = nu*acc + u + rho*(p - q) (gradient of phi in p_l); s0 += g^2
-  static constexpr int NS = 1;
-  __device__ static __forceinline__ void apply(const GemmProb& P, float* C, int row, int col, float acc,
-                                               double& s0, double&) {
-    const size_t i = (size_t)row * P.ldc + col;
-    const float g = P.alpha * acc + ((gcf)P.e0)[i] + P.beta * (((gcf)P.e1)[i] - ((gcf)P.e2)[i]);
+  static constexpr int NS = 1, kBatch = 4;   // elements whose inputs are fetched together (8 would cost the third block per compute unit)
+  struct In { float u, p, q; };
+  __device__ static __forceinline__ In load(const GemmProb& P, size_t i, int) {
+    return In{((gcf)P.e0)[i], ((gcf)P.e1)[i], ((gcf)P.e2)[i]};
+  }
+  __device__ static __forceinline__ void apply(const GemmProb& P, float* C, size_t i, int, float acc,
+                                               const In& in, double& s0, double&) {
+    const float g = P.alpha * acc + in.u + P.beta * (in.p - in.q);
     ((float PD_GLOBAL*)C)[i] = g;
     s0 += (double)g * (double)g;
   }
 };
 struct EpiResid {     // r = acc + b[col] - z; s0 += r^2; s1 += (r - carried)^2 when e2 != null
-  static constexpr int NS = 2;
-  __device__ static __forceinline__ void apply(const GemmProb& P, float* C, int row, int col, float acc,
-                                               double& s0, double& s1) {
-    const size_t i = (size_t)row * P.ldc + col;
-    const float r = acc + P.e0[col] - P.e1[i];
-    C[i] = r;
+  static constexpr int NS = 2, kBatch = 4;
+  struct In { float b, z, carried; };
+  __device__ static __forceinline__ In load(const GemmProb& P, size_t i, int col) {
+    return In{((gcf)P.e0)[col], ((gcf)P.e1)[i], P.e2 ? ((gcf)P.e2)[i] : 0.0f};
+  }
+  __device__ static __forceinline__ void apply(const GemmProb& P, float* C, size_t i, int, float acc,
+                                               const In& in, double& s0, double& s1) {
+    const float r = acc + in.b - in.z;
+    ((float PD_GLOBAL*)C)[i] = r;
     s0 += (double)r * (double)r;
     if (P.e2) {
-      const double d = (double)r - (double)P.e2[i];
+      const double d = (double)r - (double)in.carried;
       s1 += d * d;
     }
   }
 };
 struct EpiForward {   // z = acc + b[col]; q = f(z); p_next = f(z) (projected onto the grid in -Q; q too if beta != 0)
-  static constexpr int NS = 0;
-  __device__ static __forceinline__ void apply(const GemmProb& P, float* C, int row, int col, float acc,
-                                               double&, double&) {
-    const size_t i = (size_t)row * P.ldc + col;
-    const float z = acc + P.e0[col];
-    C[i] = z;
+  static constexpr int NS = 0, kBatch = 1;
+  struct In { float b; };
+  __device__ static __forceinline__ In load(const GemmProb& P, size_t, int col) { return In{((gcf)P.e0)[col]}; }
+  __device__ static __forceinline__ void apply(const GemmProb& P, float* C, size_t i, int, float acc,
+                                               const In& in, double&, double&) {
+    const float z = acc + in.b;
+    ((float PD_GLOBAL*)C)[i] = z;
     if (P.o1) {
       const float a = act_fn(z, P.slope);
       const float aq = P.grid.levels > 0 ? quant_value(quant_index(a, P.grid), P.grid) : a;
-      P.o1[i] = P.beta != 0.0f ? aq : a;    // beta != 0: q is kept on the grid as well
-      P.o2[i] = aq;
+      ((float PD_GLOBAL*)P.o1)[i] = P.beta != 0.0f ? aq : a;    // beta != 0: q is kept on the grid as well
+      ((float PD_GLOBAL*)P.o2)[i] = aq;
     }
   }
 };
-
 struct EpiBiasAct {   // C = acc + b[col], passed through f when beta != 0 (forward pass of the model, Problem 1)
-  static constexpr int NS = 0;
-  __device__ static __forceinline__ void apply(const GemmProb& P, float* C, int row, int col, float acc,
-                                               double&, double&) {
-    const float v = acc + P.e0[col];
-    ((float PD_GLOBAL*)C)[(size_t)row * P.ldc + col] = P.beta != 0.0f ? act_fn(v, P.slope) : v;
+  static constexpr int NS = 0, kBatch = 1;
+  struct In { float b; };
+  __device__ static __forceinline__ In load(const GemmProb& P, size_t, int col) { return In{((gcf)P.e0)[col]}; }
+  __device__ static __forceinline__ void apply(const GemmProb& P, float* C, size_t i, int, float acc,
+                                               const In& in, double&, double&) {
+    const float v = acc + in.b;
+    ((float PD_GLOBAL*)C)[i] = P.beta != 0.0f ? act_fn(v, P.slope) : v;
   }
 };
 
@@ -323,10 +339,20 @@ __device__ __forceinline__ void gemm_body(const GemmProb& P, const int local) {
     for (int j = 0; j < TN; ++j) {
       const int col = n0 + wn * (BN / Cfg::WN) + j * 32 + li;
       if (col < P.N) {
+        // the 16 elements of one MFMA block in batches: all extra inputs of a batch first, then results and stores
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int row = m0 + wm * (BM / Cfg::WM) + i * 32 + 8 * (v >> 2) + 4 * lh + (v & 3);
-          if (row < P.M) Epi::apply(P, Cout, row, col, acc[i][j][v], s0, s1);
+        for (int v0 = 0; v0 < 16; v0 += Epi::kBatch) {
+          typename Epi::In in[Epi::kBatch];
+#pragma unroll
+          for (int v = 0; v < Epi::kBatch; ++v) {
+            const int row = m0 + wm * (BM / Cfg::WM) + i * 32 + 8 * ((v0 + v) >> 2) + 4 * lh + ((v0 + v) & 3);
+            if (row < P.M) in[v] = Epi::load(P, (size_t)row * P.ldc + col, col);
+          }
+#pragma unroll
+          for (int v = 0; v < Epi::kBatch; ++v) {
+            const int row = m0 + wm * (BM / Cfg::WM) + i * 32 + 8 * ((v0 + v) >> 2) + 4 * lh + ((v0 + v) & 3);
+            if (row < P.M) Epi::apply(P, Cout, (size_t)row * P.ldc + col, col, acc[i][j][v0 + v], in[v], s0, s1);
+          }
         }
       }
     }
