@@ -155,6 +155,9 @@ CASES = {
     "C4-small": lambda: scaled_workload("C4", 600, hidden=36, n_layers=12, feat_dim=12),
     "C5-small": lambda: scaled_workload("C5", 1300, hidden=136, n_layers=4, feat_dim=20),
     "C5pq-small": lambda: dataclasses.replace(scaled_workload("C5", 900, hidden=72, n_layers=4, feat_dim=12), quant_q=True),
+    "paper-grid": lambda: dataclasses.replace(scaled_workload("C5", 800, hidden=60, n_layers=4, feat_dim=10),
+                                              quant=(-1.0, 20.0, 22)),      # Delta = {-1, 0, 1, ..., 20} (Section 5.1)
+    "ragged": lambda: dataclasses.replace(scaled_workload("C2", 1037, hidden=131, n_layers=3, feat_dim=7), n_classes=11),
     "leaky-small": lambda: dataclasses.replace(scaled_workload("C2", 1100, hidden=90, n_layers=4, feat_dim=14), slope=0.05),
     "odd-widths": lambda: dataclasses.replace(scaled_workload("C2", 333, hidden=50, n_layers=3, feat_dim=5),
                                               n_classes=5, hidden=37),
@@ -301,7 +304,7 @@ def test_trajectories(env, case, iters):
     assert s["r_drift"] < 1e-4
 
 
-@pytest.mark.parametrize("case", ["C5-small", "C5pq-small"])
+@pytest.mark.parametrize("case", ["C5-small", "C5pq-small", "paper-grid"])
 def test_quantized_trajectory_step_by_step_along_the_oracle_run(env, case):
     """pdADMM-G-Q over 20 iterations, one step at a time: the oracle runs its own trajectory (its state
     rounded to fp32 after every iteration); before each iteration that state is copied to the GPU, both
