@@ -44,7 +44,11 @@ struct GemmProb {
 struct NoIn {};
 struct EpiStore {     // C = alpha * acc
   static constexpr int NS = 0, kBatch = 1;
+  static constexpr bool kVec = true;
   typedef NoIn In;
+  typedef NoIn In4;
+  __device__ static __forceinline__ In4 load4(const GemmProb&, size_t) { return In4{}; }
+  __device__ static __forceinline__ f32x4 apply4(const GemmProb& P, f32x4 acc, const In4&) { return P.alpha * acc; }
   __device__ static __forceinline__ In load(const GemmProb&, size_t, int) { return In{}; }
   __device__ static __forceinline__ void apply(const GemmProb& P, float* C, size_t i, int, float acc,
                                                const In&, double&, double&) {
@@ -53,7 +57,11 @@ struct EpiStore {     // C = alpha * acc
 };
 struct EpiStoreNorm { // C = acc, s0 += acc^2
   static constexpr int NS = 1, kBatch = 1;
+  static constexpr bool kVec = true;
   typedef NoIn In;
+  typedef NoIn In4;
+  __device__ static __forceinline__ In4 load4(const GemmProb&, size_t) { return In4{}; }
+  __device__ static __forceinline__ f32x4 apply4(const GemmProb&, f32x4 acc, const In4&) { return acc; }
   __device__ static __forceinline__ In load(const GemmProb&, size_t, int) { return In{}; }
   __device__ static __forceinline__ void apply(const GemmProb&, float* C, size_t i, int, float acc,
                                                const In&, double& s0, double&) {
@@ -63,7 +71,16 @@ struct EpiStoreNorm { // C = acc, s0 += acc^2
 };
 struct EpiPGrad {     // g = nu*acc + u + rho*(p - q) (gradient of phi in p_l); s0 += g^2
   static constexpr int NS = 1, kBatch = 4;   // elements whose inputs are fetched together (8 would cost the third block per compute unit)
+  static constexpr bool kVec = true;
   struct In { float u, p, q; };
+  struct In4 { f32x4 u, p, q; };
+  __device__ static __forceinline__ In4 load4(const GemmProb& P, size_t i) {
+    return In4{*reinterpret_cast<gcf4>((gcf)P.e0 + i), *reinterpret_cast<gcf4>((gcf)P.e1 + i),
+               *reinterpret_cast<gcf4>((gcf)P.e2 + i)};
+  }
+  __device__ static __forceinline__ f32x4 apply4(const GemmProb& P, f32x4 acc, const In4& in) {
+    return P.alpha * acc + in.u + P.beta * (in.p - in.q);
+  }
   __device__ static __forceinline__ In load(const GemmProb& P, size_t i, int) {
     return In{((gcf)P.e0)[i], ((gcf)P.e1)[i], ((gcf)P.e2)[i]};
   }
@@ -76,6 +93,7 @@ struct EpiPGrad {     // g = nu*acc + u + rho*(p - q) (gradient of phi in p_l); 
 };
 struct EpiResid {     // r = acc + b[col] - z; s0 += r^2; s1 += (r - carried)^2 when e2 != null
   static constexpr int NS = 2, kBatch = 4;
+  static constexpr bool kVec = false;
   struct In { float b, z, carried; };
   __device__ static __forceinline__ In load(const GemmProb& P, size_t i, int col) {
     return In{((gcf)P.e0)[col], ((gcf)P.e1)[i], P.e2 ? ((gcf)P.e2)[i] : 0.0f};
@@ -93,6 +111,7 @@ struct EpiResid {     // r = acc + b[col] - z; s0 += r^2; s1 += (r - carried)^2 
 };
 struct EpiForward {   // z = acc + b[col]; q = f(z); p_next = f(z) (projected onto the grid in -Q; q too if beta != 0)
   static constexpr int NS = 0, kBatch = 1;
+  static constexpr bool kVec = false;
   struct In { float b; };
   __device__ static __forceinline__ In load(const GemmProb& P, size_t, int col) { return In{((gcf)P.e0)[col]}; }
   __device__ static __forceinline__ void apply(const GemmProb& P, float* C, size_t i, int, float acc,
@@ -109,6 +128,7 @@ struct EpiForward {   // z = acc + b[col]; q = f(z); p_next = f(z) (projected on
 };
 struct EpiBiasAct {   // C = acc + b[col], passed through f when beta != 0 (forward pass of the model, Problem 1)
   static constexpr int NS = 0, kBatch = 1;
+  static constexpr bool kVec = false;
   struct In { float b; };
   __device__ static __forceinline__ In load(const GemmProb& P, size_t, int col) { return In{((gcf)P.e0)[col]}; }
   __device__ static __forceinline__ void apply(const GemmProb& P, float* C, size_t i, int, float acc,
@@ -219,17 +239,22 @@ __device__ __forceinline__ void store_operand(float (*lds)[LD], const f32x4 (&re
   }
 }
 
+constexpr int kVecBatch = 4;   // 16-byte column groups per lane whose inputs are fetched together
+
 template <bool B> struct BoolTag { static constexpr bool value = B; };
 
-template <class Cfg, bool KCONTIG, class Epi>
+// VECC: the output and the epilogue's inputs are [*, ld] arrays with ld % 4 == 0 and 16-byte aligned
+// bases (true for the library's own buffers), which allows the row-contiguous epilogue below.
+template <class Cfg, bool KCONTIG, class Epi, bool VECC>
 __device__ __forceinline__ void gemm_body(const GemmProb& P, const int local) {
   constexpr int BM = Cfg::BM, BN = Cfg::BN, BK = Cfg::BK, TM = Cfg::TM, TN = Cfg::TN;
   constexpr int LDA = Cfg::LDA, LDB = Cfg::LDB;
   constexpr int NVA = BM * BK / 4 / 256, NVB = BN * BK / 4 / 256;
   static_assert(NVA >= 1 && NVB >= 1, "tile too small for 256 loader threads");
-  __shared__ __attribute__((aligned(16))) float As[2][BK][LDA];
-  __shared__ __attribute__((aligned(16))) float Bs[2][BK][LDB];
+  __shared__ __attribute__((aligned(16))) float smem[2 * BK * LDA + 2 * BK * LDB];
   __shared__ double red[4];
+  float (*As)[BK][LDA] = reinterpret_cast<float (*)[BK][LDA]>(smem);
+  float (*Bs)[BK][LDB] = reinterpret_cast<float (*)[BK][LDB]>(smem + 2 * BK * LDA);
 
   const int tiles = P.tiles_m * P.tiles_n;
   const int split = local / tiles;
@@ -333,6 +358,59 @@ __device__ __forceinline__ void gemm_body(const GemmProb& P, const int local) {
   // row 8*(v/4) + 4*(l/32) + v%4, column l%32 of the 32x32 block.
   float* Cout = P.C + (size_t)split * (size_t)P.M * (size_t)P.ldc;
   double s0 = 0.0, s1 = 0.0;
+  if constexpr (Epi::kVec && VECC) {
+    // Row-contiguous epilogue: every wave passes its 64x64 sub-tile through LDS (32 rows at a time, the
+    // operand buffers are free now) and then owns whole 16-byte column groups, so all global accesses
+    // of the epilogue are coalesced 16-byte loads and stores, a quarter as many as element by element.
+    static_assert(TN * 32 == 64 && 4 * 32 * 64 <= 2 * BK * LDA + 2 * BK * LDB, "staging area");
+    __syncthreads();                                   // all waves are done with the operand buffers
+    float* stage = smem + wave * (32 * 64);
+    const int rr = lane >> 4, c4 = (lane & 15) * 4;    // row (mod 4) and first column of this lane's groups
+    const int col = n0 + wn * (BN / Cfg::WN) + c4;
+    const int nvalid = P.N - col;                      // columns of the group inside the matrix (>= 4: all)
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) stage[(8 * (v >> 2) + 4 * lh + (v & 3)) * 64 + j * 32 + li] = acc[i][j][v];
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+      for (int it = 0; it < 8; it += kVecBatch) {
+        typename Epi::In4 in[kVecBatch];
+        f32x4 val[kVecBatch];
+        size_t idx[kVecBatch];
+        bool on[kVecBatch];
+#pragma unroll
+        for (int b = 0; b < kVecBatch; ++b) {
+          const int rl = (it + b) * 4 + rr;
+          const int row = m0 + wm * (BM / Cfg::WM) + i * 32 + rl;
+          on[b] = row < P.M && nvalid > 0;
+          idx[b] = (size_t)row * P.ldc + col;
+          val[b] = *reinterpret_cast<const f32x4*>(&stage[rl * 64 + c4]);
+          if (on[b]) in[b] = Epi::load4(P, idx[b]);
+        }
+#pragma unroll
+        for (int b = 0; b < kVecBatch; ++b) {
+          if (on[b]) {
+            f32x4 r = Epi::apply4(P, val[b], in[b]);
+            if (nvalid < 4) {                          // keep the pad columns of the row at zero
+              if (nvalid < 2) r.y = 0.f;
+              if (nvalid < 3) r.z = 0.f;
+              r.w = 0.f;
+            }
+            *reinterpret_cast<f32x4 PD_GLOBAL*>((float PD_GLOBAL*)Cout + idx[b]) = r;
+            if (Epi::NS >= 1)
+              s0 += (double)r.x * (double)r.x + (double)r.y * (double)r.y + (double)r.z * (double)r.z +
+                    (double)r.w * (double)r.w;
+          }
+        }
+      }
+      __builtin_amdgcn_wave_barrier();
+    }
+  } else {
 #pragma unroll
   for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -356,6 +434,7 @@ __device__ __forceinline__ void gemm_body(const GemmProb& P, const int local) {
         }
       }
     }
+  }
   if (Epi::NS >= 1) {
     const double t0 = block_sum_256(s0, red);
     if (tid == 0) P.part[(size_t)local * Epi::NS] = t0;
@@ -367,7 +446,7 @@ __device__ __forceinline__ void gemm_body(const GemmProb& P, const int local) {
 }
 
 // Grouped launch: block -> (problem, tile) through the table; blocks of one die are contiguous.
-template <class Cfg, bool KCONTIG, class Epi>
+template <class Cfg, bool KCONTIG, class Epi, bool VECC = false>
 __global__ __launch_bounds__(256) void gemm_kernel(const GemmProb* __restrict__ probs, const BlockMap map,
                                                    const LayerScal* __restrict__ scal, int predicated,
                                                    int panel) {
@@ -377,7 +456,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmProb* __restrict__ 
   const int pi = find_group(map, lb, &local);
   const GemmProb P = probs[pi];
   if (predicated && !scal[P.layer].active) return;
-  gemm_body<Cfg, KCONTIG, Epi>(P, local);
+  gemm_body<Cfg, KCONTIG, Epi, VECC>(P, local);
 }
 
 // Single problem with the descriptor passed by value (no table in device memory needed).
@@ -385,7 +464,7 @@ template <class Cfg, bool KCONTIG, class Epi>
 __global__ __launch_bounds__(256) void gemm_one_kernel(const GemmProb P, int panel) {
   const int lb = xcd_remap(blockIdx.x, panel);
   if (lb >= P.nblk) return;
-  gemm_body<Cfg, KCONTIG, Epi>(P, lb);
+  gemm_body<Cfg, KCONTIG, Epi, false>(P, lb);
 }
 
 // Sum the split-K partial products in a fixed order: G = alpha * sum_s part[s]; also write the

@@ -567,12 +567,14 @@ void launch_group(pdadmm_ctx* c, const Group<T>& g, K kernel, Args... args) {
   }
 }
 
-template <bool KC, class Epi>
+// VECC = true: every problem of the group writes (and reads its epilogue inputs from) workspace arrays,
+// which are 16-byte aligned with leading dimensions that are multiples of 4.
+template <bool KC, class Epi, bool VECC = false>
 void launch_gemm(pdadmm_ctx* c, const Group<GemmProb>& g, int predicated) {
   const int panel = KC ? c->panel : c->panel_tn;
   for (size_t k = 0; k < g.maps.size(); ++k) {
     if (g.maps[k].total <= 0) continue;
-    hipLaunchKernelGGL((gemm_kernel<Tile, KC, Epi>), dim3(xcd_padded(g.maps[k].total, panel)), dim3(256), 0,
+    hipLaunchKernelGGL((gemm_kernel<Tile, KC, Epi, VECC>), dim3(xcd_padded(g.maps[k].total, panel)), dim3(256), 0,
                        c->stream, (const GemmProb*)(g.dev + g.start[k]), g.maps[k], (const LayerScal*)c->scal,
                        predicated, panel);
   }
@@ -592,10 +594,10 @@ pdadmm_status phase_p(pdadmm_ctx* c) {
   const int L = c->L;
   if (L < 2) return PDADMM_OK;
   const pdadmm_config& g = c->cfg;
-  { TIMED(c, kClsGemmPGrad); launch_gemm<true, EpiPGrad>(c, c->g_pgrad, 0); }
+  { TIMED(c, kClsGemmPGrad); launch_gemm<true, EpiPGrad, true>(c, c->g_pgrad, 0); }
   LAUNCH_CHECK(c, "gemm pgrad");
   if (!g.quantize) {
-    { TIMED(c, kClsGemmTrial); launch_gemm<true, EpiStoreNorm>(c, c->g_ptrial, 0); }
+    { TIMED(c, kClsGemmTrial); launch_gemm<true, EpiStoreNorm, true>(c, c->g_ptrial, 0); }
     LAUNCH_CHECK(c, "gemm ptrial");
     for (int i = 1; i < L; ++i) ++c->p_products[i];
     { TIMED(c, kClsSelect); hipLaunchKernelGGL(select_step_kernel, dim3(L - 1), dim3(256), 0, c->stream, c->sel_p, c->scal, 0, g.rho, g.nu,
@@ -622,7 +624,7 @@ pdadmm_status phase_p(pdadmm_ctx* c) {
     if (!any) break;
     { TIMED(c, kClsQuantTrial); launch_group(c, c->g_quant, quant_trial_kernel, (const LayerScal*)c->scal, c->grid); }
     LAUNCH_CHECK(c, "quant trial");
-    { TIMED(c, kClsGemmTrial); launch_gemm<true, EpiStoreNorm>(c, c->g_ptrial, 1); }
+    { TIMED(c, kClsGemmTrial); launch_gemm<true, EpiStoreNorm, true>(c, c->g_ptrial, 1); }
     LAUNCH_CHECK(c, "gemm qtrial");
     { TIMED(c, kClsSelect); hipLaunchKernelGGL(select_quant_kernel, dim3(L - 1), dim3(256), 0, c->stream, c->sel_q, c->scal, 1, g.rho, g.nu,
                        g.bt_eta, g.bt_max_trials, c->err, c->flags); }
@@ -638,17 +640,17 @@ pdadmm_status phase_p(pdadmm_ctx* c) {
 pdadmm_status phase_w(pdadmm_ctx* c) {
   const int L = c->L;
   const pdadmm_config& g = c->cfg;
-  { TIMED(c, kClsGemmWGrad); launch_gemm<false, EpiStore>(c, c->g_wgrad, 0); }
+  { TIMED(c, kClsGemmWGrad); launch_gemm<false, EpiStore, true>(c, c->g_wgrad, 0); }
   LAUNCH_CHECK(c, "gemm wgrad");
   { TIMED(c, kClsSplitkReduce); launch_group(c, c->g_red, splitk_reduce_kernel); }
   LAUNCH_CHECK(c, "splitk reduce");
   if (c->small_wtrial) {
-    { TIMED(c, kClsGemmTrial); launch_gemm<true, EpiStore>(c, c->g_wtrial, 0); }
+    { TIMED(c, kClsGemmTrial); launch_gemm<true, EpiStore, true>(c, c->g_wtrial, 0); }
     LAUNCH_CHECK(c, "gemm wtrial (chunks)");
     { TIMED(c, kClsSplitkReduce); launch_group(c, c->g_tred, splitk_reduce_kernel); }
     LAUNCH_CHECK(c, "wtrial chunk sum");
   } else {
-    { TIMED(c, kClsGemmTrial); launch_gemm<true, EpiStoreNorm>(c, c->g_wtrial, 0); }
+    { TIMED(c, kClsGemmTrial); launch_gemm<true, EpiStoreNorm, true>(c, c->g_wtrial, 0); }
     LAUNCH_CHECK(c, "gemm wtrial");
   }
   { TIMED(c, kClsSelect); hipLaunchKernelGGL(select_step_kernel, dim3(L), dim3(256), 0, c->stream, c->sel_w, c->scal, 1, g.rho, g.nu,
