@@ -201,7 +201,7 @@ def main():
     flops_per_launch = trial_flops / launches_per_iter if launches_per_iter else 0.0
     avg_ms = ms / launches if launches else None
     achieved = flops_per_launch / (avg_ms * 1e-3) / 1e12 if launches else None
-    roofline = dict(bound="mfma", kernel="gemm_kernel<true, EpiStoreNorm> (fp32 MFMA 32x32x2; W g / G p products)",
+    roofline = dict(bound="mfma", kernel="gemm_kernel<NT, EpiTrialP|EpiTrialW|EpiStoreNorm> (fp32 MFMA 32x32x2; W g / W d and G p products)",
                     achieved=achieved, peak=MFMA_FP32_PEAK_TFLOPS, unit="TFLOP/s",
                     frac=achieved / MFMA_FP32_PEAK_TFLOPS if achieved else None,
                     traffic=MEASURED_TRAFFIC_BYTES.get(w.name), avg_launch_ms=avg_ms, launches=launches,

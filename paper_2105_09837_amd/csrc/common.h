@@ -92,6 +92,8 @@ struct LayerScal {
   double tau, theta;       // current backtracking parameters
   double norm_g, norm_t;   // last reduced squared norms (diagnostics)
   float inv_tau, inv_theta;  // 1/tau, 1/theta as applied by the step kernels (0 = skip the step)
+  float fix_tau, fix_theta;  // new minus previous 1/tau, 1/theta: what a speculative update with the previous
+                             // value still has to apply (0 when the step size did not change)
   float trial_t;           // -Q: tau of the trial in flight
   int p_trials, w_trials;
   int active;              // -Q: 1 while the p-update of this layer is still searching

@@ -10,7 +10,7 @@ namespace pdadmm {
 // ------------------------------------------------------------------------------------------
 // Flat y -= s * x over float4 groups; s comes from the layer's scalars.
 // ------------------------------------------------------------------------------------------
-enum : int { kScaleInvTau = 0, kScaleInvTheta = 1, kScaleMinusOneIfStep = 2 };
+enum : int { kScaleInvTau = 0, kScaleInvTheta = 1, kScaleMinusOneIfStep = 2, kScaleFixTau = 3, kScaleFixTheta = 4 };
 
 struct AxpySeg {
   float* y;
@@ -38,6 +38,25 @@ __global__ __launch_bounds__(256) void axpy_kernel(const AxpySeg* __restrict__ s
   const f32x4 a = stream_load(y);
   const f32x4 b = stream_load(reinterpret_cast<const f32x4*>(S.x) + i);
   stream_store(y, a - s * b);
+}
+
+// The same update as a small grid-stride kernel: the correction pass after a speculative update
+// (y already holds y - s_prev x; what is left is s = s_new - s_prev). Almost always s = 0 and the
+// blocks leave at once, which is why this pass does not get one block per 4 KiB.
+__global__ __launch_bounds__(256) void axpy_fix_kernel(const AxpySeg* __restrict__ segs, const BlockMap map,
+                                                       const LayerScal* __restrict__ scal) {
+  int local;
+  const int si = find_group(map, blockIdx.x, &local);
+  const AxpySeg S = segs[si];
+  const float s = scal[S.layer].fix_tau;
+  if (s == 0.0f) return;
+  const size_t stride = (size_t)S.nblk * 256;
+  for (size_t i = (size_t)local * 256 + threadIdx.x; i < S.n4; i += stride) {
+    f32x4* y = reinterpret_cast<f32x4*>(S.y) + i;
+    const f32x4 a = *y;
+    const f32x4 b = reinterpret_cast<const f32x4*>(S.x)[i];
+    *y = a - s * b;
+  }
 }
 
 // ------------------------------------------------------------------------------------------
@@ -74,6 +93,7 @@ __global__ __launch_bounds__(256) void select_step_kernel(const SelectDesc* __re
   LayerScal& sc = scal[D.layer];
   sc.norm_g = sg;
   sc.norm_t = st;
+  const float prev = mode == 0 ? sc.inv_tau : sc.inv_theta;
   float inv = 0.0f;
   int trials = 0;
   if (!(sg == sg) || !(st == st) || sg > 1.7e308 || st > 1.7e308) {
@@ -92,8 +112,8 @@ __global__ __launch_bounds__(256) void select_step_kernel(const SelectDesc* __re
       inv = (float)(1.0 / t);
     }
   }
-  if (mode == 0) { sc.inv_tau = inv; sc.p_trials = trials; }
-  else { sc.inv_theta = inv; sc.w_trials = trials; }
+  if (mode == 0) { sc.inv_tau = inv; sc.fix_tau = inv - prev; sc.p_trials = trials; }
+  else { sc.inv_theta = inv; sc.fix_theta = inv - prev; sc.w_trials = trials; }
 }
 
 // ------------------------------------------------------------------------------------------
@@ -157,6 +177,8 @@ struct RowSeg {
   double* colpart;      // [row_blocks][ld]
   int rows, ncols, ld;
   int cw;               // float4 column groups per block row (power of two, <= 256)
+  int rpb;              // rows per block of the column-sum pass
+  int which;            // kScaleInvTheta: full update; kScaleFixTheta: correction after a speculative update
   int col_blocks, row_blocks;
   int blk0, nblk;       // blocks of the column-sum pass
   int layer;
@@ -173,16 +195,18 @@ __global__ __launch_bounds__(256) void resid_colsum_kernel(const RowSeg* __restr
   int local;
   const int si = find_group(map, blockIdx.x, &local);
   const RowSeg S = segs[si];
-  const float inv = scal[S.layer].inv_theta;
+  const float inv = S.which == kScaleFixTheta ? scal[S.layer].fix_theta : scal[S.layer].inv_theta;
+  // correction pass: nothing to do (and the column sums taken by the product kernel stand) if theta did not change
+  if (S.which == kScaleFixTheta && inv == 0.0f) return;
   const int cb = local % S.col_blocks, rb = local / S.col_blocks;
   const int cw = S.cw, rstep = 256 / cw;
   const int cq = threadIdx.x & (cw - 1), ty = threadIdx.x / cw;
   const int col = (cb * cw + cq) * 4;
   double a0 = 0, a1 = 0, a2 = 0, a3 = 0;
   if (col < S.ld) {
-    const int rend = min(S.rows, (rb + 1) * kRowsPerBlock);
+    const int rend = min(S.rows, (rb + 1) * S.rpb);
     // four rows in flight per thread
-    for (int r = rb * kRowsPerBlock + ty; r < rend; r += 4 * rstep) {
+    for (int r = rb * S.rpb + ty; r < rend; r += 4 * rstep) {
       f32x4 v[4], t[4];
       bool on[4];
 #pragma unroll

@@ -32,6 +32,7 @@ struct GemmProb {
   float* o1;          // extra epilogue outputs
   float* o2;
   double* part;       // per-block partial sums, NS doubles per block
+  double* colpart;    // per row-tile column sums of the updated residual, [tiles_m][ldc] (EpiTrialW)
   float alpha, beta;
   float slope;        // negative-side slope of the activation (epilogues that apply f)
   QuantGrid grid;     // used by the forward epilogue in -Q mode (levels = 0: off)
@@ -47,8 +48,12 @@ struct EpiStore {     // C = alpha * acc
   static constexpr bool kVec = true;
   typedef NoIn In;
   typedef NoIn In4;
+  static constexpr bool kExtra = false, kColsum = false;
+  static constexpr int kScale = 0;
   __device__ static __forceinline__ In4 load4(const GemmProb&, size_t) { return In4{}; }
-  __device__ static __forceinline__ f32x4 apply4(const GemmProb& P, f32x4 acc, const In4&) { return P.alpha * acc; }
+  __device__ static __forceinline__ f32x4 apply4(const GemmProb& P, f32x4 acc, const In4&, float, f32x4&) {
+    return P.alpha * acc;
+  }
   __device__ static __forceinline__ In load(const GemmProb&, size_t, int) { return In{}; }
   __device__ static __forceinline__ void apply(const GemmProb& P, float* C, size_t i, int, float acc,
                                                const In&, double&, double&) {
@@ -60,8 +65,10 @@ struct EpiStoreNorm { // C = acc, s0 += acc^2
   static constexpr bool kVec = true;
   typedef NoIn In;
   typedef NoIn In4;
+  static constexpr bool kExtra = false, kColsum = false;
+  static constexpr int kScale = 0;
   __device__ static __forceinline__ In4 load4(const GemmProb&, size_t) { return In4{}; }
-  __device__ static __forceinline__ f32x4 apply4(const GemmProb&, f32x4 acc, const In4&) { return acc; }
+  __device__ static __forceinline__ f32x4 apply4(const GemmProb&, f32x4 acc, const In4&, float, f32x4&) { return acc; }
   __device__ static __forceinline__ In load(const GemmProb&, size_t, int) { return In{}; }
   __device__ static __forceinline__ void apply(const GemmProb&, float* C, size_t i, int, float acc,
                                                const In&, double& s0, double&) {
@@ -78,7 +85,9 @@ struct EpiPGrad {     // g = nu*acc + u + rho*(p - q) (gradient of phi in p_l); 
     return In4{*reinterpret_cast<gcf4>((gcf)P.e0 + i), *reinterpret_cast<gcf4>((gcf)P.e1 + i),
                *reinterpret_cast<gcf4>((gcf)P.e2 + i)};
   }
-  __device__ static __forceinline__ f32x4 apply4(const GemmProb& P, f32x4 acc, const In4& in) {
+  static constexpr bool kExtra = false, kColsum = false;
+  static constexpr int kScale = 0;
+  __device__ static __forceinline__ f32x4 apply4(const GemmProb& P, f32x4 acc, const In4& in, float, f32x4&) {
     return P.alpha * acc + in.u + P.beta * (in.p - in.q);
   }
   __device__ static __forceinline__ In load(const GemmProb& P, size_t i, int) {
@@ -91,9 +100,36 @@ struct EpiPGrad {     // g = nu*acc + u + rho*(p - q) (gradient of phi in p_l); 
     s0 += (double)g * (double)g;
   }
 };
+// Step-direction products with the residual update folded in (pdADMM-G). T = acc is stored and its norm
+// taken as in EpiStoreNorm; in the same pass the carried residual r = W p + b - z (o1, in place) takes the
+// update r -= s_prev * T with the step size of the previous iteration, which is almost always the one the
+// selection that follows confirms (tau and theta move on a grid of powers of eta). What the selection
+// changes, a small correction pass applies afterwards (fix_tau / fix_theta). EpiTrialW also leaves the
+// column sums of the updated residual (the b-update needs its node-mean) per row tile in colpart.
+template <int SCALE, bool COLSUM>
+struct EpiTrialUpd {
+  static constexpr int NS = 1, kBatch = 1;
+  static constexpr bool kVec = true, kExtra = true, kColsum = COLSUM;
+  static constexpr int kScale = SCALE;      // 1: previous 1/tau, 2: previous 1/theta
+  typedef NoIn In;
+  struct In4 { f32x4 r; };
+  __device__ static __forceinline__ In load(const GemmProb&, size_t, int) { return In{}; }
+  __device__ static __forceinline__ void apply(const GemmProb&, float*, size_t, int, float, const In&, double&, double&) {}
+  __device__ static __forceinline__ In4 load4(const GemmProb& P, size_t i) {
+    return In4{*reinterpret_cast<gcf4>((gcf)P.o1 + i)};
+  }
+  __device__ static __forceinline__ f32x4 apply4(const GemmProb&, f32x4 acc, const In4& in, float s_prev, f32x4& extra) {
+    extra = in.r - s_prev * acc;
+    return acc;
+  }
+};
+typedef EpiTrialUpd<1, false> EpiTrialP;   // T = g W^T; r -= T / tau_prev
+typedef EpiTrialUpd<2, true> EpiTrialW;    // T = p G^T; r -= T / theta_prev; column sums of r
+
 struct EpiResid {     // r = acc + b[col] - z; s0 += r^2; s1 += (r - carried)^2 when e2 != null
   static constexpr int NS = 2, kBatch = 4;
   static constexpr bool kVec = false;
+  static constexpr int kScale = 0;
   struct In { float b, z, carried; };
   __device__ static __forceinline__ In load(const GemmProb& P, size_t i, int col) {
     return In{((gcf)P.e0)[col], ((gcf)P.e1)[i], P.e2 ? ((gcf)P.e2)[i] : 0.0f};
@@ -112,6 +148,7 @@ struct EpiResid {     // r = acc + b[col] - z; s0 += r^2; s1 += (r - carried)^2 
 struct EpiForward {   // z = acc + b[col]; q = f(z); p_next = f(z) (projected onto the grid in -Q; q too if beta != 0)
   static constexpr int NS = 0, kBatch = 1;
   static constexpr bool kVec = false;
+  static constexpr int kScale = 0;
   struct In { float b; };
   __device__ static __forceinline__ In load(const GemmProb& P, size_t, int col) { return In{((gcf)P.e0)[col]}; }
   __device__ static __forceinline__ void apply(const GemmProb& P, float* C, size_t i, int, float acc,
@@ -129,6 +166,7 @@ struct EpiForward {   // z = acc + b[col]; q = f(z); p_next = f(z) (projected on
 struct EpiBiasAct {   // C = acc + b[col], passed through f when beta != 0 (forward pass of the model, Problem 1)
   static constexpr int NS = 0, kBatch = 1;
   static constexpr bool kVec = false;
+  static constexpr int kScale = 0;
   struct In { float b; };
   __device__ static __forceinline__ In load(const GemmProb& P, size_t, int col) { return In{((gcf)P.e0)[col]}; }
   __device__ static __forceinline__ void apply(const GemmProb& P, float* C, size_t i, int, float acc,
@@ -246,7 +284,7 @@ template <bool B> struct BoolTag { static constexpr bool value = B; };
 // VECC: the output and the epilogue's inputs are [*, ld] arrays with ld % 4 == 0 and 16-byte aligned
 // bases (true for the library's own buffers), which allows the row-contiguous epilogue below.
 template <class Cfg, bool KCONTIG, class Epi, bool VECC>
-__device__ __forceinline__ void gemm_body(const GemmProb& P, const int local) {
+__device__ __forceinline__ void gemm_body(const GemmProb& P, const int local, const float escale) {
   constexpr int BM = Cfg::BM, BN = Cfg::BN, BK = Cfg::BK, TM = Cfg::TM, TN = Cfg::TN;
   constexpr int LDA = Cfg::LDA, LDB = Cfg::LDB;
   constexpr int NVA = BM * BK / 4 / 256, NVB = BN * BK / 4 / 256;
@@ -368,6 +406,7 @@ __device__ __forceinline__ void gemm_body(const GemmProb& P, const int local) {
     const int rr = lane >> 4, c4 = (lane & 15) * 4;    // row (mod 4) and first column of this lane's groups
     const int col = n0 + wn * (BN / Cfg::WN) + c4;
     const int nvalid = P.N - col;                      // columns of the group inside the matrix (>= 4: all)
+    double cs0 = 0.0, cs1 = 0.0, cs2 = 0.0, cs3 = 0.0; // column sums of the second output (kColsum)
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
 #pragma unroll
@@ -395,13 +434,19 @@ __device__ __forceinline__ void gemm_body(const GemmProb& P, const int local) {
 #pragma unroll
         for (int b = 0; b < kVecBatch; ++b) {
           if (on[b]) {
-            f32x4 r = Epi::apply4(P, val[b], in[b]);
+            f32x4 extra = {0.f, 0.f, 0.f, 0.f};
+            f32x4 r = Epi::apply4(P, val[b], in[b], escale, extra);
             if (nvalid < 4) {                          // keep the pad columns of the row at zero
-              if (nvalid < 2) r.y = 0.f;
-              if (nvalid < 3) r.z = 0.f;
+              if (nvalid < 2) { r.y = 0.f; extra.y = 0.f; }
+              if (nvalid < 3) { r.z = 0.f; extra.z = 0.f; }
               r.w = 0.f;
+              extra.w = 0.f;
             }
             *reinterpret_cast<f32x4 PD_GLOBAL*>((float PD_GLOBAL*)Cout + idx[b]) = r;
+            if constexpr (Epi::kExtra) *reinterpret_cast<f32x4 PD_GLOBAL*>((float PD_GLOBAL*)P.o1 + idx[b]) = extra;
+            if constexpr (Epi::kColsum) {
+              cs0 += (double)extra.x; cs1 += (double)extra.y; cs2 += (double)extra.z; cs3 += (double)extra.w;
+            }
             if (Epi::NS >= 1)
               s0 += (double)r.x * (double)r.x + (double)r.y * (double)r.y + (double)r.z * (double)r.z +
                     (double)r.w * (double)r.w;
@@ -409,6 +454,25 @@ __device__ __forceinline__ void gemm_body(const GemmProb& P, const int local) {
         }
       }
       __builtin_amdgcn_wave_barrier();
+    }
+    if constexpr (Epi::kColsum) {
+      // lanes l, l+16, l+32, l+48 own the same columns (rows differ): add them up, then the two waves that
+      // share the columns (wm = 0, 1) through LDS; fixed order, one value per column and row tile
+      __shared__ double colred[4][64];
+      cs0 += __shfl_xor(cs0, 16, kWave); cs1 += __shfl_xor(cs1, 16, kWave);
+      cs2 += __shfl_xor(cs2, 16, kWave); cs3 += __shfl_xor(cs3, 16, kWave);
+      cs0 += __shfl_xor(cs0, 32, kWave); cs1 += __shfl_xor(cs1, 32, kWave);
+      cs2 += __shfl_xor(cs2, 32, kWave); cs3 += __shfl_xor(cs3, 32, kWave);
+      if (lane < 16) {
+        colred[wave][c4 + 0] = cs0; colred[wave][c4 + 1] = cs1;
+        colred[wave][c4 + 2] = cs2; colred[wave][c4 + 3] = cs3;
+      }
+      __syncthreads();
+      if (tid < BN) {
+        const int w = tid >> 6, c = tid & 63;          // wn, column inside the wave's 64
+        const int gcol = n0 + w * 64 + c;
+        if (gcol < P.ldc) P.colpart[(size_t)tm * P.ldc + gcol] = colred[w][c] + colred[Cfg::WN + w][c];
+      }
     }
   } else {
 #pragma unroll
@@ -456,7 +520,10 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmProb* __restrict__ 
   const int pi = find_group(map, lb, &local);
   const GemmProb P = probs[pi];
   if (predicated && !scal[P.layer].active) return;
-  gemm_body<Cfg, KCONTIG, Epi, VECC>(P, local);
+  float escale = 0.0f;
+  if (Epi::kScale == 1) escale = scal[P.layer].inv_tau;
+  if (Epi::kScale == 2) escale = scal[P.layer].inv_theta;
+  gemm_body<Cfg, KCONTIG, Epi, VECC>(P, local, escale);
 }
 
 // Single problem with the descriptor passed by value (no table in device memory needed).
@@ -464,7 +531,7 @@ template <class Cfg, bool KCONTIG, class Epi>
 __global__ __launch_bounds__(256) void gemm_one_kernel(const GemmProb P, int panel) {
   const int lb = xcd_remap(blockIdx.x, panel);
   if (lb >= P.nblk) return;
-  gemm_body<Cfg, KCONTIG, Epi, false>(P, lb);
+  gemm_body<Cfg, KCONTIG, Epi, false>(P, lb, 0.0f);
 }
 
 // Sum the split-K partial products in a fixed order: G = alpha * sum_s part[s]; also write the

@@ -65,7 +65,7 @@ struct LayerBufs {
   double *part_a, *part_b, *part_c, *colpart, *pairpart;
   int splitk, k_chunk;
   int tiles_in, tiles_out;  // GEMM tiles of [N, n_in] and [N, n_out]
-  int row_blocks, col_blocks, cw;
+  int row_blocks, col_blocks, cw, rpb;
 };
 
 // A descriptor table in device memory plus, for every launch chunk of at most kMaxGroup entries,
@@ -123,8 +123,10 @@ struct pdadmm_ctx {
   Group<GemmProb> g_pgrad, g_ptrial, g_wgrad, g_wtrial, g_resid, g_resid_obj;
   std::vector<GemmProb> fwd;          // forward pass of the starting point: one by-value launch per layer
   Group<ReduceProb> g_red, g_tred;
+  bool spec = false;          // pdADMM-G, not small: residual updates ride in the product epilogues (speculative
+                              // on the previous step size), column sums come from the G p product
   bool small_wtrial = false;  // the G p launch has too few tiles to fill the chip: split its contraction
-  Group<AxpySeg> g_pstep, g_qapply_r;
+  Group<AxpySeg> g_pstep, g_pfix, g_qapply_r;
   SelectDesc *sel_p = nullptr, *sel_w = nullptr, *sel_q = nullptr;
   Group<WStepSeg> g_w;
   Group<RowSeg> g_rows_all, g_rows_hidden;
@@ -287,6 +289,7 @@ size_t plan(pdadmm_ctx* c, void* base) {
   size_t wt_tiles = 0;
   for (int i = 0; i < L; ++i) wt_tiles += (size_t)cdiv(N, BM) * cdiv(c->dims[i + 1], BN);
   c->small_wtrial = wt_tiles * 2 <= (size_t)kGemmSlots;
+  c->spec = !Q && !c->small_wtrial;
   for (int i = 0; i < L; ++i) {
     LayerBufs& b = c->lay[i];
     b.n_in = c->dims[i];
@@ -297,7 +300,8 @@ size_t plan(pdadmm_ctx* c, void* base) {
     b.k_chunk = chunk;
     b.tiles_in = cdiv(N, BM) * cdiv(b.n_in, BN);
     b.tiles_out = cdiv(N, BM) * cdiv(b.n_out, BN);
-    b.row_blocks = cdiv(N, kRowsPerBlock);
+    b.rpb = c->spec ? BM : kRowsPerBlock;     // with spec the column sums come per 128-row product tile
+    b.row_blocks = cdiv(N, b.rpb);
     b.cw = 1;
     while (b.cw < b.ld_out / 4 && b.cw < 256) b.cw <<= 1;
     b.col_blocks = cdiv(b.ld_out / 4, b.cw);
@@ -356,6 +360,7 @@ size_t plan(pdadmm_ctx* c, void* base) {
   c->g_red.dev = cv.take<ReduceProb>(L);
   c->g_tred.dev = cv.take<ReduceProb>(L);
   c->g_pstep.dev = cv.take<AxpySeg>(2 * L);
+  c->g_pfix.dev = cv.take<AxpySeg>(L);
   c->g_qapply_r.dev = cv.take<AxpySeg>(L);
   c->sel_p = cv.take<SelectDesc>(L);
   c->sel_w = cv.take<SelectDesc>(L);
@@ -412,7 +417,7 @@ pdadmm_status build_tables(pdadmm_ctx* c) {
   const bool Q = c->cfg.quantize != 0;
   std::vector<GemmProb> pgrad, ptrial, wgrad, wtrial, resid, resid_obj, fwd;
   std::vector<ReduceProb> red, tred;
-  std::vector<AxpySeg> pstep, qapply_r;
+  std::vector<AxpySeg> pstep, pfix, qapply_r;
   std::vector<SelectDesc> sel_p, sel_w, sel_q;
   std::vector<WStepSeg> wseg;
   std::vector<RowSeg> rows;
@@ -430,6 +435,7 @@ pdadmm_status build_tables(pdadmm_ctx* c) {
       // image of the step direction under W_l: T = dir W^T (dir = g, or d in -Q)
       GemmProb T = make_nt(Q ? b.d : b.g, b.ld_in, b.W, b.ld_in, b.T, b.ld_out, N, b.n_out, b.n_in);
       T.part = b.part_b; T.layer = i;
+      if (c->spec) T.o1 = b.R;                 // r -= T / tau_prev in the epilogue
       ptrial.push_back(T);
       SelectDesc s{};
       s.part_g = b.part_a; s.ng = P.nblk; s.part_t = b.part_b; s.nt = T.nblk; s.stride_t = 1; s.layer = i;
@@ -441,7 +447,13 @@ pdadmm_status build_tables(pdadmm_ctx* c) {
       r.y = b.R; r.x = b.T; r.n4 = (size_t)N * b.ld_out / 4; r.nblk = chunk_blocks(r.n4, 1); r.layer = i;
       r.which = kScaleInvTau;
       pstep.push_back(a);
-      pstep.push_back(r);
+      if (c->spec) {                           // only the correction tau_new vs tau_prev is left for r
+        r.which = kScaleFixTau;
+        r.nblk = std::min(1024, chunk_blocks(r.n4, 1));
+        pfix.push_back(r);
+      } else {
+        pstep.push_back(r);
+      }
       if (Q) {
         QuantSeg qs{};
         qs.p = b.p; qs.g = b.g; qs.d = b.d; qs.idx = b.pidx; qs.dpart = b.part_c;
@@ -469,6 +481,10 @@ pdadmm_status build_tables(pdadmm_ctx* c) {
     GemmProb Wt_ = make_nt(b.p, b.ld_in, b.G, b.ld_in, b.T, b.ld_out, N, b.n_out, b.n_in);
     Wt_.part = b.part_b; Wt_.layer = i;
     int t_partials = Wt_.nblk;
+    if (c->spec) {                             // r -= T / theta_prev and the column sums of r in the epilogue
+      Wt_.o1 = b.R;
+      Wt_.colpart = b.colpart;
+    }
     if (c->small_wtrial) {
       // partial products into Tpart[chunk][N][ld_out]; tred sums them into T and takes ||T||^2
       Wt_.C = b.Tpart;
@@ -512,6 +528,7 @@ pdadmm_status build_tables(pdadmm_ctx* c) {
     rs.m = b.m; rs.colpart = b.colpart;
     rs.rows = N; rs.ncols = b.n_out; rs.ld = b.ld_out;
     rs.cw = b.cw; rs.col_blocks = b.col_blocks; rs.row_blocks = b.row_blocks; rs.nblk = b.col_blocks * b.row_blocks;
+    rs.rpb = b.rpb; rs.which = c->spec ? kScaleFixTheta : kScaleInvTheta;
     rs.layer = i;
     rows.push_back(rs);
     BiasSeg bs{};
@@ -543,7 +560,7 @@ pdadmm_status build_tables(pdadmm_ctx* c) {
   } while (0)
   UP(c->g_pgrad, pgrad); UP(c->g_ptrial, ptrial); UP(c->g_wgrad, wgrad); UP(c->g_wtrial, wtrial);
   UP(c->g_resid, resid); UP(c->g_resid_obj, resid_obj); UP(c->g_red, red); UP(c->g_tred, tred);
-  UP(c->g_pstep, pstep); UP(c->g_qapply_r, qapply_r);
+  UP(c->g_pstep, pstep); UP(c->g_pfix, pfix); UP(c->g_qapply_r, qapply_r);
   UP(c->g_w, wseg); UP(c->g_rows_all, rows); UP(c->g_bias, bias); UP(c->g_quant, quant); UP(c->g_pair, pair);
 #undef UP
   // the fused z/q/u pass walks the same table flat: 256*kZquUnroll float4 groups per block
@@ -597,7 +614,8 @@ pdadmm_status phase_p(pdadmm_ctx* c) {
   { TIMED(c, kClsGemmPGrad); launch_gemm<true, EpiPGrad, true>(c, c->g_pgrad, 0); }
   LAUNCH_CHECK(c, "gemm pgrad");
   if (!g.quantize) {
-    { TIMED(c, kClsGemmTrial); launch_gemm<true, EpiStoreNorm, true>(c, c->g_ptrial, 0); }
+    if (c->spec) { TIMED(c, kClsGemmTrial); launch_gemm<true, EpiTrialP, true>(c, c->g_ptrial, 0); }
+    else { TIMED(c, kClsGemmTrial); launch_gemm<true, EpiStoreNorm, true>(c, c->g_ptrial, 0); }
     LAUNCH_CHECK(c, "gemm ptrial");
     for (int i = 1; i < L; ++i) ++c->p_products[i];
     { TIMED(c, kClsSelect); hipLaunchKernelGGL(select_step_kernel, dim3(L - 1), dim3(256), 0, c->stream, c->sel_p, c->scal, 0, g.rho, g.nu,
@@ -605,6 +623,10 @@ pdadmm_status phase_p(pdadmm_ctx* c) {
     LAUNCH_CHECK(c, "select tau");
     { TIMED(c, kClsPStep); launch_group(c, c->g_pstep, axpy_kernel, (const LayerScal*)c->scal); }
     LAUNCH_CHECK(c, "p step");
+    if (c->spec) {
+      { TIMED(c, kClsPStep); launch_group(c, c->g_pfix, axpy_fix_kernel, (const LayerScal*)c->scal); }
+      LAUNCH_CHECK(c, "p step residual correction");
+    }
     return PDADMM_OK;
   }
   // -Q: trial rounds; the host only learns which layers are still searching
@@ -649,6 +671,9 @@ pdadmm_status phase_w(pdadmm_ctx* c) {
     LAUNCH_CHECK(c, "gemm wtrial (chunks)");
     { TIMED(c, kClsSplitkReduce); launch_group(c, c->g_tred, splitk_reduce_kernel); }
     LAUNCH_CHECK(c, "wtrial chunk sum");
+  } else if (c->spec) {
+    { TIMED(c, kClsGemmTrial); launch_gemm<true, EpiTrialW, true>(c, c->g_wtrial, 0); }
+    LAUNCH_CHECK(c, "gemm wtrial");
   } else {
     { TIMED(c, kClsGemmTrial); launch_gemm<true, EpiStoreNorm, true>(c, c->g_wtrial, 0); }
     LAUNCH_CHECK(c, "gemm wtrial");
