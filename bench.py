@@ -137,7 +137,8 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=10,
+                    help="untimed iterations first (default 10: by then the step sizes tau, theta of the perturbed start have settled)")
     ap.add_argument("--workload", default="C2", help="C1..C5, C5pq (default C2: the configuration the metric is quoted on)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--dominant-only", action="store_true",

@@ -76,30 +76,38 @@ struct EpiStoreNorm { // C = acc, s0 += acc^2
     s0 += (double)acc * (double)acc;
   }
 };
-struct EpiPGrad {     // g = nu*acc + u + rho*(p - q) (gradient of phi in p_l); s0 += g^2
+// g = nu*acc + u + rho*(p - q) (gradient of phi in p_l); s0 += g^2. With UPD (pdADMM-G) the same pass
+// also takes the step p -= g / tau_prev (o1 = p, in place; the old p was read for g), corrected later if
+// the selection changes tau (see EpiTrialUpd).
+template <bool UPD>
+struct EpiPGradT {
   static constexpr int NS = 1, kBatch = 4;   // elements whose inputs are fetched together (8 would cost the third block per compute unit)
-  static constexpr bool kVec = true;
+  static constexpr bool kVec = true, kExtra = UPD, kColsum = false;
+  static constexpr int kScale = UPD ? 1 : 0;
   struct In { float u, p, q; };
   struct In4 { f32x4 u, p, q; };
-  __device__ static __forceinline__ In4 load4(const GemmProb& P, size_t i) {
-    return In4{*reinterpret_cast<gcf4>((gcf)P.e0 + i), *reinterpret_cast<gcf4>((gcf)P.e1 + i),
-               *reinterpret_cast<gcf4>((gcf)P.e2 + i)};
-  }
-  static constexpr bool kExtra = false, kColsum = false;
-  static constexpr int kScale = 0;
-  __device__ static __forceinline__ f32x4 apply4(const GemmProb& P, f32x4 acc, const In4& in, float, f32x4&) {
-    return P.alpha * acc + in.u + P.beta * (in.p - in.q);
-  }
   __device__ static __forceinline__ In load(const GemmProb& P, size_t i, int) {
     return In{((gcf)P.e0)[i], ((gcf)P.e1)[i], ((gcf)P.e2)[i]};
   }
-  __device__ static __forceinline__ void apply(const GemmProb& P, float* C, size_t i, int, float acc,
-                                               const In& in, double& s0, double&) {
+  __device__ static __forceinline__ void apply(const GemmProb& P, float* C, size_t i, int, float acc, const In& in,
+                                               double& s0, double&) {
     const float g = P.alpha * acc + in.u + P.beta * (in.p - in.q);
     ((float PD_GLOBAL*)C)[i] = g;
     s0 += (double)g * (double)g;
   }
+  __device__ static __forceinline__ In4 load4(const GemmProb& P, size_t i) {
+    return In4{*reinterpret_cast<gcf4>((gcf)P.e0 + i), *reinterpret_cast<gcf4>((gcf)P.e1 + i),
+               *reinterpret_cast<gcf4>((gcf)P.e2 + i)};
+  }
+  __device__ static __forceinline__ f32x4 apply4(const GemmProb& P, f32x4 acc, const In4& in, float s_prev, f32x4& extra) {
+    const f32x4 g = P.alpha * acc + in.u + P.beta * (in.p - in.q);
+    if (UPD) extra = in.p - s_prev * g;
+    return g;
+  }
 };
+typedef EpiPGradT<false> EpiPGrad;
+typedef EpiPGradT<true> EpiPGradUpd;
+
 // Step-direction products with the residual update folded in (pdADMM-G). T = acc is stored and its norm
 // taken as in EpiStoreNorm; in the same pass the carried residual r = W p + b - z (o1, in place) takes the
 // update r -= s_prev * T with the step size of the previous iteration, which is almost always the one the
@@ -416,14 +424,16 @@ __device__ __forceinline__ void gemm_body(const GemmProb& P, const int local, co
       __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
       __builtin_amdgcn_wave_barrier();
       __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+      // three input streams plus a second output leave registers for two groups only
+      constexpr int VB = (Epi::kExtra && sizeof(typename Epi::In4) > 16) ? 2 : kVecBatch;
 #pragma unroll
-      for (int it = 0; it < 8; it += kVecBatch) {
-        typename Epi::In4 in[kVecBatch];
-        f32x4 val[kVecBatch];
-        size_t idx[kVecBatch];
-        bool on[kVecBatch];
+      for (int it = 0; it < 8; it += VB) {
+        typename Epi::In4 in[VB];
+        f32x4 val[VB];
+        size_t idx[VB];
+        bool on[VB];
 #pragma unroll
-        for (int b = 0; b < kVecBatch; ++b) {
+        for (int b = 0; b < VB; ++b) {
           const int rl = (it + b) * 4 + rr;
           const int row = m0 + wm * (BM / Cfg::WM) + i * 32 + rl;
           on[b] = row < P.M && nvalid > 0;
@@ -432,7 +442,7 @@ __device__ __forceinline__ void gemm_body(const GemmProb& P, const int local, co
           if (on[b]) in[b] = Epi::load4(P, idx[b]);
         }
 #pragma unroll
-        for (int b = 0; b < kVecBatch; ++b) {
+        for (int b = 0; b < VB; ++b) {
           if (on[b]) {
             f32x4 extra = {0.f, 0.f, 0.f, 0.f};
             f32x4 r = Epi::apply4(P, val[b], in[b], escale, extra);

@@ -360,7 +360,7 @@ size_t plan(pdadmm_ctx* c, void* base) {
   c->g_red.dev = cv.take<ReduceProb>(L);
   c->g_tred.dev = cv.take<ReduceProb>(L);
   c->g_pstep.dev = cv.take<AxpySeg>(2 * L);
-  c->g_pfix.dev = cv.take<AxpySeg>(L);
+  c->g_pfix.dev = cv.take<AxpySeg>(2 * L);
   c->g_qapply_r.dev = cv.take<AxpySeg>(L);
   c->sel_p = cv.take<SelectDesc>(L);
   c->sel_w = cv.take<SelectDesc>(L);
@@ -431,6 +431,7 @@ pdadmm_status build_tables(pdadmm_ctx* c) {
       GemmProb P = make_nt(b.R, b.ld_out, b.Wt, b.ld_out, b.g, b.ld_in, N, b.n_in, b.n_out);
       P.e0 = c->lay[i - 1].u; P.e1 = b.p; P.e2 = c->lay[i - 1].q;
       P.alpha = nu; P.beta = rho; P.part = b.part_a; P.layer = i;
+      if (c->spec) P.o1 = b.p;                 // p -= g / tau_prev in the epilogue
       pgrad.push_back(P);
       // image of the step direction under W_l: T = dir W^T (dir = g, or d in -Q)
       GemmProb T = make_nt(Q ? b.d : b.g, b.ld_in, b.W, b.ld_in, b.T, b.ld_out, N, b.n_out, b.n_in);
@@ -446,12 +447,14 @@ pdadmm_status build_tables(pdadmm_ctx* c) {
       AxpySeg r{};
       r.y = b.R; r.x = b.T; r.n4 = (size_t)N * b.ld_out / 4; r.nblk = chunk_blocks(r.n4, 1); r.layer = i;
       r.which = kScaleInvTau;
-      pstep.push_back(a);
-      if (c->spec) {                           // only the correction tau_new vs tau_prev is left for r
-        r.which = kScaleFixTau;
+      if (c->spec) {                           // only the correction tau_new vs tau_prev is left for p and r
+        a.which = r.which = kScaleFixTau;
+        a.nblk = std::min(1024, chunk_blocks(a.n4, 1));
         r.nblk = std::min(1024, chunk_blocks(r.n4, 1));
+        pfix.push_back(a);
         pfix.push_back(r);
       } else {
+        pstep.push_back(a);
         pstep.push_back(r);
       }
       if (Q) {
@@ -611,7 +614,8 @@ pdadmm_status phase_p(pdadmm_ctx* c) {
   const int L = c->L;
   if (L < 2) return PDADMM_OK;
   const pdadmm_config& g = c->cfg;
-  { TIMED(c, kClsGemmPGrad); launch_gemm<true, EpiPGrad, true>(c, c->g_pgrad, 0); }
+  if (c->spec) { TIMED(c, kClsGemmPGrad); launch_gemm<true, EpiPGradUpd, true>(c, c->g_pgrad, 0); }
+  else { TIMED(c, kClsGemmPGrad); launch_gemm<true, EpiPGrad, true>(c, c->g_pgrad, 0); }
   LAUNCH_CHECK(c, "gemm pgrad");
   if (!g.quantize) {
     if (c->spec) { TIMED(c, kClsGemmTrial); launch_gemm<true, EpiTrialP, true>(c, c->g_ptrial, 0); }
@@ -621,11 +625,12 @@ pdadmm_status phase_p(pdadmm_ctx* c) {
     { TIMED(c, kClsSelect); hipLaunchKernelGGL(select_step_kernel, dim3(L - 1), dim3(256), 0, c->stream, c->sel_p, c->scal, 0, g.rho, g.nu,
                        g.bt_eta, g.bt_max_trials, c->err); }
     LAUNCH_CHECK(c, "select tau");
-    { TIMED(c, kClsPStep); launch_group(c, c->g_pstep, axpy_kernel, (const LayerScal*)c->scal); }
-    LAUNCH_CHECK(c, "p step");
-    if (c->spec) {
+    if (!c->spec) {
+      { TIMED(c, kClsPStep); launch_group(c, c->g_pstep, axpy_kernel, (const LayerScal*)c->scal); }
+      LAUNCH_CHECK(c, "p step");
+    } else {
       { TIMED(c, kClsPStep); launch_group(c, c->g_pfix, axpy_fix_kernel, (const LayerScal*)c->scal); }
-      LAUNCH_CHECK(c, "p step residual correction");
+      LAUNCH_CHECK(c, "p step correction");
     }
     return PDADMM_OK;
   }
