@@ -37,17 +37,21 @@ def gemm_flops_per_iteration(dims, n_nodes):
                 gemm_wgrad=sum(per))                 # r p^T          (all l)
 
 
-def elementwise_bytes_per_iteration(dims, n_nodes, quant):
+def elementwise_bytes_per_iteration(dims, n_nodes, quant, fused):
     """Algorithmic HBM bytes of the streaming kernels of one iteration (fp32 arrays of N x n, each counted
-    once per read and once per write): p-step 3 passes over [N, n_{l-1}] and 3 over [N, n_l] (l >= 2);
-    residual update + column sums 3 passes over [N, n_l] (all l); fused z/q/u 5 reads + 4 writes over
-    [N, n_l] (l < L). The -Q projection kernels are left out (they run a data-dependent number of times)."""
+    once per read and once per write): fused z/q/u 5 reads + 4 writes over [N, n_l] (l < L); where the
+    library applies them in separate kernels (fused = False) also the p-step, 3 passes over [N, n_{l-1}]
+    and 3 over [N, n_l] (l >= 2), and the residual update + column sums, 3 passes over [N, n_l] (all l).
+    With fused = True those two ride in the product epilogues and the kernels of their classes are
+    corrections that do nothing once the step sizes have settled: no bytes are credited to them.
+    The -Q projection kernels are left out (they run a data-dependent number of times)."""
     L = len(dims) - 1
     e = 4.0 * n_nodes
-    out = dict(resid_colsum=sum(3 * e * dims[i + 1] for i in range(L)),
-               zqu=sum(9 * e * dims[i + 1] for i in range(L - 1)))
-    if not quant:
-        out["p_step"] = sum(3 * e * (dims[i] + dims[i + 1]) for i in range(1, L))
+    out = dict(zqu=sum(9 * e * dims[i + 1] for i in range(L - 1)))
+    if not fused:
+        out["resid_colsum"] = sum(3 * e * dims[i + 1] for i in range(L))
+        if not quant:
+            out["p_step"] = sum(3 * e * (dims[i] + dims[i + 1]) for i in range(1, L))
     return out
 
 
@@ -187,6 +191,7 @@ def main():
     timing = P.pdadmm_timing_read(ctx)
     P.pdadmm_timing(ctx, 0)
     stats = P.pdadmm_stats(ctx)
+    plan = P.pdadmm_plan_info(ctx)
     obj = P.pdadmm_objective(ctx)
 
     flops = gemm_flops_per_iteration(w.dims, w.n_nodes)
@@ -218,13 +223,15 @@ def main():
                gemm_tflops_whole_iteration=total_gemm_flops * args.steps / dt / 1e12,
                roofline=roofline,
                augment_ms=info["augment_ms"], objective_after=obj["L_rho"],
-               p_trials=[int(x) for x in stats["p_trials"]], w_trials=[int(x) for x in stats["w_trials"]])
+               p_trials=[int(x) for x in stats["p_trials"]], w_trials=[int(x) for x in stats["w_trials"]],
+               plan=dict(fused_updates=plan["fused_updates"], wgrad_split=[int(x) for x in plan["wgrad_split"]],
+                         wtrial_split=plan["wtrial_split"]))
     if not args.dominant_only and not args.graph:
         cls = {k: v[0] / args.steps for k, v in timing.items() if v[1]}
         out["class_ms_per_step"] = cls
         gemm_ms = sum(cls.get(k, 0.0) for k in ("gemm_pgrad", "gemm_trial", "gemm_wgrad", "splitk_reduce"))
         launched = total_gemm_flops
-        eb = elementwise_bytes_per_iteration(w.dims, w.n_nodes, w.quant)
+        eb = elementwise_bytes_per_iteration(w.dims, w.n_nodes, w.quant, plan["fused_updates"])
         ew_ms = sum(cls.get(k, 0.0) for k in eb)
         out["phases"] = dict(
             gemm=dict(ms=gemm_ms, tflops=launched / (gemm_ms * 1e-3) / 1e12 if gemm_ms else None,
@@ -232,6 +239,8 @@ def main():
             elementwise=dict(ms=ew_ms, gbs=sum(eb.values()) / (ew_ms * 1e-3) / 1e9 if ew_ms else None,
                              frac_of_hbm_peak=sum(eb.values()) / (ew_ms * 1e-3) / 1e9 / HBM_PEAK_GBS if ew_ms else None,
                              per_kernel_gbs={k: eb[k] / (cls[k] * 1e-3) / 1e9 for k in eb if cls.get(k)}))
+        if plan["fused_updates"]:     # what is left of these classes: the step-size corrections
+            out["phases"]["corrections_ms"] = cls.get("p_step", 0.0) + cls.get("resid_colsum", 0.0)
     if not args.no_cpu_baseline:
         del ctx
         torch.cuda.empty_cache()

@@ -214,6 +214,15 @@ pdadmm_status pdadmm_predict(pdadmm_ctx* ctx, int32_t* pred, float* logits, cons
 pdadmm_status pdadmm_stats(pdadmm_ctx* ctx, double* tau, double* theta, int32_t* p_trials,
                            int32_t* w_trials, double* r_drift, int64_t* p_products);
 
+/* Launch plan the context was built with (HOST outputs, each may be NULL). fused_updates: 1 if the
+ * p-step and the residual updates r -= T/tau, r -= T/theta (with their column sums) are applied in the
+ * epilogues of the dense products with the step size of the previous iteration and corrected by a
+ * separate pass only when the backtracking rule picks another one (pdADMM-G with enough product tiles
+ * to fill the chip), 0 if separate streaming kernels apply them. wgrad_split (L entries): number of
+ * node-range chunks the r p^T product of each layer is split into. wtrial_split: number of chunks the
+ * contraction of the G p products is split into (1 = not split). Does not synchronise. */
+pdadmm_status pdadmm_plan_info(pdadmm_ctx* ctx, int32_t* fused_updates, int32_t* wgrad_split, int32_t* wtrial_split);
+
 /*
  * Per-launch timing with HIP events recorded on the context's stream around the launches of the
  * selected kernel classes (bit i of class_mask = class i; 0 switches timing off and drops pending

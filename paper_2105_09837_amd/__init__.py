@@ -7,7 +7,7 @@ from .binding import (PdadmmError, Config, Context, load_library, library_path, 
                       pdadmm_normalize_adj, pdadmm_augment, pdadmm_quantize, pdadmm_gemm_nt,
                       pdadmm_gemm_tn, pdadmm_workspace_bytes, pdadmm_init, pdadmm_set_var,
                       pdadmm_get_var, pdadmm_iterate, pdadmm_step_phase, pdadmm_sync,
-                      pdadmm_objective, pdadmm_residual, pdadmm_stats, pdadmm_predict, pdadmm_destroy,
+                      pdadmm_objective, pdadmm_residual, pdadmm_stats, pdadmm_plan_info, pdadmm_predict, pdadmm_destroy,
                       pdadmm_timing, pdadmm_timing_read, TIMING_CLASSES,
                       VAR, PHASE)
 

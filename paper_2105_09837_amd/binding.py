@@ -44,7 +44,8 @@ class _CObjective(C.Structure):
 
 EXPORTS = ["pdadmm_normalize_adj", "pdadmm_augment", "pdadmm_quantize", "pdadmm_gemm_nt", "pdadmm_gemm_tn",
            "pdadmm_workspace_bytes", "pdadmm_init", "pdadmm_set_var", "pdadmm_get_var", "pdadmm_iterate",
-           "pdadmm_step_phase", "pdadmm_sync", "pdadmm_objective", "pdadmm_residual", "pdadmm_stats", "pdadmm_predict",
+           "pdadmm_step_phase", "pdadmm_sync", "pdadmm_objective", "pdadmm_residual", "pdadmm_stats", "pdadmm_plan_info",
+           "pdadmm_predict",
            "pdadmm_timing", "pdadmm_timing_read", "pdadmm_last_error", "pdadmm_destroy"]
 
 
@@ -84,6 +85,7 @@ def load_library():
     lib.pdadmm_objective.argtypes = [vp, C.POINTER(_CObjective)]
     lib.pdadmm_residual.argtypes = [vp, C.POINTER(C.c_double), vp]
     lib.pdadmm_stats.argtypes = [vp, vp, vp, vp, vp, vp, vp]
+    lib.pdadmm_plan_info.argtypes = [vp, vp, vp, vp]
     lib.pdadmm_predict.argtypes = [vp, vp, vp, vp, vp]
     lib.pdadmm_timing.argtypes = [vp, C.c_uint32]
     lib.pdadmm_timing_read.argtypes = [vp, vp, vp, i32]
@@ -362,6 +364,14 @@ def pdadmm_stats(ctx: Context, drift: bool = False) -> dict:
                                        wt.ctypes.data, C.addressof(d) if drift else None, pp.ctypes.data),
            "pdadmm_stats", ctx)
     return dict(tau=tau, theta=theta, p_trials=pt, w_trials=wt, r_drift=d.value if drift else None, p_products=pp)
+
+
+def pdadmm_plan_info(ctx: Context) -> dict:
+    fused, wts = C.c_int32(0), C.c_int32(0)
+    ws = np.zeros(ctx.L, dtype=np.int32)
+    _check(load_library().pdadmm_plan_info(ctx.handle, C.addressof(fused), ws.ctypes.data, C.addressof(wts)),
+           "pdadmm_plan_info", ctx)
+    return dict(fused_updates=bool(fused.value), wgrad_split=ws, wtrial_split=int(wts.value))
 
 
 def pdadmm_predict(ctx: Context, mask=None, want_logits: bool = False) -> dict:

@@ -256,21 +256,30 @@ __device__ __forceinline__ void load_operand(f32x4 (&reg)[NV], gcf base, int ld,
   }
 }
 
+// LDS position of element (k, c) of a staged operand tile: rows of LD floats, and rows with k & 8 set
+// start 8 floats later. k-contiguous operands arrive through a transposing 4-byte store in which the
+// four lanes of a quad hold k = 0, 4, 8, 12 of one tile row; with LD = 4 (mod 32) rows k and k + 8
+// would meet in the same banks, the shift moves them 8 banks apart. Fragment reads (32 consecutive c of
+// one k) and 16-byte row stores are unaffected. A tile buffer holds BK * LD + 8 floats.
+template <int LD>
+__device__ __forceinline__ constexpr int lds_pos(int k, int c) { return k * LD + (k & 8) + c; }
+
 // Writes a register tile to LDS as [k][m]. With FAST the entries whose k lies beyond kend are zeroed here.
 template <bool KCONTIG, bool FAST, int ROWS, int BK, int LD, int NV>
-__device__ __forceinline__ void store_operand(float (*lds)[LD], const f32x4 (&reg)[NV], int kb, int kend, int tid) {
+__device__ __forceinline__ void store_operand(float* lds, const f32x4 (&reg)[NV], int kb, int kend, int tid) {
   if (KCONTIG) {
     constexpr int KQ = BK / 4;
     constexpr int RSTEP = 256 / KQ;
     const int r = tid / KQ, kq = (tid % KQ) * 4;
     const int rem = kend - (kb + kq);     // components c < rem are inside the k range
+    float* dst = lds + lds_pos<LD>(kq, r);  // kq + 0..3 share the bit kq & 8
 #pragma unroll
     for (int h = 0; h < NV; ++h) {
-      const int c = r + RSTEP * h;
-      lds[kq + 0][c] = (!FAST || rem > 0) ? reg[h].x : 0.f;
-      lds[kq + 1][c] = (!FAST || rem > 1) ? reg[h].y : 0.f;
-      lds[kq + 2][c] = (!FAST || rem > 2) ? reg[h].z : 0.f;
-      lds[kq + 3][c] = (!FAST || rem > 3) ? reg[h].w : 0.f;
+      const int c = RSTEP * h;
+      dst[0 * LD + c] = (!FAST || rem > 0) ? reg[h].x : 0.f;
+      dst[1 * LD + c] = (!FAST || rem > 1) ? reg[h].y : 0.f;
+      dst[2 * LD + c] = (!FAST || rem > 2) ? reg[h].z : 0.f;
+      dst[3 * LD + c] = (!FAST || rem > 3) ? reg[h].w : 0.f;
     }
   } else {
     constexpr int MQ = ROWS / 4;
@@ -280,7 +289,7 @@ __device__ __forceinline__ void store_operand(float (*lds)[LD], const f32x4 (&re
     for (int h = 0; h < NV; ++h) {
       f32x4 v = reg[h];
       if (FAST && kb + kr + KSTEP * h >= kend) v = f32x4{0.f, 0.f, 0.f, 0.f};
-      *reinterpret_cast<f32x4*>(&lds[kr + KSTEP * h][mq]) = v;
+      *reinterpret_cast<f32x4*>(lds + lds_pos<LD>(kr + KSTEP * h, mq)) = v;
     }
   }
 }
@@ -297,10 +306,12 @@ __device__ __forceinline__ void gemm_body(const GemmProb& P, const int local, co
   constexpr int LDA = Cfg::LDA, LDB = Cfg::LDB;
   constexpr int NVA = BM * BK / 4 / 256, NVB = BN * BK / 4 / 256;
   static_assert(NVA >= 1 && NVB >= 1, "tile too small for 256 loader threads");
-  __shared__ __attribute__((aligned(16))) float smem[2 * BK * LDA + 2 * BK * LDB];
+  constexpr int BUFA = BK * LDA + 8, BUFB = BK * LDB + 8;   // one staged tile of each operand (see lds_pos)
+  static_assert(BK <= 16, "lds_pos shifts the rows with k & 8 set: at most one shifted run per tile");
+  __shared__ __attribute__((aligned(16))) float smem[2 * BUFA + 2 * BUFB];
   __shared__ double red[4];
-  float (*As)[BK][LDA] = reinterpret_cast<float (*)[BK][LDA]>(smem);
-  float (*Bs)[BK][LDB] = reinterpret_cast<float (*)[BK][LDB]>(smem + 2 * BK * LDA);
+  float* const As = smem;
+  float* const Bs = smem + 2 * BUFA;
 
   const int tiles = P.tiles_m * P.tiles_n;
   const int split = local / tiles;
@@ -335,17 +346,17 @@ __device__ __forceinline__ void gemm_body(const GemmProb& P, const int local, co
   auto compute_tile = [&](int cur, auto&& mid) {
     float a[2][TM], b[2][TN];
 #pragma unroll
-    for (int i = 0; i < TM; ++i) a[0][i] = As[cur][lh][wm * (BM / Cfg::WM) + i * 32 + li];
+    for (int i = 0; i < TM; ++i) a[0][i] = As[cur * BUFA + lds_pos<LDA>(0, 0) + lh * LDA + wm * (BM / Cfg::WM) + i * 32 + li];
 #pragma unroll
-    for (int j = 0; j < TN; ++j) b[0][j] = Bs[cur][lh][wn * (BN / Cfg::WN) + j * 32 + li];
+    for (int j = 0; j < TN; ++j) b[0][j] = Bs[cur * BUFB + lds_pos<LDB>(0, 0) + lh * LDB + wn * (BN / Cfg::WN) + j * 32 + li];
 #pragma unroll
     for (int kk = 0; kk < BK; kk += 2) {
       const int c = (kk >> 1) & 1, n = c ^ 1;
       if (kk + 2 < BK) {
 #pragma unroll
-        for (int i = 0; i < TM; ++i) a[n][i] = As[cur][kk + 2 + lh][wm * (BM / Cfg::WM) + i * 32 + li];
+        for (int i = 0; i < TM; ++i) a[n][i] = As[cur * BUFA + lds_pos<LDA>(kk + 2, 0) + lh * LDA + wm * (BM / Cfg::WM) + i * 32 + li];
 #pragma unroll
-        for (int j = 0; j < TN; ++j) b[n][j] = Bs[cur][kk + 2 + lh][wn * (BN / Cfg::WN) + j * 32 + li];
+        for (int j = 0; j < TN; ++j) b[n][j] = Bs[cur * BUFB + lds_pos<LDB>(kk + 2, 0) + lh * LDB + wn * (BN / Cfg::WN) + j * 32 + li];
       }
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -375,8 +386,8 @@ __device__ __forceinline__ void gemm_body(const GemmProb& P, const int local, co
     };
     auto store_tile = [&](int kt, int buf, const f32x4 (&ra)[NVA], const f32x4 (&rb)[NVB]) {
       const int kb = kbeg + kt * BK;
-      store_operand<KCONTIG, FAST, BM, BK, LDA, NVA>(As[buf], ra, kb, kend, tid);
-      store_operand<KCONTIG, FAST, BN, BK, LDB, NVB>(Bs[buf], rb, kb, kend, tid);
+      store_operand<KCONTIG, FAST, BM, BK, LDA, NVA>(As + buf * BUFA, ra, kb, kend, tid);
+      store_operand<KCONTIG, FAST, BN, BK, LDB, NVB>(Bs + buf * BUFB, rb, kb, kend, tid);
     };
     load_tile(0, ra0, rb0);
     load_tile(1, ra1, rb1);
@@ -408,7 +419,7 @@ __device__ __forceinline__ void gemm_body(const GemmProb& P, const int local, co
     // Row-contiguous epilogue: every wave passes its 64x64 sub-tile through LDS (32 rows at a time, the
     // operand buffers are free now) and then owns whole 16-byte column groups, so all global accesses
     // of the epilogue are coalesced 16-byte loads and stores, a quarter as many as element by element.
-    static_assert(TN * 32 == 64 && 4 * 32 * 64 <= 2 * BK * LDA + 2 * BK * LDB, "staging area");
+    static_assert(TN * 32 == 64 && 4 * 32 * 64 <= 2 * BUFA + 2 * BUFB, "staging area");
     __syncthreads();                                   // all waves are done with the operand buffers
     float* stage = smem + wave * (32 * 64);
     const int rr = lane >> 4, c4 = (lane & 15) * 4;    // row (mod 4) and first column of this lane's groups

@@ -1259,6 +1259,19 @@ pdadmm_status pdadmm_stats(pdadmm_ctx* c, double* tau, double* theta, int32_t* p
   return check_device_flags(c);
 }
 
+pdadmm_status pdadmm_plan_info(pdadmm_ctx* c, int32_t* fused_updates, int32_t* wgrad_split, int32_t* wtrial_split) {
+  if (!c) return PDADMM_EINVAL;
+  if (fused_updates) *fused_updates = c->spec ? 1 : 0;
+  if (wgrad_split)
+    for (int i = 0; i < c->L; ++i) wgrad_split[i] = c->lay[i].splitk;
+  if (wtrial_split) {
+    int s = 1;
+    for (int i = 0; i < c->L; ++i) s = std::max(s, c->lay[i].wt_split);
+    *wtrial_split = s;
+  }
+  return PDADMM_OK;
+}
+
 pdadmm_status pdadmm_predict(pdadmm_ctx* c, int32_t* pred, float* logits, const uint8_t* mask, double* accuracy) {
   if (!c) return PDADMM_EINVAL;
   const int N = c->N, L = c->L;
