@@ -40,18 +40,18 @@ def gemm_flops_per_iteration(dims, n_nodes):
 def elementwise_bytes_per_iteration(dims, n_nodes, quant, fused):
     """Algorithmic HBM bytes of the streaming kernels of one iteration (fp32 arrays of N x n, each counted
     once per read and once per write): fused z/q/u 5 reads + 4 writes over [N, n_l] (l < L); where the
-    library applies them in separate kernels (fused = False) also the p-step, 3 passes over [N, n_{l-1}]
-    and 3 over [N, n_l] (l >= 2), and the residual update + column sums, 3 passes over [N, n_l] (all l).
-    With fused = True those two ride in the product epilogues and the kernels of their classes are
-    corrections that do nothing once the step sizes have settled: no bytes are credited to them.
-    The -Q projection kernels are left out (they run a data-dependent number of times)."""
+    library applies them in separate kernels also the p-step, 3 passes over [N, n_{l-1}] and 3 over
+    [N, n_l] (l >= 2; bit 0 of `fused` clear), and the residual update + column sums, 3 passes over
+    [N, n_l] (all l; bit 1 clear). Where a bit is set that update rides in the product epilogues and the
+    kernels of its class are corrections that do nothing once the step sizes have settled: no bytes are
+    credited to them. The -Q projection kernels are left out (they run a data-dependent number of times)."""
     L = len(dims) - 1
     e = 4.0 * n_nodes
     out = dict(zqu=sum(9 * e * dims[i + 1] for i in range(L - 1)))
-    if not fused:
+    if not fused & 2:
         out["resid_colsum"] = sum(3 * e * dims[i + 1] for i in range(L))
-        if not quant:
-            out["p_step"] = sum(3 * e * (dims[i] + dims[i + 1]) for i in range(1, L))
+    if not fused & 1 and not quant:
+        out["p_step"] = sum(3 * e * (dims[i] + dims[i + 1]) for i in range(1, L))
     return out
 
 
@@ -240,7 +240,8 @@ def main():
                              frac_of_hbm_peak=sum(eb.values()) / (ew_ms * 1e-3) / 1e9 / HBM_PEAK_GBS if ew_ms else None,
                              per_kernel_gbs={k: eb[k] / (cls[k] * 1e-3) / 1e9 for k in eb if cls.get(k)}))
         if plan["fused_updates"]:     # what is left of these classes: the step-size corrections
-            out["phases"]["corrections_ms"] = cls.get("p_step", 0.0) + cls.get("resid_colsum", 0.0)
+            out["phases"]["corrections_ms"] = ((cls.get("p_step", 0.0) if plan["fused_updates"] & 1 else 0.0)
+                                               + (cls.get("resid_colsum", 0.0) if plan["fused_updates"] & 2 else 0.0))
     if not args.no_cpu_baseline:
         del ctx
         torch.cuda.empty_cache()

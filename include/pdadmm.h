@@ -167,6 +167,26 @@ pdadmm_status pdadmm_init(pdadmm_ctx** out, const pdadmm_config* cfg, void* work
                           const float* const* W0, const float* const* b0, void* stream);
 
 /*
+ * Greedy layer-wise training (Section 3.2, the paragraph after Algorithm 1; Section 5.3 trains 2, then
+ * 5, then all 10 layers): start a deeper model from a trained shallower one. A new context is set up
+ * exactly as by pdadmm_init, except that layer l of the new model takes W_l, b_l from layer
+ * from_layer[l-1] of the context `from` where that entry is positive (that layer must have the same
+ * n_{l-1} and n_l), and from the caller's W0[l-1], b0[l-1] where it is 0. Which layers are carried over
+ * is the caller's schedule (the paper fixes none); the state is the forward-consistent start of the
+ * new weights, step sizes start again at tau0, theta0.
+ *  from:       context with the same n_nodes; its stream is synchronised first; it stays valid and
+ *              unchanged, and may be destroyed afterwards.
+ *  from_layer: HOST int32 [n_layers]. W0, b0: HOST arrays of n_layers DEVICE pointers; entries of
+ *              carried-over layers are ignored (NULL allowed); both may be NULL if every layer is
+ *              carried over. Everything else as for pdadmm_init, the errors too (EINVAL also for a
+ *              source layer out of range or of another shape).
+ */
+pdadmm_status pdadmm_grow_layers(pdadmm_ctx** out, const pdadmm_config* cfg, void* workspace, size_t workspace_bytes,
+                                 const float* X_aug, const int32_t* labels, const uint8_t* train_mask,
+                                 pdadmm_ctx* from, const int32_t* from_layer, const float* const* W0,
+                                 const float* const* b0, void* stream);
+
+/*
  * Copy a variable in or out. `layer` is the paper's l. The buffer is dense (leading dimension =
  * width) and may be HOST or DEVICE memory, except TAU/THETA (HOST double) and PROBE (HOST int32[2]).
  * Both calls synchronise.
@@ -214,11 +234,12 @@ pdadmm_status pdadmm_predict(pdadmm_ctx* ctx, int32_t* pred, float* logits, cons
 pdadmm_status pdadmm_stats(pdadmm_ctx* ctx, double* tau, double* theta, int32_t* p_trials,
                            int32_t* w_trials, double* r_drift, int64_t* p_products);
 
-/* Launch plan the context was built with (HOST outputs, each may be NULL). fused_updates: 1 if the
- * p-step and the residual updates r -= T/tau, r -= T/theta (with their column sums) are applied in the
- * epilogues of the dense products with the step size of the previous iteration and corrected by a
- * separate pass only when the backtracking rule picks another one (pdADMM-G with enough product tiles
- * to fill the chip), 0 if separate streaming kernels apply them. wgrad_split (L entries): number of
+/* Launch plan the context was built with (HOST outputs, each may be NULL). fused_updates: bit 0 set if
+ * the p-step and the residual update r -= Wg/tau are applied in the epilogues of the dense products
+ * with the step size of the previous iteration and corrected by a separate pass only when the
+ * backtracking rule picks another one (pdADMM-G with enough product tiles to fill the chip); bit 1
+ * set if the same holds for r -= Gp/theta and its column sums (both variants, same size condition).
+ * A clear bit means separate streaming kernels apply that update. wgrad_split (L entries): number of
  * node-range chunks the r p^T product of each layer is split into. wtrial_split: number of chunks the
  * contraction of the G p products is split into (1 = not split). Does not synchronise. */
 pdadmm_status pdadmm_plan_info(pdadmm_ctx* ctx, int32_t* fused_updates, int32_t* wgrad_split, int32_t* wtrial_split);

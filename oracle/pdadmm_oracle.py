@@ -225,6 +225,26 @@ def init_forward(X_aug, W0, b0, y, rho, nu, grid: Optional[Grid] = None, mask=No
                  p_wait=[0] * L, p_skip=[0] * L, **kw)
 
 
+def grow_layers(st: State, from_layer, W_new, b_new, **kw) -> State:
+    """Greedy layer-wise training (Section 3.2, after Algorithm 1; Section 5.3 goes 2 -> 5 -> 10 layers):
+    a deeper model whose layer l takes W_l, b_l from layer from_layer[l-1] of the trained model `st`
+    where that entry is positive and from W_new[l-1], b_new[l-1] where it is 0; the state is the
+    forward-consistent start of these weights on the same inputs, labels, rho, nu, grid and activation
+    (the paper fixes neither the schedule nor the restart; step sizes start again)."""
+    W, b = [], []
+    for i, src in enumerate(from_layer):
+        if src > 0:
+            if st.W[src - 1].shape[1] != (W[-1].shape[0] if W else st.p[0].shape[1]):
+                raise ValueError(f"layer {i + 1}: source layer {src} has another input width")
+            W.append(st.W[src - 1].copy())
+            b.append(st.b[src - 1].copy())
+        else:
+            W.append(np.asarray(W_new[i], dtype=F64))
+            b.append(np.asarray(b_new[i], dtype=F64))
+    return init_forward(st.p[0], W, b, st.y, st.rho, st.nu, grid=st.grid, mask=st.mask,
+                        quantize_q=st.quantize_q, slope=st.slope, **kw)
+
+
 def phi(st: State, i: int, p=None, W=None, b=None) -> float:
     """phi for layer l = i+1 (Section 3.2): (nu/2)||z - W p - b||^2, plus for l >= 2
     <u_{l-1}, p - q_{l-1}> + (rho/2)||p - q_{l-1}||^2."""

@@ -43,7 +43,7 @@ class _CObjective(C.Structure):
 
 
 EXPORTS = ["pdadmm_normalize_adj", "pdadmm_augment", "pdadmm_quantize", "pdadmm_gemm_nt", "pdadmm_gemm_tn",
-           "pdadmm_workspace_bytes", "pdadmm_init", "pdadmm_set_var", "pdadmm_get_var", "pdadmm_iterate",
+           "pdadmm_workspace_bytes", "pdadmm_init", "pdadmm_grow_layers", "pdadmm_set_var", "pdadmm_get_var", "pdadmm_iterate",
            "pdadmm_step_phase", "pdadmm_sync", "pdadmm_objective", "pdadmm_residual", "pdadmm_stats", "pdadmm_plan_info",
            "pdadmm_predict",
            "pdadmm_timing", "pdadmm_timing_read", "pdadmm_last_error", "pdadmm_destroy"]
@@ -77,6 +77,8 @@ def load_library():
     lib.pdadmm_workspace_bytes.restype = C.c_size_t
     lib.pdadmm_init.argtypes = [C.POINTER(vp), C.POINTER(_CConfig), vp, C.c_size_t, vp, vp, vp,
                                 C.POINTER(vp), C.POINTER(vp), vp]
+    lib.pdadmm_grow_layers.argtypes = [C.POINTER(vp), C.POINTER(_CConfig), vp, C.c_size_t, vp, vp, vp, vp, vp,
+                                       C.POINTER(vp), C.POINTER(vp), vp]
     lib.pdadmm_set_var.argtypes = [vp, i32, i32, vp]
     lib.pdadmm_get_var.argtypes = [vp, i32, i32, vp]
     lib.pdadmm_iterate.argtypes = [vp, i32]
@@ -252,6 +254,17 @@ def pdadmm_workspace_bytes(cfg: Config) -> int:
 def pdadmm_init(cfg: Config, X_aug, labels, W0, b0, train_mask=None, stream=None, workspace=None) -> Context:
     """Create a context. All tensors live on the GPU; the workspace tensor is allocated here with
     torch (device memory plumbing) unless one is passed in."""
+    return _new_context(cfg, X_aug, labels, W0, b0, train_mask, stream, workspace, None, None)
+
+
+def pdadmm_grow_layers(source: Context, from_layer, cfg: Config, X_aug, labels, W0, b0, train_mask=None, stream=None,
+                       workspace=None) -> Context:
+    """Deeper model from a trained one: layer l takes W, b from layer from_layer[l-1] of `source` where
+    that entry is positive, else from W0[l-1], b0[l-1] (device tensors; None allowed for carried layers)."""
+    return _new_context(cfg, X_aug, labels, W0, b0, train_mask, stream, workspace, source, from_layer)
+
+
+def _new_context(cfg, X_aug, labels, W0, b0, train_mask, stream, workspace, source, from_layer) -> Context:
     import torch
     lib = load_library()
     cc = cfg.to_c()
@@ -267,12 +280,21 @@ def pdadmm_init(cfg: Config, X_aug, labels, W0, b0, train_mask=None, stream=None
     Wp = (C.c_void_p * L)(*[_ptr(w) for w in W0])
     bp = (C.c_void_p * L)(*[_ptr(b) for b in b0])
     handle = C.c_void_p()
-    code = lib.pdadmm_init(C.byref(handle), C.byref(cc), aligned, avail, _ptr(X_aug), _ptr(labels),
-                           _ptr(train_mask), Wp, bp, _stream_ptr(stream))
+    if source is None:
+        what = "pdadmm_init"
+        code = lib.pdadmm_init(C.byref(handle), C.byref(cc), aligned, avail, _ptr(X_aug), _ptr(labels),
+                               _ptr(train_mask), Wp, bp, _stream_ptr(stream))
+    else:
+        what = "pdadmm_grow_layers"
+        fl = np.ascontiguousarray(from_layer, dtype=np.int32)
+        if fl.shape != (L,):
+            raise ValueError("from_layer needs one entry per layer of the new model")
+        code = lib.pdadmm_grow_layers(C.byref(handle), C.byref(cc), aligned, avail, _ptr(X_aug), _ptr(labels),
+                                      _ptr(train_mask), source.handle, fl.ctypes.data, Wp, bp, _stream_ptr(stream))
     ctx = Context(handle, cfg, workspace, stream)
     if code != 0:
         detail = ctx.last_error() if handle else ""
-        raise PdadmmError(code, "pdadmm_init", detail)
+        raise PdadmmError(code, what, detail)
     return ctx
 
 
@@ -371,7 +393,7 @@ def pdadmm_plan_info(ctx: Context) -> dict:
     ws = np.zeros(ctx.L, dtype=np.int32)
     _check(load_library().pdadmm_plan_info(ctx.handle, C.addressof(fused), ws.ctypes.data, C.addressof(wts)),
            "pdadmm_plan_info", ctx)
-    return dict(fused_updates=bool(fused.value), wgrad_split=ws, wtrial_split=int(wts.value))
+    return dict(fused_updates=int(fused.value), wgrad_split=ws, wtrial_split=int(wts.value))
 
 
 def pdadmm_predict(ctx: Context, mask=None, want_logits: bool = False) -> dict:

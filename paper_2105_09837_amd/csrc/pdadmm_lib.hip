@@ -123,8 +123,9 @@ struct pdadmm_ctx {
   Group<GemmProb> g_pgrad, g_ptrial, g_wgrad, g_wtrial, g_resid, g_resid_obj;
   std::vector<GemmProb> fwd;          // forward pass of the starting point: one by-value launch per layer
   Group<ReduceProb> g_red, g_tred;
-  bool spec = false;          // pdADMM-G, not small: residual updates ride in the product epilogues (speculative
-                              // on the previous step size), column sums come from the G p product
+  bool spec_p = false;        // pdADMM-G, not small: the p-step and r -= Wg/tau ride in the product epilogues with
+                              // the step size of the previous iteration, corrected only when the rule picks another
+  bool spec_w = false;        // not small (both variants): the same for r -= Gp/theta and the column sums of r
   bool small_wtrial = false;  // the G p launch has too few tiles to fill the chip: split its contraction
   Group<AxpySeg> g_pstep, g_pfix, g_qapply_r;
   SelectDesc *sel_p = nullptr, *sel_w = nullptr, *sel_q = nullptr;
@@ -289,7 +290,8 @@ size_t plan(pdadmm_ctx* c, void* base) {
   size_t wt_tiles = 0;
   for (int i = 0; i < L; ++i) wt_tiles += (size_t)cdiv(N, BM) * cdiv(c->dims[i + 1], BN);
   c->small_wtrial = wt_tiles * 2 <= (size_t)kGemmSlots;
-  c->spec = !Q && !c->small_wtrial;
+  c->spec_w = !c->small_wtrial;
+  c->spec_p = !Q && c->spec_w;
   for (int i = 0; i < L; ++i) {
     LayerBufs& b = c->lay[i];
     b.n_in = c->dims[i];
@@ -300,7 +302,7 @@ size_t plan(pdadmm_ctx* c, void* base) {
     b.k_chunk = chunk;
     b.tiles_in = cdiv(N, BM) * cdiv(b.n_in, BN);
     b.tiles_out = cdiv(N, BM) * cdiv(b.n_out, BN);
-    b.rpb = c->spec ? BM : kRowsPerBlock;     // with spec the column sums come per 128-row product tile
+    b.rpb = c->spec_w ? BM : kRowsPerBlock;   // fused: column sums come per 128-row product tile
     b.row_blocks = cdiv(N, b.rpb);
     b.cw = 1;
     while (b.cw < b.ld_out / 4 && b.cw < 256) b.cw <<= 1;
@@ -431,12 +433,12 @@ pdadmm_status build_tables(pdadmm_ctx* c) {
       GemmProb P = make_nt(b.R, b.ld_out, b.Wt, b.ld_out, b.g, b.ld_in, N, b.n_in, b.n_out);
       P.e0 = c->lay[i - 1].u; P.e1 = b.p; P.e2 = c->lay[i - 1].q;
       P.alpha = nu; P.beta = rho; P.part = b.part_a; P.layer = i;
-      if (c->spec) P.o1 = b.p;                 // p -= g / tau_prev in the epilogue
+      if (c->spec_p) P.o1 = b.p;                 // p -= g / tau_prev in the epilogue
       pgrad.push_back(P);
       // image of the step direction under W_l: T = dir W^T (dir = g, or d in -Q)
       GemmProb T = make_nt(Q ? b.d : b.g, b.ld_in, b.W, b.ld_in, b.T, b.ld_out, N, b.n_out, b.n_in);
       T.part = b.part_b; T.layer = i;
-      if (c->spec) T.o1 = b.R;                 // r -= T / tau_prev in the epilogue
+      if (c->spec_p) T.o1 = b.R;                 // r -= T / tau_prev in the epilogue
       ptrial.push_back(T);
       SelectDesc s{};
       s.part_g = b.part_a; s.ng = P.nblk; s.part_t = b.part_b; s.nt = T.nblk; s.stride_t = 1; s.layer = i;
@@ -447,7 +449,7 @@ pdadmm_status build_tables(pdadmm_ctx* c) {
       AxpySeg r{};
       r.y = b.R; r.x = b.T; r.n4 = (size_t)N * b.ld_out / 4; r.nblk = chunk_blocks(r.n4, 1); r.layer = i;
       r.which = kScaleInvTau;
-      if (c->spec) {                           // only the correction tau_new vs tau_prev is left for p and r
+      if (c->spec_p) {                         // only the correction tau_new vs tau_prev is left for p and r
         a.which = r.which = kScaleFixTau;
         a.nblk = std::min(1024, chunk_blocks(a.n4, 1));
         r.nblk = std::min(1024, chunk_blocks(r.n4, 1));
@@ -484,7 +486,7 @@ pdadmm_status build_tables(pdadmm_ctx* c) {
     GemmProb Wt_ = make_nt(b.p, b.ld_in, b.G, b.ld_in, b.T, b.ld_out, N, b.n_out, b.n_in);
     Wt_.part = b.part_b; Wt_.layer = i;
     int t_partials = Wt_.nblk;
-    if (c->spec) {                             // r -= T / theta_prev and the column sums of r in the epilogue
+    if (c->spec_w) {                           // r -= T / theta_prev and the column sums of r in the epilogue
       Wt_.o1 = b.R;
       Wt_.colpart = b.colpart;
     }
@@ -531,7 +533,7 @@ pdadmm_status build_tables(pdadmm_ctx* c) {
     rs.m = b.m; rs.colpart = b.colpart;
     rs.rows = N; rs.ncols = b.n_out; rs.ld = b.ld_out;
     rs.cw = b.cw; rs.col_blocks = b.col_blocks; rs.row_blocks = b.row_blocks; rs.nblk = b.col_blocks * b.row_blocks;
-    rs.rpb = b.rpb; rs.which = c->spec ? kScaleFixTheta : kScaleInvTheta;
+    rs.rpb = b.rpb; rs.which = c->spec_w ? kScaleFixTheta : kScaleInvTheta;
     rs.layer = i;
     rows.push_back(rs);
     BiasSeg bs{};
@@ -614,18 +616,18 @@ pdadmm_status phase_p(pdadmm_ctx* c) {
   const int L = c->L;
   if (L < 2) return PDADMM_OK;
   const pdadmm_config& g = c->cfg;
-  if (c->spec) { TIMED(c, kClsGemmPGrad); launch_gemm<true, EpiPGradUpd, true>(c, c->g_pgrad, 0); }
+  if (c->spec_p) { TIMED(c, kClsGemmPGrad); launch_gemm<true, EpiPGradUpd, true>(c, c->g_pgrad, 0); }
   else { TIMED(c, kClsGemmPGrad); launch_gemm<true, EpiPGrad, true>(c, c->g_pgrad, 0); }
   LAUNCH_CHECK(c, "gemm pgrad");
   if (!g.quantize) {
-    if (c->spec) { TIMED(c, kClsGemmTrial); launch_gemm<true, EpiTrialP, true>(c, c->g_ptrial, 0); }
+    if (c->spec_p) { TIMED(c, kClsGemmTrial); launch_gemm<true, EpiTrialP, true>(c, c->g_ptrial, 0); }
     else { TIMED(c, kClsGemmTrial); launch_gemm<true, EpiStoreNorm, true>(c, c->g_ptrial, 0); }
     LAUNCH_CHECK(c, "gemm ptrial");
     for (int i = 1; i < L; ++i) ++c->p_products[i];
     { TIMED(c, kClsSelect); hipLaunchKernelGGL(select_step_kernel, dim3(L - 1), dim3(256), 0, c->stream, c->sel_p, c->scal, 0, g.rho, g.nu,
                        g.bt_eta, g.bt_max_trials, c->err); }
     LAUNCH_CHECK(c, "select tau");
-    if (!c->spec) {
+    if (!c->spec_p) {
       { TIMED(c, kClsPStep); launch_group(c, c->g_pstep, axpy_kernel, (const LayerScal*)c->scal); }
       LAUNCH_CHECK(c, "p step");
     } else {
@@ -676,7 +678,7 @@ pdadmm_status phase_w(pdadmm_ctx* c) {
     LAUNCH_CHECK(c, "gemm wtrial (chunks)");
     { TIMED(c, kClsSplitkReduce); launch_group(c, c->g_tred, splitk_reduce_kernel); }
     LAUNCH_CHECK(c, "wtrial chunk sum");
-  } else if (c->spec) {
+  } else if (c->spec_w) {
     { TIMED(c, kClsGemmTrial); launch_gemm<true, EpiTrialW, true>(c, c->g_wtrial, 0); }
     LAUNCH_CHECK(c, "gemm wtrial");
   } else {
@@ -923,17 +925,36 @@ size_t pdadmm_workspace_bytes(const pdadmm_config* cfg) {
   return plan(&tmp, nullptr);
 }
 
-pdadmm_status pdadmm_init(pdadmm_ctx** out, const pdadmm_config* cfg, void* workspace, size_t workspace_bytes,
+}  // extern "C"
+
+namespace {
+
+// Common part of pdadmm_init and pdadmm_grow_layers. Layer i takes W, b from layer from_layer[i] (1-based)
+// of the context `from` where that entry is positive, else from the dense caller arrays W0[i], b0[i].
+pdadmm_status init_common(pdadmm_ctx** out, const pdadmm_config* cfg, void* workspace, size_t workspace_bytes,
                           const float* X_aug, const int32_t* labels, const uint8_t* train_mask,
-                          const float* const* W0, const float* const* b0, void* stream) {
+                          const float* const* W0, const float* const* b0, void* stream, pdadmm_ctx* from,
+                          const int32_t* from_layer) {
   if (!out) return PDADMM_EINVAL;
   *out = nullptr;
   std::string why;
   if (!config_ok(cfg, &why)) return PDADMM_EINVAL;
-  if (!workspace || !X_aug || !labels || !W0 || !b0) return PDADMM_EINVAL;
+  if (!workspace || !X_aug || !labels) return PDADMM_EINVAL;
   if (reinterpret_cast<uintptr_t>(workspace) & 255) return PDADMM_EINVAL;
-  for (int i = 0; i < cfg->n_layers; ++i)
-    if (!W0[i] || !b0[i]) return PDADMM_EINVAL;
+  if (from && !from_layer) return PDADMM_EINVAL;
+  for (int i = 0; i < cfg->n_layers; ++i) {
+    const int src = from ? from_layer[i] : 0;
+    if (src == 0) {
+      if (!W0 || !b0 || !W0[i] || !b0[i]) return PDADMM_EINVAL;
+    } else {
+      if (src < 0 || src > from->L) return PDADMM_EINVAL;
+      if (from->dims[src - 1] != cfg->dims[i] || from->dims[src] != cfg->dims[i + 1]) return PDADMM_EINVAL;
+    }
+  }
+  if (from) {   // its pending work writes the arrays copied below
+    if (from->N != cfg->n_nodes) return PDADMM_EINVAL;
+    if (hipStreamSynchronize(from->stream) != hipSuccess) return PDADMM_EHIP;
+  }
   pdadmm_ctx* c = new pdadmm_ctx;
   c->cfg = *cfg;
   c->N = cfg->n_nodes;
@@ -964,9 +985,13 @@ pdadmm_status pdadmm_init(pdadmm_ctx** out, const pdadmm_config* cfg, void* work
   std::vector<LayerScal> hs(L);
   for (int i = 0; i < L; ++i) {
     const LayerBufs& b = c->lay[i];
-    HIP_TRY(c, hipMemcpy2DAsync(b.W, (size_t)b.ld_in * 4, W0[i], (size_t)b.n_in * 4, (size_t)b.n_in * 4, b.n_out,
+    const int src = from ? from_layer[i] : 0;
+    const float* Wsrc = src ? from->lay[src - 1].W : W0[i];
+    const float* bsrc = src ? from->lay[src - 1].b : b0[i];
+    const size_t pitch = src ? (size_t)from->lay[src - 1].ld_in * 4 : (size_t)b.n_in * 4;
+    HIP_TRY(c, hipMemcpy2DAsync(b.W, (size_t)b.ld_in * 4, Wsrc, pitch, (size_t)b.n_in * 4, b.n_out,
                                 hipMemcpyDeviceToDevice, c->stream));
-    HIP_TRY(c, hipMemcpyAsync(b.b, b0[i], sizeof(float) * b.n_out, hipMemcpyDeviceToDevice, c->stream));
+    HIP_TRY(c, hipMemcpyAsync(b.b, bsrc, sizeof(float) * b.n_out, hipMemcpyDeviceToDevice, c->stream));
     std::memset(&hs[i], 0, sizeof(LayerScal));
     hs[i].tau = cfg->tau0;
     hs[i].theta = cfg->theta0;
@@ -999,6 +1024,25 @@ pdadmm_status pdadmm_init(pdadmm_ctx** out, const pdadmm_config* cfg, void* work
     HIP_TRY(c, hipEventCreateWithFlags(&c->ev_out, hipEventDisableTiming));
   }
   return PDADMM_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+pdadmm_status pdadmm_init(pdadmm_ctx** out, const pdadmm_config* cfg, void* workspace, size_t workspace_bytes,
+                          const float* X_aug, const int32_t* labels, const uint8_t* train_mask,
+                          const float* const* W0, const float* const* b0, void* stream) {
+  if (!W0 || !b0) return PDADMM_EINVAL;
+  return init_common(out, cfg, workspace, workspace_bytes, X_aug, labels, train_mask, W0, b0, stream, nullptr, nullptr);
+}
+
+pdadmm_status pdadmm_grow_layers(pdadmm_ctx** out, const pdadmm_config* cfg, void* workspace, size_t workspace_bytes,
+                                 const float* X_aug, const int32_t* labels, const uint8_t* train_mask,
+                                 pdadmm_ctx* from, const int32_t* from_layer, const float* const* W0,
+                                 const float* const* b0, void* stream) {
+  if (!from || !from_layer) return PDADMM_EINVAL;
+  return init_common(out, cfg, workspace, workspace_bytes, X_aug, labels, train_mask, W0, b0, stream, from, from_layer);
 }
 
 pdadmm_status pdadmm_set_var(pdadmm_ctx* c, int32_t kind, int32_t layer, const void* src) {
@@ -1261,7 +1305,7 @@ pdadmm_status pdadmm_stats(pdadmm_ctx* c, double* tau, double* theta, int32_t* p
 
 pdadmm_status pdadmm_plan_info(pdadmm_ctx* c, int32_t* fused_updates, int32_t* wgrad_split, int32_t* wtrial_split) {
   if (!c) return PDADMM_EINVAL;
-  if (fused_updates) *fused_updates = c->spec ? 1 : 0;
+  if (fused_updates) *fused_updates = (c->spec_p ? 1 : 0) | (c->spec_w ? 2 : 0);
   if (wgrad_split)
     for (int i = 0; i < c->L; ++i) wgrad_split[i] = c->lay[i].splitk;
   if (wtrial_split) {

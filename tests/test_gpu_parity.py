@@ -158,6 +158,8 @@ CASES = {
     # large enough (> 384 output tiles per launch) for the path that folds the residual updates and the
     # column sums into the product epilogues, with step sizes that still change in the first iterations
     "mid": lambda: scaled_workload("C2", 3300, hidden=260, n_layers=8, feat_dim=10),
+    # -Q at the same size: r -= Gp/theta and the column sums ride in the product epilogue there too
+    "mid-Q": lambda: scaled_workload("C5", 3300, hidden=260, n_layers=6, feat_dim=10),
     "paper-grid": lambda: dataclasses.replace(scaled_workload("C5", 800, hidden=60, n_layers=4, feat_dim=10),
                                               quant=(-1.0, 20.0, 22)),      # Delta = {-1, 0, 1, ..., 20} (Section 5.1)
     "ragged": lambda: dataclasses.replace(scaled_workload("C2", 1037, hidden=131, n_layers=3, feat_dim=7), n_classes=11),
@@ -308,7 +310,7 @@ def test_trajectories(env, case, iters):
     assert s["r_drift"] < 1e-4
 
 
-@pytest.mark.parametrize("case", ["C5-small", "C5pq-small", "paper-grid"])
+@pytest.mark.parametrize("case", ["C5-small", "C5pq-small", "paper-grid", "mid-Q"])
 def test_quantized_trajectory_step_by_step_along_the_oracle_run(env, case):
     """pdADMM-G-Q over 20 iterations, one step at a time: the oracle runs its own trajectory (its state
     rounded to fp32 after every iteration); before each iteration that state is copied to the GPU, both
@@ -496,10 +498,11 @@ def test_training_learns_planted_labels_then_grows_greedily(env):
     # greedy growth: 3 -> 5 layers
     deep = dataclasses.replace(w, n_layers=5, name="deep")
     Wn, bn = make_weights(deep)
-    Wt = [P.pdadmm_get_var(ctx, P.VAR.W, l) for l in (1, 2, 3)]
-    bt = [P.pdadmm_get_var(ctx, P.VAR.B, l) for l in (1, 2, 3)]
-    inp2 = dict(inp, W=[Wt[0], Wt[1], Wn[2], Wn[3], Wt[2]], b=[bt[0], bt[1], bn[2], bn[3], bt[2]])
-    ctx2 = H.gpu_context(deep, inp2)
+    dev = torch.device("cuda:0")
+    fresh = lambda arrs: [torch.from_numpy(np.ascontiguousarray(a, dtype=F32)).to(dev) if i in (2, 3) else None
+                          for i, a in enumerate(arrs)]
+    ctx2 = P.pdadmm_grow_layers(ctx, [1, 2, 0, 0, 3], H.config_of(deep), torch.from_numpy(inp["X_aug"]).to(dev),
+                                torch.from_numpy(inp["y"]).to(dev), fresh(Wn), fresh(bn))
     obj = [P.pdadmm_objective(ctx2)["F"]]
     for _ in range(3):
         P.pdadmm_iterate(ctx2, 10)
@@ -507,6 +510,68 @@ def test_training_learns_planted_labels_then_grows_greedily(env):
     acc2 = P.pdadmm_predict(ctx2)["accuracy"]
     _say(f"  grown to 5 layers: F {obj[0]:.4f} -> {obj[-1]:.4f}, accuracy {acc2:.3f}")
     assert obj[-1] < obj[0] and acc2 > chance + 0.2
+
+
+@pytest.mark.parametrize("quant", [False, True])
+def test_grow_layers_matches_the_oracle(env, quant):
+    """Greedy layer-wise schedule through the library's own entry point: a 3-layer model trained by the
+    oracle (its weights copied to the GPU) grows to 5 layers, the two hidden layers and the output layer
+    carried over, two fresh layers in between. The grown start and three iterations from it must match
+    the oracle's grow_layers element by element; the source context stays usable and unchanged."""
+    torch, P, H = env
+    from workloads import make_weights
+    base = scaled_workload("C5" if quant else "C2", 700, hidden=40, n_layers=3, feat_dim=9)
+    inp = oracle_inputs(base)
+    st = oracle_state(base, inp)
+    O.iterate(st, 4)
+    st = H.round_state_to_fp32(st)
+    src = H.gpu_context(base, inp, st)
+    deep = dataclasses.replace(base, n_layers=5, name="deep")
+    Wn, bn = make_weights(deep)
+    from_layer = [1, 2, 0, 0, 3]
+    ref = O.grow_layers(st, from_layer, Wn, bn)
+    dev = torch.device("cuda:0")
+    W0 = [None if f else torch.from_numpy(np.ascontiguousarray(a, dtype=F32)).to(dev) for f, a in zip(from_layer, Wn)]
+    b0 = [None if f else torch.from_numpy(np.ascontiguousarray(a, dtype=F32)).to(dev) for f, a in zip(from_layer, bn)]
+    Xa, y = torch.from_numpy(inp["X_aug"]).to(dev), torch.from_numpy(inp["y"]).to(dev)
+    ctx = P.pdadmm_grow_layers(src, from_layer, H.config_of(deep), Xa, y, W0, b0)
+    for i, f in enumerate(from_layer):
+        want = (st.W[f - 1] if f else Wn[i]).astype(F32)
+        assert np.array_equal(P.pdadmm_get_var(ctx, P.VAR.W, i + 1), want), f"W{i + 1}"
+        assert np.array_equal(P.pdadmm_get_var(ctx, P.VAR.B, i + 1), (st.b[f - 1] if f else bn[i]).astype(F32))
+    tol = 1e-4
+    _, worst, rep = H.compare_state(ctx, ref, tol, "grown start")
+    _say(f"  grown start: worst rel-L2 {worst:.2e}")
+    assert worst <= (2e-2 if quant else 1e-5), rep     # -Q: isolated one-level index flips
+    tau, theta, _, _ = H.step_sizes(ctx)
+    assert all(t == 1.0 for t in tau[1:]) and all(t == 1.0 for t in theta)
+    if not quant:
+        # a forward-consistent start has vanishing residuals and duals (nothing to compare after one
+        # iteration but rounding noise): move off it as the other parity cases do, on both sides
+        from workloads import perturb_state
+        z, q, p, u = perturb_state(deep, [a.astype(F32) for a in ref.z], [a.astype(F32) for a in ref.q])
+        for i in range(ref.L):
+            ref.z[i] = z[i].astype(F64)
+            if i < ref.L - 1:
+                ref.q[i], ref.p[i + 1], ref.u[i] = q[i].astype(F64), p[i].astype(F64), u[i].astype(F64)
+        H.push_state(ctx, H.round_state_to_fp32(ref))
+        before = ref.copy()
+        O.iterate(ref, 1)
+        P.pdadmm_iterate(ctx, 1)
+        _, worst, rep = H.compare_state(ctx, ref, tol, "grown +1", before=before)
+        _say(f"  one iteration from the grown start: worst rel-L2 {worst:.2e}")
+        assert worst <= tol, rep
+    # the source context is untouched and still iterates
+    assert np.array_equal(P.pdadmm_get_var(src, P.VAR.W, 2), st.W[1].astype(F32))
+    P.pdadmm_iterate(src, 1)
+    P.pdadmm_sync(src)
+    # shape mismatch and bad indices are refused
+    for bad in ([2, 1, 0, 0, 3], [1, 2, 0, 0, 4], [1, 2, 0, 0, -1]):
+        with pytest.raises(P.PdadmmError):
+            P.pdadmm_grow_layers(src, bad, H.config_of(deep), Xa, y, [w if w is not None else Xa for w in W0],
+                                 [b if b is not None else Xa for b in b0])
+    with pytest.raises(P.PdadmmError):      # a fresh layer without weights
+        P.pdadmm_grow_layers(src, [1, 2, 0, 0, 0], H.config_of(deep), Xa, y, W0, b0)
 
 
 @pytest.mark.parametrize("case", ["C1-full", "C4-small", "mid"])

@@ -481,6 +481,38 @@ def test_forward_pass_ignores_the_admm_variables():
     np.testing.assert_allclose(O.forward(a), a.z[-1], rtol=1e-6, atol=1e-6)
 
 
+def test_growing_by_identity_layers_keeps_the_function():
+    # Greedy layer-wise schedule (Section 3.2): a fresh hidden layer W = I, b = 0 placed after a ReLU layer
+    # computes relu(relu(x)) = relu(x), so the grown model must reproduce the trained one's output exactly,
+    # and its start must be forward-consistent (zero residuals, zero duals).
+    w = small(n=150, hidden=12, n_layers=3, feat_dim=5)
+    inp = oracle_inputs(w)
+    st = O.init_forward(inp["X_aug"], inp["W"], inp["b"], inp["y"], w.rho, w.nu)
+    O.iterate(st, 5)
+    h = w.hidden
+    eye, zero = np.eye(h), np.zeros(h)
+    deep = O.grow_layers(st, [1, 2, 0, 0, 3], [None, None, eye, eye, None], [None, None, zero, zero, None])
+    assert deep.L == 5
+    np.testing.assert_allclose(O.forward(deep), O.forward(st), rtol=0, atol=1e-12)
+    assert np.array_equal(O.predict(deep)[0], O.predict(st)[0])
+    for i, src in enumerate([1, 2, 0, 0, 3]):
+        if src:
+            assert np.array_equal(deep.W[i], st.W[src - 1]) and deep.W[i] is not st.W[src - 1]
+            assert np.array_equal(deep.b[i], st.b[src - 1])
+    for i in range(deep.L):
+        assert np.max(np.abs(deep.p[i] @ deep.W[i].T + deep.b[i] - deep.z[i])) < 1e-12
+        if i < deep.L - 1:
+            assert not deep.u[i].any() and np.array_equal(deep.p[i + 1], deep.q[i])
+    assert deep.tau == [1.0] * 5 and deep.theta == [1.0] * 5
+    # training the grown model goes on decreasing the objective from that start
+    f0 = O.objective(deep)["L_rho"]
+    O.iterate(deep, 3)
+    assert O.objective(deep)["L_rho"] < f0
+    # a source layer of another shape is refused
+    with pytest.raises(ValueError):
+        O.grow_layers(st, [2, 1, 3], [None] * 3, [None] * 3)
+
+
 def test_variant_with_p_and_q_on_the_grid():
     # Appendix B, last paragraph: q_l <- nearest member of Delta to the closed-form q.
     w = dataclasses.replace(small("C5", n=200, hidden=16, n_layers=4, feat_dim=6), quant_q=True)
