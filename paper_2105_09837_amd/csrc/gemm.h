@@ -564,21 +564,49 @@ struct ReduceProb {
   int M, N, ld, splitk;
   int blk0, nblk;
   float alpha;
+  int vec;             // ld % 4 == 0 and part, G 16-byte aligned
 };
 
+// The partial sums of one element are added in the order of the chunks (fixed by the split, not by the
+// launch); the loads of up to 8 chunks are issued together before their ordered additions.
 __device__ __forceinline__ void splitk_reduce_body(const ReduceProb& P, const int local) {
   __shared__ double red[4];
   const size_t plane = (size_t)P.M * P.ld;
   double s = 0.0;
-  for (size_t i = (size_t)local * 256 + threadIdx.x; i < plane; i += (size_t)P.nblk * 256) {
-    const int col = (int)(i % P.ld);
-    float sum = 0.0f;
-    if (col < P.N) {
-      for (int k = 0; k < P.splitk; ++k) sum += P.part[(size_t)k * plane + i];
-      sum *= P.alpha;
+  if (P.vec) {   // ld % 4 == 0, 16-byte aligned bases: one float4 group per thread and step
+    const size_t groups = plane / 4;
+    for (size_t i = (size_t)local * 256 + threadIdx.x; i < groups; i += (size_t)P.nblk * 256) {
+      const int col = (int)((i * 4) % P.ld);
+      const float* src = P.part + i * 4;
+      f32x4 sum = {0.f, 0.f, 0.f, 0.f};
+      int k = 0;
+      for (; k + 8 <= P.splitk; k += 8) {
+        f32x4 v[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) v[j] = stream_load(reinterpret_cast<const f32x4*>(src + (size_t)(k + j) * plane));
+#pragma unroll
+        for (int j = 0; j < 8; ++j) sum += v[j];
+      }
+      for (; k < P.splitk; ++k) sum += stream_load(reinterpret_cast<const f32x4*>(src + (size_t)k * plane));
+      sum.x = col + 0 < P.N ? sum.x * P.alpha : 0.f;
+      sum.y = col + 1 < P.N ? sum.y * P.alpha : 0.f;
+      sum.z = col + 2 < P.N ? sum.z * P.alpha : 0.f;
+      sum.w = col + 3 < P.N ? sum.w * P.alpha : 0.f;
+      *reinterpret_cast<f32x4*>(P.G + i * 4) = sum;
+      s += (double)sum.x * (double)sum.x + (double)sum.y * (double)sum.y + (double)sum.z * (double)sum.z +
+           (double)sum.w * (double)sum.w;
     }
-    P.G[i] = sum;
-    s += (double)sum * (double)sum;
+  } else {
+    for (size_t i = (size_t)local * 256 + threadIdx.x; i < plane; i += (size_t)P.nblk * 256) {
+      const int col = (int)(i % P.ld);
+      float sum = 0.0f;
+      if (col < P.N) {
+        for (int k = 0; k < P.splitk; ++k) sum += P.part[(size_t)k * plane + i];
+        sum *= P.alpha;
+      }
+      P.G[i] = sum;
+      s += (double)sum * (double)sum;
+    }
   }
   const double t = block_sum_256(s, red);
   if (threadIdx.x == 0 && P.norm_part) P.norm_part[local] = t;
