@@ -437,6 +437,10 @@ struct QuantSeg {
   int layer;
 };
 
+// A block owns kQuantUnroll * 256 consecutive float4 groups (one contiguous chunk per array); all loads of a
+// thread are issued before the first projection.
+constexpr int kQuantUnroll = 4;
+
 __global__ __launch_bounds__(256) void quant_trial_kernel(const QuantSeg* __restrict__ segs, const BlockMap map,
                                                           const LayerScal* __restrict__ scal, QuantGrid grid) {
   __shared__ double red[4];
@@ -445,21 +449,31 @@ __global__ __launch_bounds__(256) void quant_trial_kernel(const QuantSeg* __rest
   const QuantSeg S = segs[si];
   if (!scal[S.layer].active) return;
   const float t = scal[S.layer].trial_t;
-  const size_t stride = (size_t)S.nblk * 256;
+  const size_t base = (size_t)local * (256 * kQuantUnroll) + threadIdx.x;
+  f32x4 pv[kQuantUnroll], gv[kQuantUnroll];
+#pragma unroll
+  for (int j = 0; j < kQuantUnroll; ++j) {
+    const size_t i = base + (size_t)j * 256;
+    if (i < S.n4) {
+      pv[j] = stream_load(reinterpret_cast<const f32x4*>(S.p) + i);
+      gv[j] = stream_load(reinterpret_cast<const f32x4*>(S.g) + i);
+    }
+  }
   double ds = 0.0;
-  for (size_t i = (size_t)local * 256 + threadIdx.x; i < S.n4; i += stride) {
-    const float4 pv = reinterpret_cast<const float4*>(S.p)[i];
-    const float4 gv = reinterpret_cast<const float4*>(S.g)[i];
+#pragma unroll
+  for (int j = 0; j < kQuantUnroll; ++j) {
+    const size_t i = base + (size_t)j * 256;
+    if (i >= S.n4) continue;
     const int col0 = (int)((i * 4) % (size_t)S.ld);
-    float4 dv;
+    f32x4 dv;
     uchar4 iv;
 #define PDADMM_QT(c, k)                                                       \
   {                                                                           \
     if (col0 + k < S.ncols) {                                                 \
-      const float v = sub_rn(pv.c, div_rn(gv.c, t));                          \
+      const float v = sub_rn(pv[j].c, div_rn(gv[j].c, t));                    \
       const int id = quant_index(v, grid);                                    \
       iv.c = (unsigned char)id;                                               \
-      dv.c = sub_rn(quant_value(id, grid), pv.c);                             \
+      dv.c = sub_rn(quant_value(id, grid), pv[j].c);                          \
       ds += (double)dv.c * (double)dv.c;                                      \
     } else {                                                                  \
       iv.c = 0;                                                               \
@@ -468,7 +482,7 @@ __global__ __launch_bounds__(256) void quant_trial_kernel(const QuantSeg* __rest
   }
     PDADMM_QT(x, 0) PDADMM_QT(y, 1) PDADMM_QT(z, 2) PDADMM_QT(w, 3)
 #undef PDADMM_QT
-    reinterpret_cast<float4*>(S.d)[i] = dv;
+    reinterpret_cast<f32x4*>(S.d)[i] = dv;       // re-read by the product W d that follows
     reinterpret_cast<uchar4*>(S.idx)[i] = iv;
   }
   const double tot = block_sum_256(ds, red);
@@ -545,16 +559,24 @@ __global__ __launch_bounds__(256) void quant_apply_kernel(const QuantSeg* __rest
   const int si = find_group(map, blockIdx.x, &local);
   const QuantSeg S = segs[si];
   if (scal[S.layer].inv_tau == 0.0f) return;
-  const size_t stride = (size_t)S.nblk * 256;
-  for (size_t i = (size_t)local * 256 + threadIdx.x; i < S.n4; i += stride) {
-    const uchar4 iv = reinterpret_cast<const uchar4*>(S.idx)[i];
+  const size_t base = (size_t)local * (256 * kQuantUnroll) + threadIdx.x;
+  uchar4 iv[kQuantUnroll];
+#pragma unroll
+  for (int j = 0; j < kQuantUnroll; ++j) {
+    const size_t i = base + (size_t)j * 256;
+    if (i < S.n4) iv[j] = reinterpret_cast<const uchar4*>(S.idx)[i];
+  }
+#pragma unroll
+  for (int j = 0; j < kQuantUnroll; ++j) {
+    const size_t i = base + (size_t)j * 256;
+    if (i >= S.n4) continue;
     const int col0 = (int)((i * 4) % (size_t)S.ld);
-    float4 pv;
-    pv.x = col0 + 0 < S.ncols ? quant_value(iv.x, grid) : 0.0f;
-    pv.y = col0 + 1 < S.ncols ? quant_value(iv.y, grid) : 0.0f;
-    pv.z = col0 + 2 < S.ncols ? quant_value(iv.z, grid) : 0.0f;
-    pv.w = col0 + 3 < S.ncols ? quant_value(iv.w, grid) : 0.0f;
-    reinterpret_cast<float4*>(S.p)[i] = pv;
+    f32x4 pv;
+    pv.x = col0 + 0 < S.ncols ? quant_value(iv[j].x, grid) : 0.0f;
+    pv.y = col0 + 1 < S.ncols ? quant_value(iv[j].y, grid) : 0.0f;
+    pv.z = col0 + 2 < S.ncols ? quant_value(iv[j].z, grid) : 0.0f;
+    pv.w = col0 + 3 < S.ncols ? quant_value(iv[j].w, grid) : 0.0f;
+    reinterpret_cast<f32x4*>(S.p)[i] = pv;
   }
 }
 

@@ -341,7 +341,8 @@ size_t plan(pdadmm_ctx* c, void* base) {
     const size_t np = 2 * (size_t)std::max({b.tiles_in, b.tiles_out, 2048});
     b.part_a = cv.take<double>(np);
     b.part_b = cv.take<double>(np);
-    b.part_c = cv.take<double>(np);
+    // -Q: one partial of ||d||^2 per block of the projection kernel
+    b.part_c = cv.take<double>(Q && i >= 1 ? std::max(np, (size_t)chunk_blocks(in_sz / 4, kQuantUnroll)) : np);
     b.colpart = cv.take<double>((size_t)b.row_blocks * b.ld_out);
     b.pairpart = cv.take<double>(3 * 2048);
   }
@@ -463,7 +464,7 @@ pdadmm_status build_tables(pdadmm_ctx* c) {
         QuantSeg qs{};
         qs.p = b.p; qs.g = b.g; qs.d = b.d; qs.idx = b.pidx; qs.dpart = b.part_c;
         qs.n4 = (size_t)N * b.ld_in / 4; qs.ncols = b.n_in; qs.ld = b.ld_in;
-        qs.nblk = flat_blocks(qs.n4); qs.layer = i;
+        qs.nblk = chunk_blocks(qs.n4, kQuantUnroll); qs.layer = i;
         quant.push_back(qs);
         SelectDesc sq{};
         sq.part_g = b.part_c; sq.ng = qs.nblk; sq.part_t = b.part_b; sq.nt = T.nblk; sq.stride_t = 1; sq.layer = i;
