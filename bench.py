@@ -24,7 +24,7 @@ HBM_PEAK_GBS = 8000.0
 
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc runs (FETCH_SIZE / WRITE_SIZE scaled
 # by a copy kernel of known size); see profiles/. None until measured for a workload.
-MEASURED_TRAFFIC_BYTES = {"C2": 1.75e9, "C3": 4.11e10}   # FETCH_SIZE + WRITE_SIZE per launch, profiles/<workload>_iteration_kernels.md
+MEASURED_TRAFFIC_BYTES = {"C2": 1.74e9, "C3": 4.17e10}   # FETCH_SIZE + WRITE_SIZE per launch, profiles/<workload>_iteration_kernels.md
 
 
 def gemm_flops_per_iteration(dims, n_nodes):
