@@ -512,6 +512,23 @@ def test_training_learns_planted_labels_then_grows_greedily(env):
     assert obj[-1] < obj[0] and acc2 > chance + 0.2
 
 
+def test_plan_info_reports_which_updates_ride_in_the_epilogues(env):
+    """Small models keep separate streaming kernels and split the contraction of the G p products; models
+    with enough product tiles fuse the step updates into the epilogues (pdADMM-G: p- and W-side, -Q: the
+    W-side only). The parity cases above therefore cover all three plans."""
+    torch, P, H = env
+    want = {"C2-small": 0, "mid": 3, "mid-Q": 2, "C5-small": 0}
+    for case, fused in want.items():
+        w = CASES[case]()
+        ctx = H.gpu_context(w, oracle_inputs(w))
+        info = P.pdadmm_plan_info(ctx)
+        assert info["fused_updates"] == fused, (case, info)
+        if fused:
+            assert info["wtrial_split"] == 1, (case, info)
+        assert len(info["wgrad_split"]) == w.n_layers and all(s >= 1 for s in info["wgrad_split"])
+        P.pdadmm_destroy(ctx)
+
+
 @pytest.mark.parametrize("quant", [False, True])
 def test_grow_layers_matches_the_oracle(env, quant):
     """Greedy layer-wise schedule through the library's own entry point: a 3-layer model trained by the
