@@ -531,8 +531,10 @@ __device__ __forceinline__ void gemm_body(const GemmProb& P, const int local, co
 }
 
 // Grouped launch: block -> (problem, tile) through the table; blocks of one die are contiguous.
+// The second launch bound asks for 3 waves per SIMD (3 blocks per compute unit, 768 on the chip, which the
+// launch plans count on): the compiler then keeps accumulators and staging registers within 168 in all.
 template <class Cfg, bool KCONTIG, class Epi, bool VECC = false>
-__global__ __launch_bounds__(256) void gemm_kernel(const GemmProb* __restrict__ probs, const BlockMap map,
+__global__ __launch_bounds__(256, 3) void gemm_kernel(const GemmProb* __restrict__ probs, const BlockMap map,
                                                    const LayerScal* __restrict__ scal, int predicated,
                                                    int panel) {
   const int lb = xcd_remap(blockIdx.x, panel);
