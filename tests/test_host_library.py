@@ -2,6 +2,8 @@
 arguments, and its host-side adjacency normalisation equals the oracle's bit for bit."""
 import os
 import re
+import shutil
+import subprocess
 
 import numpy as np
 import pytest
@@ -27,6 +29,31 @@ def test_every_declared_symbol_is_exported(lib):
     assert declared == set(P.exported_symbols())
     for name in declared:
         assert hasattr(lib, name), name
+
+
+def test_header_is_plain_c_and_a_c_program_links_against_the_library(lib, tmp_path):
+    """The boundary is a C ABI: the header must compile as C99 without warnings, and a C program that
+    names every entry point must link against the shared library (no compute calls: no GPU here)."""
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no C compiler")
+    header = os.path.join(ROOT, "include", "pdadmm.h")
+    res = subprocess.run([gcc, "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only", "-x", "c", header],
+                         capture_output=True, text=True)
+    assert res.returncode == 0, res.stderr
+    src = tmp_path / "link.c"
+    names = sorted(P.exported_symbols())
+    src.write_text('#include "pdadmm.h"\n#include <stdio.h>\nint main(void) {\n  const void* f[] = {' +
+                   ", ".join(f"(const void*)(size_t){n}" for n in names) +
+                   '};\n  printf("%d\\n", (int)(sizeof f / sizeof f[0]));\n  return f[0] == 0;\n}\n')
+    exe = tmp_path / "link"
+    libdir = os.path.dirname(P.library_path())
+    res = subprocess.run([gcc, "-std=c99", "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe),
+                          "-L", libdir, "-l:libpdadmm.so", f"-Wl,-rpath,{libdir}"], capture_output=True, text=True)
+    assert res.returncode == 0, res.stderr
+    # config validation through the linked program's view of the ABI: an invalid config needs no GPU
+    cfg = P.Config(n_nodes=0, dims=[4, 2], rho=1.0, nu=1.0)
+    assert P.pdadmm_workspace_bytes(cfg) == 0
 
 
 @pytest.mark.parametrize("name,n", [("C1", 2000), ("C2", 5000), ("C3", 3000)])
