@@ -236,7 +236,8 @@ pdadmm_status pdadmm_stats(pdadmm_ctx* ctx, double* tau, double* theta, int32_t*
 
 /* Launch plan the context was built with (HOST outputs, each may be NULL). fused_updates: bit 0 set if
  * the p-step and the residual update r -= Wg/tau are applied in the epilogues of the dense products
- * with the step size of the previous iteration and corrected by a separate pass only when the
+ * with the step size guessed ahead (the previous one, or the previous one divided by bt_eta while the
+ * step size is still falling) and corrected by a separate pass only when the
  * backtracking rule picks another one (pdADMM-G with enough product tiles to fill the chip); bit 1
  * set if the same holds for r -= Gp/theta and its column sums (both variants, same size condition).
  * A clear bit means separate streaming kernels apply that update. wgrad_split (L entries): number of

@@ -92,8 +92,11 @@ struct LayerScal {
   double tau, theta;       // current backtracking parameters
   double norm_g, norm_t;   // last reduced squared norms (diagnostics)
   float inv_tau, inv_theta;  // 1/tau, 1/theta as applied by the step kernels (0 = skip the step)
-  float fix_tau, fix_theta;  // new minus previous 1/tau, 1/theta: what a speculative update with the previous
-                             // value still has to apply (0 when the step size did not change)
+  float spec_tau, spec_theta;  // 1/tau, 1/theta that the product epilogues of the NEXT update apply ahead of the
+                               // selection: the value just chosen, or that value times eta if it was accepted at
+                               // the first trial (a step size that is still falling usually falls again)
+  float fix_tau, fix_theta;  // chosen minus applied-ahead 1/tau, 1/theta: what the correction pass still has to
+                             // apply (0 when the guess was right)
   float trial_t;           // -Q: tau of the trial in flight
   int p_trials, w_trials;
   int active;              // -Q: 1 while the p-update of this layer is still searching

@@ -41,7 +41,7 @@ __global__ __launch_bounds__(256) void axpy_kernel(const AxpySeg* __restrict__ s
 }
 
 // The same update as a small grid-stride kernel: the correction pass after a speculative update
-// (y already holds y - s_prev x; what is left is s = s_new - s_prev). Almost always s = 0 and the
+// (y already holds y - s_ahead x; what is left is s = s_new - s_ahead). Almost always s = 0 and the
 // blocks leave at once, which is why this pass does not get one block per 4 KiB.
 __global__ __launch_bounds__(256) void axpy_fix_kernel(const AxpySeg* __restrict__ segs, const BlockMap map,
                                                        const LayerScal* __restrict__ scal) {
@@ -93,8 +93,8 @@ __global__ __launch_bounds__(256) void select_step_kernel(const SelectDesc* __re
   LayerScal& sc = scal[D.layer];
   sc.norm_g = sg;
   sc.norm_t = st;
-  const float prev = mode == 0 ? sc.inv_tau : sc.inv_theta;
-  float inv = 0.0f;
+  const float ahead = mode == 0 ? sc.spec_tau : sc.spec_theta;   // what the epilogues of this update applied
+  float inv = 0.0f, next = 0.0f;
   int trials = 0;
   if (!(sg == sg) || !(st == st) || sg > 1.7e308 || st > 1.7e308) {
     atomicOr(err, kErrNonFinite);
@@ -110,10 +110,12 @@ __global__ __launch_bounds__(256) void select_step_kernel(const SelectDesc* __re
     else {
       if (mode == 0) sc.tau = t; else sc.theta = t;
       inv = (float)(1.0 / t);
+      // the next update starts at t/eta: accepted at once this time, it is likely to be accepted again
+      next = trials == 1 ? (float)(1.0 / (t / (double)eta)) : inv;
     }
   }
-  if (mode == 0) { sc.inv_tau = inv; sc.fix_tau = inv - prev; sc.p_trials = trials; }
-  else { sc.inv_theta = inv; sc.fix_theta = inv - prev; sc.w_trials = trials; }
+  if (mode == 0) { sc.inv_tau = inv; sc.fix_tau = inv - ahead; sc.spec_tau = next; sc.p_trials = trials; }
+  else { sc.inv_theta = inv; sc.fix_theta = inv - ahead; sc.spec_theta = next; sc.w_trials = trials; }
 }
 
 // ------------------------------------------------------------------------------------------

@@ -77,8 +77,8 @@ struct EpiStoreNorm { // C = acc, s0 += acc^2
   }
 };
 // g = nu*acc + u + rho*(p - q) (gradient of phi in p_l); s0 += g^2. With UPD (pdADMM-G) the same pass
-// also takes the step p -= g / tau_prev (o1 = p, in place; the old p was read for g), corrected later if
-// the selection changes tau (see EpiTrialUpd).
+// also takes the step p -= g * s_prev with the 1/tau guessed ahead (o1 = p, in place; the old p was read
+// for g), corrected later if the selection picks another tau (see EpiTrialUpd).
 template <bool UPD>
 struct EpiPGradT {
   static constexpr int NS = 1, kBatch = 4;   // elements whose inputs are fetched together (8 would cost the third block per compute unit)
@@ -110,15 +110,16 @@ typedef EpiPGradT<true> EpiPGradUpd;
 
 // Step-direction products with the residual update folded in (pdADMM-G). T = acc is stored and its norm
 // taken as in EpiStoreNorm; in the same pass the carried residual r = W p + b - z (o1, in place) takes the
-// update r -= s_prev * T with the step size of the previous iteration, which is almost always the one the
-// selection that follows confirms (tau and theta move on a grid of powers of eta). What the selection
-// changes, a small correction pass applies afterwards (fix_tau / fix_theta). EpiTrialW also leaves the
+// update r -= s_prev * T with the 1/tau or 1/theta guessed ahead by the previous selection (LayerScal::spec_*:
+// the value it chose, or that value times eta while the step size is still falling), which is almost always
+// what the selection that follows picks (tau and theta move on a grid of powers of eta). The difference, if
+// any, a small correction pass applies afterwards (fix_tau / fix_theta). EpiTrialW also leaves the
 // column sums of the updated residual (the b-update needs its node-mean) per row tile in colpart.
 template <int SCALE, bool COLSUM>
 struct EpiTrialUpd {
   static constexpr int NS = 1, kBatch = 1;
   static constexpr bool kVec = true, kExtra = true, kColsum = COLSUM;
-  static constexpr int kScale = SCALE;      // 1: previous 1/tau, 2: previous 1/theta
+  static constexpr int kScale = SCALE;      // 1: 1/tau guessed ahead, 2: 1/theta guessed ahead
   typedef NoIn In;
   struct In4 { f32x4 r; };
   __device__ static __forceinline__ In load(const GemmProb&, size_t, int) { return In{}; }
@@ -544,8 +545,8 @@ __global__ __launch_bounds__(256, 3) void gemm_kernel(const GemmProb* __restrict
   const GemmProb P = probs[pi];
   if (predicated && !scal[P.layer].active) return;
   float escale = 0.0f;
-  if (Epi::kScale == 1) escale = scal[P.layer].inv_tau;
-  if (Epi::kScale == 2) escale = scal[P.layer].inv_theta;
+  if (Epi::kScale == 1) escale = scal[P.layer].spec_tau;
+  if (Epi::kScale == 2) escale = scal[P.layer].spec_theta;
   gemm_body<Cfg, KCONTIG, Epi, VECC>(P, local, escale);
 }
 

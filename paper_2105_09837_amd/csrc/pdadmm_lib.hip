@@ -124,7 +124,7 @@ struct pdadmm_ctx {
   std::vector<GemmProb> fwd;          // forward pass of the starting point: one by-value launch per layer
   Group<ReduceProb> g_red, g_tred;
   bool spec_p = false;        // pdADMM-G, not small: the p-step and r -= Wg/tau ride in the product epilogues with
-                              // the step size of the previous iteration, corrected only when the rule picks another
+                              // the step size guessed ahead (LayerScal::spec_tau), corrected only when the rule picks another
   bool spec_w = false;        // not small (both variants): the same for r -= Gp/theta and the column sums of r
   bool small_wtrial = false;  // the G p launch has too few tiles to fill the chip: split its contraction
   Group<AxpySeg> g_pstep, g_pfix, g_qapply_r;
