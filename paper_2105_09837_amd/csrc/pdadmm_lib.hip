@@ -481,7 +481,7 @@ pdadmm_status build_tables(pdadmm_ctx* c) {
     ReduceProb rp{};
     rp.part = b.Gpart; rp.G = b.G; rp.norm_part = b.part_a; rp.M = b.n_out; rp.N = b.n_in; rp.ld = b.ld_in;
     rp.splitk = b.splitk; rp.alpha = nu; rp.vec = 1;
-    rp.nblk = std::min(2048, std::max(1, cdiv(b.n_out * b.ld_in, 1024)));
+    rp.nblk = (int)std::min<size_t>(2048, std::max<size_t>(1, ((size_t)b.n_out * b.ld_in + 1023) / 1024));
     red.push_back(rp);
     // image of G under p: T = p G^T
     GemmProb Wt_ = make_nt(b.p, b.ld_in, b.G, b.ld_in, b.T, b.ld_out, N, b.n_out, b.n_in);
@@ -500,7 +500,7 @@ pdadmm_status build_tables(pdadmm_ctx* c) {
       ReduceProb tr{};
       tr.part = b.Tpart; tr.G = b.T; tr.norm_part = b.part_b; tr.M = N; tr.N = b.n_out; tr.ld = b.ld_out;
       tr.splitk = b.wt_split; tr.alpha = 1.0f; tr.vec = 1;
-      tr.nblk = std::min(2048, std::max(1, cdiv(N * b.ld_out, 1024)));
+      tr.nblk = (int)std::min<size_t>(2048, std::max<size_t>(1, ((size_t)N * b.ld_out + 1023) / 1024));
       tred.push_back(tr);
       t_partials = tr.nblk;
     }
@@ -912,7 +912,7 @@ pdadmm_status pdadmm_gemm_tn(int32_t M, int32_t N, int32_t K, float alpha, const
   ReduceProb R{};
   R.part = part; R.G = C; R.norm_part = nullptr; R.M = M; R.N = N; R.ld = ldc; R.splitk = sk; R.alpha = alpha;
   R.vec = ldc % 4 == 0 && ((reinterpret_cast<uintptr_t>(part) | reinterpret_cast<uintptr_t>(C)) & 15) == 0;
-  R.nblk = std::min(2048, std::max(1, cdiv(M * ldc, 1024)));
+  R.nblk = (int)std::min<size_t>(2048, std::max<size_t>(1, ((size_t)M * ldc + 1023) / 1024));
   hipLaunchKernelGGL(splitk_reduce_one_kernel, dim3(R.nblk), dim3(256), 0, st, R);
   return hipGetLastError() == hipSuccess ? PDADMM_OK : PDADMM_EHIP;
 }
