@@ -166,7 +166,8 @@ def _window_state(w, layer, win, X_aug, y):
     return st, i
 
 
-WINDOWS = [("C4", 1), ("C4", 26), ("C4", 50), ("C3", 1), ("C3", 5), ("C3", 10), ("C5", 2), ("C5", 9), ("C5", 16)]
+# every distinct layer shape of the three large workloads (C5's inner layers all have the shape of layer 2)
+WINDOWS = [("C4", 1), ("C4", 26), ("C4", 50), ("C3", 1), ("C3", 5), ("C3", 10), ("C5", 2), ("C5", 16)]
 
 
 @pytest.mark.parametrize("name,layer", WINDOWS)
