@@ -487,7 +487,8 @@ def test_growing_by_identity_layers_keeps_the_function():
     # and its start must be forward-consistent (zero residuals, zero duals).
     w = small(n=150, hidden=12, n_layers=3, feat_dim=5)
     inp = oracle_inputs(w)
-    st = O.init_forward(inp["X_aug"], inp["W"], inp["b"], inp["y"], w.rho, w.nu)
+    mask = np.arange(w.n_nodes) % 3 != 0
+    st = O.init_forward(inp["X_aug"], inp["W"], inp["b"], inp["y"], 1.0, 0.01, mask=mask)
     O.iterate(st, 5)
     h = w.hidden
     eye, zero = np.eye(h), np.zeros(h)
@@ -504,6 +505,9 @@ def test_growing_by_identity_layers_keeps_the_function():
         if i < deep.L - 1:
             assert not deep.u[i].any() and np.array_equal(deep.p[i + 1], deep.q[i])
     assert deep.tau == [1.0] * 5 and deep.theta == [1.0] * 5
+    # the problem itself is carried over: penalties, labels, mask, activation, grid
+    assert (deep.rho, deep.nu, deep.slope, deep.grid, deep.quantize_q) == (1.0, 0.01, st.slope, None, False)
+    assert deep.mask is st.mask and np.array_equal(deep.y, st.y) and np.array_equal(deep.p[0], st.p[0])
     # training the grown model goes on decreasing the objective from that start
     f0 = O.objective(deep)["L_rho"]
     O.iterate(deep, 3)
