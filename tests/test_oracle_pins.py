@@ -303,6 +303,49 @@ def test_fista_two_classes_matches_logistic_prox_by_bisection():
         assert abs(z[j].sum() - a[j].sum()) < 1e-9        # the mean direction is untouched
 
 
+def test_fista_first_two_steps_are_plain_gradient_steps():
+    # Beck & Teboulle's recursion starts with t_1 = 1, so the first extrapolation coefficient (t_1 - 1)/t_2
+    # vanishes: two FISTA steps are two gradient steps of size 1/(nu + 1/2) on R(z; y) + (nu/2)||z - a||^2.
+    # The gradient here comes from central differences of that objective, not from the oracle's formula.
+    # From the third step on the extrapolation is active, so three steps must differ from three such steps.
+    rng = np.random.default_rng(11)
+    n, c, nu = 5, 4, 0.3
+    a, z0 = rng.standard_normal((n, c)), rng.standard_normal((n, c))
+    y = rng.integers(0, c, n)
+    h = lambda z: O.risk(z, y) + 0.5 * nu * float(np.sum((z - a) ** 2))
+
+    def fd_grad(z, eps=1e-6):
+        g = np.zeros_like(z)
+        for j in range(z.shape[0]):
+            for k in range(z.shape[1]):
+                e = np.zeros_like(z)
+                e[j, k] = eps
+                g[j, k] = (h(z + e) - h(z - e)) / (2 * eps)
+        return g
+
+    gd = [z0]
+    for _ in range(3):
+        gd.append(gd[-1] - fd_grad(gd[-1]) / (nu + 0.5))
+    np.testing.assert_allclose(O.fista_z_last(z0, a, y, nu, 1), gd[1], atol=1e-8)
+    np.testing.assert_allclose(O.fista_z_last(z0, a, y, nu, 2), gd[2], atol=1e-8)
+    x3 = O.fista_z_last(z0, a, y, nu, 3)
+    assert np.max(np.abs(x3 - gd[3])) > 1e-4
+    # ... and the third step extrapolates FORWARD along the last move: x_3 is the gradient step taken from
+    # x_2 + beta (x_2 - x_1) with 0 < beta < 1 (beta = (t_2 - 1)/t_3 = 0.28...); recover beta by a 1-D search
+    def step_from(beta):
+        wv = gd[2] + beta * (gd[2] - gd[1])
+        return wv - fd_grad(wv) / (nu + 0.5)
+    from scipy.optimize import minimize_scalar
+    betas = np.linspace(0.0, 1.0, 101)
+    errs = [np.sum((step_from(bv) - x3) ** 2) for bv in betas]
+    coarse = float(betas[int(np.argmin(errs))])
+    fit = minimize_scalar(lambda bv: np.sum((step_from(bv) - x3) ** 2), bounds=(coarse - 0.01, coarse + 0.01),
+                          method="bounded", options=dict(xatol=1e-10))
+    t2 = (1 + 5 ** 0.5) / 2
+    t3 = (1 + (1 + 4 * t2 * t2) ** 0.5) / 2
+    assert np.max(np.abs(step_from(fit.x) - x3)) < 1e-6 and abs(fit.x - (t2 - 1) / t3) < 1e-5
+
+
 def test_fista_unlabelled_nodes_take_linear_output_and_step_is_safe():
     rng = np.random.default_rng(8)
     n, c = 12, 5
