@@ -211,10 +211,17 @@ def test_backtracking_accepts_smallest_admissible_step_parameter(name):
     # tau on the grid previous/eta * eta^j that does, so tau/eta must fail unless it was trial 1.
     w = small(name, n=100, hidden=12, n_layers=4, feat_dim=5)
     st = oracle_state(w)
-    for it in range(3):
+    searched_p = searched_w = 0
+    for it in range(4):
+        if it == 1:
+            # start far below the admissible range so that the search has to climb: only then does the
+            # accepted value show that every term of the condition is in place
+            st.tau = [1e-5] * st.L
+            st.theta = [1e-5] * st.L
         before = st.copy()
         for i in range(1, st.L):
             O.update_p(st, i)
+            searched_p += st.p_trials[i] > 2
         for i in range(1, st.L):
             g = O.grad_p(before, i)
             def cond(t):
@@ -235,6 +242,7 @@ def test_backtracking_accepts_smallest_admissible_step_parameter(name):
         mid = st.copy()
         for i in range(st.L):
             O.update_W(st, i)
+            searched_w += st.w_trials[i] > 2
         for i in range(st.L):
             G = O.grad_W(mid, i)
             def condw(t):
@@ -254,6 +262,7 @@ def test_backtracking_accepts_smallest_admissible_step_parameter(name):
             O.update_q(st, i)
         for i in range(st.L - 1):
             O.update_u(st, i)
+    assert searched_p >= st.L - 1 and searched_w >= st.L
 
 
 # ----------------------------------------------------------------------------- P5
@@ -478,6 +487,36 @@ def test_backtracking_schedule_convention():
             assert st.p_trials[i] >= 1 and st.tau[i] == tau0[i] / st.eta * st.eta ** (st.p_trials[i] - 1)
         for i in range(st.L):
             assert st.w_trials[i] >= 1 and st.theta[i] == th0[i] / st.eta * st.eta ** (st.w_trials[i] - 1)
+
+
+def test_objective_terms_and_residual_on_a_hand_computed_state():
+    # Problem 2 / Section 3.2 on one node, widths 1-1-1-2, every term worked out by hand:
+    #   layer 1: W p + b = 1*2 + 0.5 = 2.5, z = 2      -> (z - Wp - b)^2 = 0.25; q = 1.5, f(z) = 2 -> 0.25
+    #            p_2 = 1, u_1 = 0.2                      -> u (p - q) = -0.1, (p - q)^2 = 0.25
+    #   layer 2: 2*1 - 1 = 1, z = -1                     -> 4;              q = 0.5, f(z) = 0 -> 0.25
+    #            p_3 = 3.5, u_2 = -1                     -> -3,             (p - q)^2 = 9
+    #   layer 3: a = (3.5, -3.5), z = (0, ln 3)          -> 12.25 + (ln 3 + 3.5)^2
+    #            softmax(z) = (1/4, 3/4), label 0        -> R = ln 4
+    nu, rho = 0.1, 3.0
+    W = [np.array([[1.0]]), np.array([[2.0]]), np.array([[1.0], [-1.0]])]
+    b = [np.array([0.5]), np.array([-1.0]), np.array([0.0, 0.0])]
+    st = O.init_forward(np.array([[2.0]]), W, b, np.array([0]), rho, nu)
+    st.z = [np.array([[2.0]]), np.array([[-1.0]]), np.array([[0.0, np.log(3.0)]])]
+    st.q = [np.array([[1.5]]), np.array([[0.5]])]
+    st.p = [np.array([[2.0]]), np.array([[1.0]]), np.array([[3.5]])]
+    st.u = [np.array([[0.2]]), np.array([[-1.0]])]
+    o = O.objective(st)
+    lin = 0.25 + 4.0 + 12.25 + (np.log(3.0) + 3.5) ** 2
+    want = dict(risk=np.log(4.0), lin_pen=0.05 * lin, act_pen=0.05 * 0.5, dual_lin=-3.1, dual_quad=1.5 * 9.25)
+    for k, v in want.items():
+        assert abs(o[k] - v) < 1e-12, (k, o[k], v)
+    assert abs(o["F"] - (np.log(4.0) + 0.05 * lin + 0.025)) < 1e-12
+    assert abs(o["L_rho"] - (np.log(4.0) + 0.05 * lin + 0.025 - 3.1 + 13.875)) < 1e-12
+    tot, per = O.residual(st)
+    assert abs(tot - np.sqrt(9.25)) < 1e-12 and np.allclose(per, [0.5, 3.0], atol=1e-15)
+    # phi of Section 3.2 on the same numbers: layer 2 = (nu/2)*4 + u_1 (p_2 - q_1) + (rho/2)(p_2 - q_1)^2
+    assert abs(O.phi(st, 1) - (0.05 * 4.0 - 0.1 + 1.5 * 0.25)) < 1e-12
+    assert abs(O.phi(st, 0) - 0.05 * 0.25) < 1e-12
 
 
 # ----------------------------------------------------------------------------- the model (Problem 1)
