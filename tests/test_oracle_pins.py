@@ -489,6 +489,41 @@ def test_backtracking_schedule_convention():
             assert st.w_trials[i] >= 1 and st.theta[i] == th0[i] / st.eta * st.eta ** (st.w_trials[i] - 1)
 
 
+def test_quantized_start_keeps_p_on_the_grid_and_q_only_in_the_variant():
+    # Problem 3: p_l in Delta for l >= 2 from the start on; q_l is a free variable (q_l = f(z_l) at the
+    # forward-consistent start) unless the variant of Appendix B's last paragraph keeps it on Delta too.
+    w = small("C5", n=120, hidden=10, n_layers=4, feat_dim=5)
+    inp = oracle_inputs(w)
+    for both in (False, True):
+        st = oracle_state(dataclasses.replace(w, quant_q=both), inp, perturbed=False)
+        mem = st.grid.members().astype(F64)
+        half = 0.5 * float(st.grid.step32)
+        for i in range(1, st.L):
+            fz = O.act(st.z[i - 1])
+            dist = np.abs(fz[..., None] - mem)
+            nearest = mem[np.argmin(dist, axis=-1)]
+            clear = np.abs(np.sort(dist, axis=-1)[..., 0] - np.sort(dist, axis=-1)[..., 1]) > 1e-6 * half
+            assert np.isin(st.p[i], mem).all()
+            assert np.array_equal(st.p[i][clear], nearest[clear])          # brute-force nearest member
+            if both:
+                assert np.array_equal(st.q[i - 1], st.p[i])
+            else:
+                assert np.allclose(st.q[i - 1], fz, rtol=0, atol=1e-6)
+                assert not np.isin(st.q[i - 1], mem).all()
+
+
+def test_risk_is_stable_for_large_outputs():
+    # R = logsumexp(z) - z_y (Section 3.1 uses the cross-entropy): for z = (1000, 0) it is 0 for label 0
+    # and 1000 for label 1; a naive exp overflows here.
+    z = np.array([[1000.0, 0.0], [-1000.0, 0.0], [0.0, 0.0]])
+    with np.errstate(over="raise", invalid="raise"):
+        assert abs(O.risk(z[:1], np.array([0]))) < 1e-12
+        assert abs(O.risk(z[:1], np.array([1])) - 1000.0) < 1e-9
+        assert abs(O.risk(z, np.array([1, 0, 0])) - (1000.0 + 1000.0 + np.log(2.0))) < 1e-9
+        out = O.fista_z_last(z, z.copy(), np.array([1, 0, 0]), 0.1, 3)
+    assert np.isfinite(out).all()
+
+
 def test_objective_terms_and_residual_on_a_hand_computed_state():
     # Problem 2 / Section 3.2 on one node, widths 1-1-1-2, every term worked out by hand:
     #   layer 1: W p + b = 1*2 + 0.5 = 2.5, z = 2      -> (z - Wp - b)^2 = 0.25; q = 1.5, f(z) = 2 -> 0.25
