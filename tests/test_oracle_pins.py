@@ -524,6 +524,50 @@ def test_risk_is_stable_for_large_outputs():
     assert np.isfinite(out).all()
 
 
+@pytest.mark.parametrize("name", ["C1", "C5"])
+def test_iteration_takes_the_updates_in_the_order_of_algorithm_1(name):
+    # Algorithm 1: p_l (l = 2..L) from the old W, b, z, q, u; then W_l from the new p; b_l from the new p, W;
+    # z_l from the new p, W, b; q_l from the new p_{l+1}, z_l and the old u_l; last u_l from the new p, q.
+    # Each update below is applied to a state that holds exactly those versions; the sweep must agree.
+    w = small(name, n=90, hidden=9, n_layers=4, feat_dim=4)
+    st = oracle_state(w)
+    ref = st.copy()
+    O.iterate(st, 1)
+    L = ref.L
+    old = ref.copy()
+    for i in range(1, L):
+        O.update_p(ref, i)
+    for i in range(1, L):        # the p-updates of different layers do not see each other
+        solo = old.copy()
+        O.update_p(solo, i)
+        assert np.array_equal(solo.p[i], ref.p[i])
+    assert all(np.array_equal(ref.W[i], old.W[i]) for i in range(L))
+    for i in range(L):
+        O.update_W(ref, i)
+    for i in range(L):
+        O.update_b(ref, i)
+    assert all(np.array_equal(ref.z[i], old.z[i]) for i in range(L))
+    for i in range(L - 1):
+        O.update_z_hidden(ref, i)
+    O.update_z_last(ref)
+    assert all(np.array_equal(ref.u[i], old.u[i]) for i in range(L - 1))
+    for i in range(L - 1):
+        O.update_q(ref, i)
+    for i in range(L - 1):
+        O.update_u(ref, i)
+    for name_, a, b in [("p", st.p, ref.p), ("W", st.W, ref.W), ("b", st.b, ref.b), ("z", st.z, ref.z),
+                        ("q", st.q, ref.q), ("u", st.u, ref.u)]:
+        for i in range(len(a)):
+            assert np.array_equal(a[i], b[i]), (name_, i)
+    # the W-update has used the NEW p: its gradient at the old p would have given another W
+    # (in -Q a small step can project back onto the old p; then there is nothing to tell apart)
+    probe = old.copy()
+    O.update_W(probe, 1)
+    moved = not np.array_equal(old.p[1], st.p[1])
+    assert moved or name == "C5"
+    assert np.array_equal(probe.W[1], st.W[1]) == (not moved)
+
+
 def test_objective_terms_and_residual_on_a_hand_computed_state():
     # Problem 2 / Section 3.2 on one node, widths 1-1-1-2, every term worked out by hand:
     #   layer 1: W p + b = 1*2 + 0.5 = 2.5, z = 2      -> (z - Wp - b)^2 = 0.25; q = 1.5, f(z) = 2 -> 0.25
