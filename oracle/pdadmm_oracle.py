@@ -29,7 +29,13 @@ paper itself; the tests pin them only through the mathematical properties they i
     (not mean) of cross-entropy over labelled nodes; unlabelled nodes take z = W p + b;
   * Delta is a uniform grid (lo, hi, levels); the nearest-level decision is taken in fp32
     (the precision of the stored p), ties to the even index;
-  * variant with p and q both on Delta (Appendix B, last paragraph): the start projects q_l too.
+  * variant with p and q both on Delta (Appendix B, last paragraph): the start projects q_l too;
+  * least-squares risk R(z; y) = 1/2 sum_j ||z_j - e_{y_j}||^2 over labelled nodes (Section 3.1 only asks
+    R to be convex and continuous; Section 5.1 uses cross-entropy): its z_L-subproblem has a closed form.
+
+Memory-lean mode (State.store32): every variable is STORED as fp32 (the precision the HIP path stores)
+and each update reads its operands up to fp64, computes in fp64 exactly as below and rounds its result to
+fp32 once. It exists so that the two largest workloads fit the host memory; the arithmetic is the same.
 """
 from __future__ import annotations
 
@@ -40,6 +46,11 @@ import numpy as np
 
 F32 = np.float32
 F64 = np.float64
+
+
+def _f64(x):
+    """Operand of an update in fp64 (no copy when it already is)."""
+    return np.asarray(x, dtype=F64)
 
 
 # --------------------------------------------------------------------------------------
@@ -181,10 +192,17 @@ class State:
     p_wait: List[int] = field(default_factory=list)    # -Q: iterations to wait after a failed probe of tau/eta
     p_skip: List[int] = field(default_factory=list)    # -Q: iterations left until the next probe
     probe_cap: int = 16
+    probe_backoff: bool = True     # -Q: False = every p-update starts at previous/eta, as in pdADMM-G
+    risk_kind: str = "ce"          # "ce": cross-entropy (Section 5.1); "ls": least squares against the one-hot label
+    store32: bool = False          # memory-lean mode: variables are kept as fp32 between updates
 
     @property
     def L(self) -> int:
         return len(self.W)
+
+    def keep(self, x):
+        """Result of an update as it is stored: fp64, or rounded once to fp32 in the memory-lean mode."""
+        return np.asarray(x, dtype=F32) if self.store32 else x
 
     def copy(self) -> "State":
         c = lambda xs: [np.array(x, copy=True) for x in xs]
@@ -192,7 +210,7 @@ class State:
                      self.mask, self.rho, self.nu, self.grid, list(self.tau), list(self.theta),
                      self.eta, self.bt_max_trials, self.fista_iters, list(self.p_trials),
                      list(self.w_trials), self.quantize_q, self.slope, list(self.p_wait), list(self.p_skip),
-                     self.probe_cap)
+                     self.probe_cap, self.probe_backoff, self.risk_kind, self.store32)
 
 
 def init_forward(X_aug, W0, b0, y, rho, nu, grid: Optional[Grid] = None, mask=None,
@@ -202,13 +220,16 @@ def init_forward(X_aug, W0, b0, y, rho, nu, grid: Optional[Grid] = None, mask=No
     onto Delta for -Q; q_l too in the variant that keeps q on the grid), u_l = 0. (The paper only
     says 'initialise'; its theorems hold from any start.)"""
     L = len(W0)
-    W = [np.asarray(w, dtype=F64) for w in W0]
-    b = [np.asarray(v, dtype=F64) for v in b0]
-    p = [np.asarray(X_aug, dtype=F64)]
-    z, q, u = [], [], []
+    st = State([], [], [], [], [], [], np.asarray(y), mask, float(rho), float(nu), grid,
+               [tau0] * L, [theta0] * L, p_trials=[0] * L, w_trials=[0] * L,
+               quantize_q=bool(quantize_q and grid is not None), slope=float(slope),
+               p_wait=[0] * L, p_skip=[0] * L, **kw)
+    st.W = [st.keep(np.asarray(w, dtype=F64)) for w in W0]
+    st.b = [st.keep(np.asarray(v, dtype=F64)) for v in b0]
+    st.p = [st.keep(np.asarray(X_aug, dtype=F64))]
     for i in range(L):
-        zi = p[i] @ W[i].T + b[i]
-        z.append(zi)
+        zi = _f64(st.p[i]) @ _f64(st.W[i]).T + _f64(st.b[i])
+        st.z.append(st.keep(zi))
         if i < L - 1:
             qi = act(zi, slope)
             nxt = qi
@@ -216,13 +237,10 @@ def init_forward(X_aug, W0, b0, y, rho, nu, grid: Optional[Grid] = None, mask=No
                 nxt = quantize(qi, grid)[1].astype(F64)
                 if quantize_q:
                     qi = nxt.copy()
-            q.append(qi)
-            p.append(np.array(nxt, dtype=F64, copy=True))
-            u.append(np.zeros_like(qi))
-    return State(W, b, z, p, q, u, np.asarray(y), mask, float(rho), float(nu), grid,
-                 [tau0] * L, [theta0] * L, p_trials=[0] * L, w_trials=[0] * L,
-                 quantize_q=bool(quantize_q and grid is not None), slope=float(slope),
-                 p_wait=[0] * L, p_skip=[0] * L, **kw)
+            st.q.append(st.keep(qi))
+            st.p.append(st.keep(np.array(nxt, dtype=F64, copy=True)))
+            st.u.append(st.keep(np.zeros_like(qi)))
+    return st
 
 
 def grow_layers(st: State, from_layer, W_new, b_new, **kw) -> State:
@@ -242,38 +260,41 @@ def grow_layers(st: State, from_layer, W_new, b_new, **kw) -> State:
             W.append(np.asarray(W_new[i], dtype=F64))
             b.append(np.asarray(b_new[i], dtype=F64))
     return init_forward(st.p[0], W, b, st.y, st.rho, st.nu, grid=st.grid, mask=st.mask,
-                        quantize_q=st.quantize_q, slope=st.slope, **kw)
+                        quantize_q=st.quantize_q, slope=st.slope, probe_backoff=st.probe_backoff,
+                        risk_kind=st.risk_kind, store32=st.store32, **kw)
 
 
 def phi(st: State, i: int, p=None, W=None, b=None) -> float:
     """phi for layer l = i+1 (Section 3.2): (nu/2)||z - W p - b||^2, plus for l >= 2
     <u_{l-1}, p - q_{l-1}> + (rho/2)||p - q_{l-1}||^2."""
-    p = st.p[i] if p is None else p
-    W = st.W[i] if W is None else W
-    b = st.b[i] if b is None else b
-    res = st.z[i] - (p @ W.T + b)
+    p = _f64(st.p[i] if p is None else p)
+    W = _f64(st.W[i] if W is None else W)
+    b = _f64(st.b[i] if b is None else b)
+    res = _f64(st.z[i]) - (p @ W.T + b)
     val = 0.5 * st.nu * float(np.sum(res * res))
     if i >= 1:
-        dpq = p - st.q[i - 1]
-        val += float(np.sum(st.u[i - 1] * dpq)) + 0.5 * st.rho * float(np.sum(dpq * dpq))
+        dpq = p - _f64(st.q[i - 1])
+        val += float(np.sum(_f64(st.u[i - 1]) * dpq)) + 0.5 * st.rho * float(np.sum(dpq * dpq))
     return val
 
 
 def grad_p(st: State, i: int) -> np.ndarray:
     """Gradient of phi in p_l (l = i+1 >= 2): nu W^T (W p + b - z) + u_{l-1} + rho (p - q_{l-1})."""
-    r = st.p[i] @ st.W[i].T + st.b[i] - st.z[i]
-    return st.nu * (r @ st.W[i]) + st.u[i - 1] + st.rho * (st.p[i] - st.q[i - 1])
+    p, W = _f64(st.p[i]), _f64(st.W[i])
+    r = p @ W.T + _f64(st.b[i]) - _f64(st.z[i])
+    return st.nu * (r @ W) + _f64(st.u[i - 1]) + st.rho * (p - _f64(st.q[i - 1]))
 
 
 def grad_W(st: State, i: int) -> np.ndarray:
     """Gradient of phi in W_l: nu (W p + b - z) p^T."""
-    r = st.p[i] @ st.W[i].T + st.b[i] - st.z[i]
-    return st.nu * (r.T @ st.p[i])
+    p = _f64(st.p[i])
+    r = p @ _f64(st.W[i]).T + _f64(st.b[i]) - _f64(st.z[i])
+    return st.nu * (r.T @ p)
 
 
 def grad_b(st: State, i: int) -> np.ndarray:
     """Gradient of phi in b_l: nu * sum over nodes of (W p + b - z)."""
-    r = st.p[i] @ st.W[i].T + st.b[i] - st.z[i]
+    r = _f64(st.p[i]) @ _f64(st.W[i]).T + _f64(st.b[i]) - _f64(st.z[i])
     return st.nu * r.sum(axis=0)
 
 
@@ -293,14 +314,16 @@ def update_p(st: State, i: int) -> None:
     is only probed when it has a chance: after a probe that was rejected the next probe waits
     1, 2, 4, ... (at most probe_cap) iterations, during which the update starts at the previous tau; a
     probe that is accepted at once resets the wait. From its start value tau is multiplied by eta
-    until the condition holds, in both variants."""
+    until the condition holds, in both variants. With probe_backoff = False the -Q update follows the
+    plain schedule of pdADMM-G (every update starts at previous/eta)."""
     g = grad_p(st, i)
     if not np.any(g):
         st.p_trials[i] = 0
         return
-    p_old = st.p[i]
+    p_old = _f64(st.p[i])
     phi0 = phi(st, i)
-    probing = st.grid is None or st.p_skip[i] == 0
+    backoff = st.grid is not None and st.probe_backoff
+    probing = not backoff or st.p_skip[i] == 0
     if not probing:
         st.p_skip[i] -= 1
     t = st.tau[i] / st.eta if probing else st.tau[i]
@@ -312,9 +335,9 @@ def update_p(st: State, i: int) -> None:
         upper = phi0 + float(np.sum(g * d)) + 0.5 * t * float(np.sum(d * d))
         if phi(st, i, p=cand) <= upper:
             st.tau[i] = t
-            st.p[i] = cand
+            st.p[i] = st.keep(cand)
             st.p_trials[i] = trial
-            if st.grid is not None and probing:
+            if backoff and probing:
                 if trial == 1:
                     st.p_wait[i] = 0
                 else:
@@ -331,7 +354,7 @@ def update_W(st: State, i: int) -> None:
     if not np.any(G):
         st.w_trials[i] = 0
         return
-    W_old = st.W[i]
+    W_old = _f64(st.W[i])
     phi0 = phi(st, i)
     t = st.theta[i] / st.eta
     for trial in range(1, st.bt_max_trials + 1):
@@ -340,7 +363,7 @@ def update_W(st: State, i: int) -> None:
         upper = phi0 + float(np.sum(G * D)) + 0.5 * t * float(np.sum(D * D))
         if phi(st, i, W=cand) <= upper:
             st.theta[i] = t
-            st.W[i] = cand
+            st.W[i] = st.keep(cand)
             st.w_trials[i] = trial
             return
         t *= st.eta
@@ -350,7 +373,7 @@ def update_W(st: State, i: int) -> None:
 def update_b(st: State, i: int) -> None:
     """b_l <- b_l - grad_b phi / (nu |V|): the exact minimiser over a broadcast bias."""
     n_nodes = st.p[i].shape[0]
-    st.b[i] = st.b[i] - grad_b(st, i) / (st.nu * n_nodes)
+    st.b[i] = st.keep(_f64(st.b[i]) - grad_b(st, i) / (st.nu * n_nodes))
 
 
 def z_subproblem_value(z, a, q, z_old, slope: float = 0.0):
@@ -364,13 +387,13 @@ def update_z_hidden(st: State, i: int) -> None:
     derivation (minimise the quadratic on each half-line, clamp at 0) gives
     min((a + z_old + slope*q)/(2 + slope^2), 0) for the non-positive side; the positive side is
     unchanged. Keep the candidate with the smaller subproblem value, ties to the non-positive one."""
-    a = st.p[i] @ st.W[i].T + st.b[i]
-    z_old, q, sl = st.z[i], st.q[i], st.slope
+    a = _f64(st.p[i]) @ _f64(st.W[i]).T + _f64(st.b[i])
+    z_old, q, sl = _f64(st.z[i]), _f64(st.q[i]), st.slope
     z_neg = np.minimum((a + z_old + sl * q) / (2.0 + sl * sl), 0.0)
     z_pos = np.maximum((a + q + z_old) / 3.0, 0.0)
     h_neg = z_subproblem_value(z_neg, a, q, z_old, sl)
     h_pos = z_subproblem_value(z_pos, a, q, z_old, sl)
-    st.z[i] = np.where(h_pos < h_neg, z_pos, z_neg)
+    st.z[i] = st.keep(np.where(h_pos < h_neg, z_pos, z_neg))
 
 
 def log_softmax(z):
@@ -379,10 +402,20 @@ def log_softmax(z):
     return e - np.log(np.exp(e).sum(axis=1, keepdims=True))
 
 
-def risk(z_last, y, mask=None) -> float:
-    """R(z_L; y): cross-entropy summed over labelled nodes."""
-    ls = log_softmax(z_last)
-    per = -ls[np.arange(z_last.shape[0]), y]
+def risk(z_last, y, mask=None, kind: str = "ce") -> float:
+    """R(z_L; y) summed over labelled nodes. "ce": cross-entropy, logsumexp(z_j) - z_{j, y_j} (Section 5.1);
+    "ls": least squares against the one-hot label, 1/2 ||z_j - e_{y_j}||^2 (any convex continuous risk is
+    admissible, Section 3.1)."""
+    z_last = _f64(z_last)
+    rows = np.arange(z_last.shape[0])
+    if kind == "ce":
+        per = -log_softmax(z_last)[rows, y]
+    elif kind == "ls":
+        t = np.zeros_like(z_last)
+        t[rows, y] = 1.0
+        per = 0.5 * np.sum((z_last - t) ** 2, axis=1)
+    else:
+        raise ValueError(f"unknown risk {kind!r}")
     if mask is not None:
         per = per[mask]
     return float(per.sum())
@@ -409,24 +442,41 @@ def fista_z_last(z_start, a, y, nu, iters, mask=None):
     return x
 
 
+def least_squares_z_last(a, y, nu, mask=None):
+    """argmin_z 1/2 ||z - e_y||^2 + (nu/2)||z - a||^2 per labelled node: the gradient (z - e_y) + nu (z - a)
+    vanishes at z = (e_y + nu a) / (1 + nu). Unlabelled nodes have no risk term: z = a."""
+    n, c = a.shape
+    onehot = np.zeros((n, c))
+    onehot[np.arange(n), y] = 1.0
+    z = (onehot + nu * a) / (1.0 + nu)
+    if mask is not None:
+        z = np.where(mask[:, None], z, a)
+    return z
+
+
 def update_z_last(st: State) -> None:
+    """z_L <- argmin R(z; y) + (nu/2)||z - W_L p_L - b_L||^2 (Appendix A 'update z', the l = L line):
+    FISTA for the cross-entropy risk, the closed form for the least-squares risk."""
     i = st.L - 1
-    a = st.p[i] @ st.W[i].T + st.b[i]
-    st.z[i] = fista_z_last(st.z[i], a, st.y, st.nu, st.fista_iters, st.mask)
+    a = _f64(st.p[i]) @ _f64(st.W[i]).T + _f64(st.b[i])
+    if st.risk_kind == "ls":
+        st.z[i] = st.keep(least_squares_z_last(a, st.y, st.nu, st.mask))
+    else:
+        st.z[i] = st.keep(fista_z_last(_f64(st.z[i]), a, st.y, st.nu, st.fista_iters, st.mask))
 
 
 def update_q(st: State, i: int) -> None:
     """q_l <- (rho p_{l+1} + u_l + nu f(z_l)) / (rho + nu) (Appendix A 'update q'); in the variant
     that quantises q as well, the nearest member of Delta to that value (Appendix B, last paragraph)."""
-    q = (st.rho * st.p[i + 1] + st.u[i] + st.nu * act(st.z[i], st.slope)) / (st.rho + st.nu)
+    q = (st.rho * _f64(st.p[i + 1]) + _f64(st.u[i]) + st.nu * act(_f64(st.z[i]), st.slope)) / (st.rho + st.nu)
     if st.quantize_q:
         q = quantize(q, st.grid)[1].astype(F64)
-    st.q[i] = q
+    st.q[i] = st.keep(q)
 
 
 def update_u(st: State, i: int) -> None:
     """u_l <- u_l + rho (p_{l+1} - q_l)."""
-    st.u[i] = st.u[i] + st.rho * (st.p[i + 1] - st.q[i])
+    st.u[i] = st.keep(_f64(st.u[i]) + st.rho * (_f64(st.p[i + 1]) - _f64(st.q[i])))
 
 
 def iterate(st: State, n_iters: int = 1) -> None:
@@ -454,9 +504,9 @@ def iterate(st: State, n_iters: int = 1) -> None:
 def forward(st: State) -> np.ndarray:
     """Output layer of the GA-MLP for the current weights: p_1 = X, p_{l+1} = f(W_l p_l + b_l) for
     l < L, result W_L p_L + b_L (node-major [|V|, n_L]). The ADMM variables p, z, q are not used."""
-    a = st.p[0]
+    a = _f64(st.p[0])
     for i in range(st.L):
-        z = a @ st.W[i].T + st.b[i]
+        z = a @ _f64(st.W[i]).T + _f64(st.b[i])
         a = act(z, st.slope)
     return z
 
@@ -482,11 +532,11 @@ def objective(st: State) -> dict:
     """Terms of L_rho: risk, (nu/2) sum ||z - W p - b||^2, (nu/2) sum ||q - f(z)||^2,
     sum <u, p_{l+1} - q_l>, (rho/2) sum ||p_{l+1} - q_l||^2; F = first three; L_rho = all."""
     L = st.L
-    lin = sum(float(np.sum((st.z[i] - st.p[i] @ st.W[i].T - st.b[i]) ** 2)) for i in range(L))
-    actp = sum(float(np.sum((st.q[i] - act(st.z[i], st.slope)) ** 2)) for i in range(L - 1))
-    dl = sum(float(np.sum(st.u[i] * (st.p[i + 1] - st.q[i]))) for i in range(L - 1))
-    dq = sum(float(np.sum((st.p[i + 1] - st.q[i]) ** 2)) for i in range(L - 1))
-    out = dict(risk=risk(st.z[L - 1], st.y, st.mask), lin_pen=0.5 * st.nu * lin,
+    lin = sum(float(np.sum((_f64(st.z[i]) - _f64(st.p[i]) @ _f64(st.W[i]).T - _f64(st.b[i])) ** 2)) for i in range(L))
+    actp = sum(float(np.sum((_f64(st.q[i]) - act(_f64(st.z[i]), st.slope)) ** 2)) for i in range(L - 1))
+    dl = sum(float(np.sum(_f64(st.u[i]) * (_f64(st.p[i + 1]) - _f64(st.q[i])))) for i in range(L - 1))
+    dq = sum(float(np.sum((_f64(st.p[i + 1]) - _f64(st.q[i])) ** 2)) for i in range(L - 1))
+    out = dict(risk=risk(st.z[L - 1], st.y, st.mask, st.risk_kind), lin_pen=0.5 * st.nu * lin,
                act_pen=0.5 * st.nu * actp, dual_lin=dl, dual_quad=0.5 * st.rho * dq)
     out["F"] = out["risk"] + out["lin_pen"] + out["act_pen"]
     out["L_rho"] = out["F"] + out["dual_lin"] + out["dual_quad"]
@@ -495,5 +545,5 @@ def objective(st: State) -> dict:
 
 def residual(st: State):
     """sqrt(sum_l ||p_{l+1} - q_l||_F^2) and the per-layer norms."""
-    per = np.array([np.sqrt(float(np.sum((st.p[i + 1] - st.q[i]) ** 2))) for i in range(st.L - 1)])
+    per = np.array([np.sqrt(float(np.sum((_f64(st.p[i + 1]) - _f64(st.q[i])) ** 2))) for i in range(st.L - 1)])
     return float(np.sqrt(np.sum(per ** 2))), per

@@ -6,17 +6,27 @@ nothing here touches the HIP library. The paper prints no worked numeric example
 so these files are the stored expectations for the full-size trajectory tests:
 
     python tests/golden/write_golden.py C1 C2 C4
+    python tests/golden/write_golden.py C3 C5 C5:plain      (hours on 8 cores; run in the background)
 
 One text file per workload, `<name>_trajectory.txt`: a header with the recipe, then one line per
 iteration k = 0..iters (k = 0 is the perturbed start) with
     k risk lin_pen act_pen dual_lin dual_quad F L_rho residual | tau_2..tau_L | theta_1..theta_L
 Floating-point numbers are printed with 17 significant digits (round-trip exact for fp64).
+
+C3 and C5 do not fit the host memory in fp64: they run in the oracle's memory-lean mode (variables
+stored as fp32 between updates, every update computed in fp64), and, because one oracle iteration of
+theirs takes a quarter of an hour on one core, with the updates of different layers of one phase running
+side by side in threads (`--workers N`; within a phase of Algorithm 1 the layers are independent, every
+update is still the oracle's own function call). `<name>:plain` runs a -Q workload with
+the plain backtracking schedule (every p-update starts at the previous tau divided by eta) instead of
+the probe back-off and writes `<name>_plain_trajectory.txt`.
 """
 from __future__ import annotations
 
 import os
 import sys
 import time
+from concurrent.futures import ThreadPoolExecutor
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(os.path.dirname(HERE))
@@ -38,25 +48,67 @@ def line(k, st):
             " ".join(f"{t:.17g}" for t in st.tau[1:]) + " | " + " ".join(f"{t:.17g}" for t in st.theta))
 
 
-def write(name: str) -> str:
+LEAN = ("C3", "C5", "C5pq")     # state too large for fp64 storage on the host
+
+
+def iterate_layers_side_by_side(st, workers: int) -> None:
+    """One iteration of Algorithm 1, phase after phase as O.iterate does it, with the per-layer updates of a
+    phase spread over `workers` threads (they read and write disjoint variables)."""
+    L = st.L
+    with ThreadPoolExecutor(max_workers=workers) as ex:
+        def phase(fn, layers):
+            for _ in ex.map(lambda i: fn(st, i), layers):
+                pass
+        phase(O.update_p, range(1, L))
+        phase(O.update_W, range(L))
+        phase(O.update_b, range(L))
+        phase(O.update_z_hidden, range(L - 1))
+        O.update_z_last(st)
+        phase(O.update_q, range(L - 1))
+        phase(O.update_u, range(L - 1))
+
+
+def write(spec: str, workers: int = 1) -> str:
+    name, _, mode = spec.partition(":")
+    if mode not in ("", "plain"):
+        raise SystemExit(f"unknown mode {mode!r}")
     w = get_workload(name)
+    lean = name in LEAN
     t0 = time.time()
     inp = oracle_inputs(w)
-    st = oracle_state(w, inp)          # forward-consistent start, perturbed, fp32-representable
-    path = os.path.join(HERE, f"{name}_trajectory.txt")
+    kw = dict(store32=True) if lean else {}
+    if mode == "plain":
+        if w.quant is None:
+            raise SystemExit("the plain schedule is the only one pdADMM-G has")
+        kw["probe_backoff"] = False
+    st = oracle_state(w, inp, **kw)    # forward-consistent start, perturbed, fp32-representable
+    del inp
+    print(f"{spec}: start state ready, {time.time() - t0:.0f} s", flush=True)
+    path = os.path.join(HERE, f"{name}{'_plain' if mode else ''}_trajectory.txt")
     with open(path, "w") as f:
         f.write(f"# oracle trajectory of workload {name}: N={w.n_nodes} dims={w.dims[0]},{w.dims[1]}x{w.n_layers - 1},{w.dims[-1]} "
-                f"rho={w.rho} nu={w.nu} quant={w.quant} iters={w.iters}; start = tests.helpers.oracle_state(w)\n")
+                f"rho={w.rho} nu={w.nu} quant={w.quant} iters={w.iters}; start = tests.helpers.oracle_state(w"
+                f"{', store32=True' if lean else ''}{', probe_backoff=False' if mode else ''})"
+                f"{'; variables stored as fp32 between updates, updates in fp64' if lean else ''}\n")
         f.write("# k " + " ".join(KEYS) + " residual | tau_2..tau_L | theta_1..theta_L\n")
         f.write(line(0, st) + "\n")
         for k in range(1, w.iters + 1):
-            O.iterate(st, 1)
+            if workers > 1:
+                iterate_layers_side_by_side(st, workers)
+            else:
+                O.iterate(st, 1)
             f.write(line(k, st) + "\n")
             f.flush()
-            print(f"{name}: iteration {k}/{w.iters} done, {time.time() - t0:.0f} s", flush=True)
+            print(f"{spec}: iteration {k}/{w.iters} done, {time.time() - t0:.0f} s", flush=True)
     return path
 
 
 if __name__ == "__main__":
-    for nm in sys.argv[1:] or ["C1", "C2"]:
-        print(write(nm))
+    args = sys.argv[1:]
+    n_workers = 1
+    if "--workers" in args:
+        k = args.index("--workers")
+        n_workers = int(args[k + 1])
+        del args[k:k + 2]
+    for nm in args or ["C1", "C2"]:
+        print(write(nm, n_workers))

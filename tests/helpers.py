@@ -5,7 +5,7 @@ import numpy as np
 
 from oracle import pdadmm_oracle as O
 from workloads import (get_workload, make_features, make_graph, make_labels, make_weights,
-                       perturb_state, scaled_workload, stream_rng)
+                       perturb_layers, perturb_state, scaled_workload, stream_rng)
 
 F32, F64 = np.float32, np.float64
 
@@ -27,27 +27,29 @@ def oracle_inputs(w):
 
 
 def oracle_state(w, inp=None, perturbed=True, **kw):
-    """Forward-consistent oracle state, optionally perturbed (all arrays fp32-representable)."""
+    """Forward-consistent oracle state, optionally perturbed (all arrays fp32-representable).
+    With store32=True (the oracle's memory-lean mode) the arrays stay fp32 and are replaced layer by
+    layer, so that the largest workloads fit the host memory."""
     inp = oracle_inputs(w) if inp is None else inp
     g = grid_of(w)
+    kw.setdefault("risk_kind", w.risk)
     st = O.init_forward(inp["X_aug"], inp["W"], inp["b"], inp["y"], w.rho, w.nu, grid=g, quantize_q=w.quant_q, slope=w.slope, **kw)
+    hold = (lambda a: a) if st.store32 else (lambda a: a.astype(F64))
     if perturbed:
         quant = (lambda a: O.quantize(a, g)[1]) if g is not None else None
-        z, q, p, u = perturb_state(w, [a.astype(F32) for a in st.z], [a.astype(F32) for a in st.q],
-                                   quantizer=quant)
-        for i in range(st.L):
-            st.z[i] = z[i].astype(F64)
+        for i, z, q, p, u in perturb_layers(w, st.z, st.q, quantizer=quant):
+            st.z[i] = hold(z)
             if i < st.L - 1:
-                st.q[i] = (quant(q[i]) if w.quant_q else q[i]).astype(F64)
-                st.p[i + 1] = p[i].astype(F64)
-                st.u[i] = u[i].astype(F64)
+                st.q[i] = hold(quant(q) if w.quant_q else q)
+                st.p[i + 1] = hold(p)
+                st.u[i] = hold(u)
     else:
         # make every array fp32-representable so that both sides start from identical bits
         for i in range(st.L):
-            st.z[i] = st.z[i].astype(F32).astype(F64)
+            st.z[i] = hold(st.z[i].astype(F32))
             if i < st.L - 1:
-                st.q[i] = st.q[i].astype(F32).astype(F64)
-                st.p[i + 1] = st.p[i + 1].astype(F32).astype(F64)
+                st.q[i] = hold(st.q[i].astype(F32))
+                st.p[i + 1] = hold(st.p[i + 1].astype(F32))
     return st
 
 

@@ -7,8 +7,8 @@ no augmentation, no forward pass and no ADMM update lives here.
 from .configs import Workload, WORKLOADS, get_workload, scaled_workload
 from .graphs import erdos_renyi, preferential_attachment, make_graph
 from .data import (stream_rng, make_features, make_labels, make_weights,
-                   noise_like, perturb_state, layer_window, planted_labels)
+                   noise_like, perturb_state, perturb_layers, layer_window, planted_labels)
 
 __all__ = ["Workload", "WORKLOADS", "get_workload", "scaled_workload", "erdos_renyi",
            "preferential_attachment", "make_graph", "stream_rng", "make_features",
-           "make_labels", "make_weights", "noise_like", "perturb_state", "layer_window", "planted_labels"]
+           "make_labels", "make_weights", "noise_like", "perturb_state", "perturb_layers", "layer_window", "planted_labels"]

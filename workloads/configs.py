@@ -30,6 +30,7 @@ class Workload:
     quant: Optional[Tuple[float, float, int]] = None   # (lo, hi, levels) of the uniform grid
     quant_q: bool = False                               # q_l is kept on the grid as well (needs quant)
     slope: float = 0.0                                  # negative-side slope of the activation (0 = ReLU)
+    risk: str = "ce"                                    # risk on the output layer: "ce" cross-entropy, "ls" least squares
 
     @property
     def n0(self) -> int:

@@ -51,32 +51,43 @@ def _rms(a: np.ndarray) -> np.float32:
     return np.float32(np.sqrt(np.mean(np.square(a, dtype=np.float64))))
 
 
-def perturb_state(w: Workload, z, q, quantizer=None, scale: float = 0.1):
-    """Given forward-consistent z_1..z_L and q_1..q_{L-1} (node-major fp32 arrays), return
-    perturbed (z, q, p_2..p_L, u_1..u_{L-1}):
-        z_l += s*rms(z_l)*n1,  q_l += s*rms(q_l)*n2,  p_{l+1} = q_l + s*rms(q_l)*n3,
-        u_l = s*nu*rms(q_l)*n4,
-    with n* ~ N(0,1) from the workload's noise stream. `quantizer`, when given, is applied to
-    every p (it is the caller's projection onto the grid; this module does not define it)."""
+def perturb_layers(w: Workload, z, q, quantizer=None, scale: float = 0.1):
+    """Given forward-consistent z_1..z_L and q_1..q_{L-1} (node-major arrays), yield per layer
+    (l, z_l', q_l', p_{l+1}', u_l') with
+        z_l' = z_l + s*rms(z_l)*n1,  q_l' = q_l + s*rms(q_l)*n2,  p_{l+1}' = q_l' + s*rms(q_l)*n3,
+        u_l' = s*nu*rms(q_l)*n4,
+    n* ~ N(0,1) from the workload's noise stream (the last layer has z only: the other three are None).
+    `quantizer`, when given, is applied to every p (it is the caller's projection onto the grid; this
+    module does not define it). z[l], q[l] are read when layer l is reached, so a caller short of memory
+    may replace its arrays layer by layer while iterating."""
     rng = stream_rng(w, S_NOISE)
     L = len(z)
     s = np.float32(scale)
-    z_out, q_out, p_out, u_out = [], [], [], []
     for l in range(L):
         zl = z[l].astype(np.float32, copy=True)
         zl += s * _rms(zl) * noise_like(rng, zl.shape)
-        z_out.append(zl)
         if l < L - 1:
-            r = _rms(q[l])
             ql = q[l].astype(np.float32, copy=True)
+            r = _rms(ql)
             ql += s * r * noise_like(rng, ql.shape)
             pl = ql + s * r * noise_like(rng, ql.shape)
             if quantizer is not None:
                 pl = quantizer(pl)
             ul = (s * np.float32(w.nu) * r) * noise_like(rng, ql.shape)
+            yield l, zl, ql, pl.astype(np.float32, copy=False), ul.astype(np.float32, copy=False)
+        else:
+            yield l, zl, None, None, None
+
+
+def perturb_state(w: Workload, z, q, quantizer=None, scale: float = 0.1):
+    """perturb_layers collected into lists: (z, q, p_2..p_L, u_1..u_{L-1})."""
+    z_out, q_out, p_out, u_out = [], [], [], []
+    for l, zl, ql, pl, ul in perturb_layers(w, z, q, quantizer, scale):
+        z_out.append(zl)
+        if ql is not None:
             q_out.append(ql)
-            p_out.append(pl.astype(np.float32, copy=False))
-            u_out.append(ul.astype(np.float32, copy=False))
+            p_out.append(pl)
+            u_out.append(ul)
     return z_out, q_out, p_out, u_out
 
 
