@@ -14,7 +14,9 @@
  *    not thread-safe. After PDADMM_EHIP the context must be destroyed.
  *  - Kernels are enqueued on the stream given at init / in the call (a hipStream_t passed
  *    as void*; NULL = the default stream). pdadmm_iterate is asynchronous for pdADMM-G;
- *    for pdADMM-G-Q it waits for one 4-byte-per-layer flag copy per backtracking round.
+ *    for pdADMM-G-Q it waits for one 4-byte-per-layer flag copy per pair of backtracking rounds.
+ *  - Calls that have no context (or fail before one exists) leave their reason in a per-thread
+ *    text that pdadmm_last_error(NULL) returns.
  */
 #ifndef PDADMM_H
 #define PDADMM_H
@@ -62,6 +64,14 @@ typedef struct {
                               of the library's own, ordered against `stream` by events (helps small,
                               launch-bound models). Ignored for -Q, while pdadmm_timing is on and when
                               refresh_every > 0 */
+  int32_t bt_probe_backoff;/* -Q only. 1: the smaller start value tau/bt_eta is probed with the back-off described
+                              at bt_eta. 0: plain schedule, every p-update starts at the previous tau divided by
+                              bt_eta exactly as in pdADMM-G (one more product per update once tau has settled).
+                              Appendix A fixes only the acceptance condition; both schedules meet it */
+  int32_t risk_kind;       /* R(z_L; y) of Problem 2: 0 = cross-entropy (Section 5.1), z_L by FISTA;
+                              1 = least squares 1/2 ||z_j - e_{y_j}||^2 summed over labelled nodes (Section 3.1
+                              admits any convex continuous risk), z_L = (e_y + nu (W_L p_L + b_L)) / (1 + nu) in
+                              closed form (the z_L line of Appendix A 'update z' with this R) */
 } pdadmm_config;
 
 /* Terms of the augmented Lagrangian L_rho (Section 3.2). */
@@ -86,11 +96,12 @@ enum {
   PDADMM_VAR_TAU = 6,    /* tau_l, l = 2..L: one HOST double */
   PDADMM_VAR_THETA = 7,  /* theta_l, l = 1..L: one HOST double */
   PDADMM_VAR_PIDX = 8,   /* get only, -Q: indices of p_l in Delta, uint8 [N, n_{l-1}], l = 2..L */
-  /* read-only internals, for diagnostics */
+  /* (diagnostics) read-only internals */
   PDADMM_VAR_RESID = 9,  /* carried W_l p_l + b_l - z_l, [N, n_l] */
   PDADMM_VAR_GRAD_P = 10,/* last gradient of phi in p_l, [N, n_{l-1}], l = 2..L */
   PDADMM_VAR_GRAD_W = 11,/* last gradient of phi in W_l, [n_l, n_{l-1}] */
-  PDADMM_VAR_PROBE = 12  /* -Q, l = 2..L: two HOST int32 {wait, left}: back-off state of the tau search */
+  PDADMM_VAR_PROBE = 12  /* (diagnostics; part of a -Q checkpoint) l = 2..L: two HOST int32 {wait, left}: back-off
+                            state of the tau search */
 };
 
 /* Phases of Algorithm 1 as this library groups them (pdadmm_step_phase). */
@@ -129,8 +140,14 @@ pdadmm_status pdadmm_augment(int32_t n, int64_t nnz, const int32_t* rowptr, cons
 pdadmm_status pdadmm_quantize(const float* v, int64_t count, float lo, float hi, int32_t levels,
                               uint8_t* idx, float* val, void* stream);
 
+/* ------------------------------------------------------------------------------------------------
+ * DIAGNOSTICS. The entry points and variable kinds marked "diagnostics" below (pdadmm_gemm_nt/_tn,
+ * pdadmm_step_phase, pdadmm_timing/_read, PDADMM_VAR_RESID / GRAD_P / GRAD_W / PROBE) exist for the
+ * tests, the benchmark and the profiles; a training loop needs none of them.
+ * ------------------------------------------------------------------------------------------------ */
+
 /*
- * Dense fp32 products on the matrix cores, exposed for tests and micro-benchmarks of the kernels
+ * (diagnostics) Dense fp32 products on the matrix cores, exposed for tests and micro-benchmarks of the kernels
  * that carry the layer updates (the n_l x n_{l-1} x |V| products named in Section 3.2).
  *   pdadmm_gemm_nt: C[M,N] = A[M,K] * B[N,K]^T         (row-major, leading dimensions in floats)
  *   pdadmm_gemm_tn: C[M,N] = alpha * A[K,M]^T * B[K,N]  with the K range split in `splitk` parts
@@ -201,7 +218,7 @@ pdadmm_status pdadmm_get_var(pdadmm_ctx* ctx, int32_t kind, int32_t layer, void*
 /* Run n_iters iterations of Algorithm 1 (phases p, W, b, z, q, u; every phase over all layers). */
 pdadmm_status pdadmm_iterate(pdadmm_ctx* ctx, int32_t n_iters);
 
-/* Run one phase group of the current iteration (diagnostics; iterate = P, W, BZQU in this order). */
+/* (diagnostics) Run one phase group of the current iteration (iterate = P, W, BZQU in this order). */
 pdadmm_status pdadmm_step_phase(pdadmm_ctx* ctx, int32_t phase);
 
 /* Wait for all enqueued work; report sticky device-side errors (EBACKTRACK, ENONFINITE). */
@@ -246,7 +263,7 @@ pdadmm_status pdadmm_stats(pdadmm_ctx* ctx, double* tau, double* theta, int32_t*
 pdadmm_status pdadmm_plan_info(pdadmm_ctx* ctx, int32_t* fused_updates, int32_t* wgrad_split, int32_t* wtrial_split);
 
 /*
- * Per-launch timing with HIP events recorded on the context's stream around the launches of the
+ * (diagnostics) Per-launch timing with HIP events recorded on the context's stream around the launches of the
  * selected kernel classes (bit i of class_mask = class i; 0 switches timing off and drops pending
  * records). Classes: 0 p-gradient product (W^T r, fused gradient), 1 step-direction products
  * (W g / W d and G p), 2 W-gradient product (r p^T, split over nodes), 3 its partial-sum reduce,
@@ -259,6 +276,9 @@ pdadmm_status pdadmm_plan_info(pdadmm_ctx* ctx, int32_t* fused_updates, int32_t*
 pdadmm_status pdadmm_timing(pdadmm_ctx* ctx, uint32_t class_mask);
 pdadmm_status pdadmm_timing_read(pdadmm_ctx* ctx, double* ms, int64_t* launches, int32_t n_classes);
 
+/* Text of the last failure on this context; with ctx = NULL, of the calling thread's last failed call
+ * that had no context (pdadmm_init before a context exists, pdadmm_workspace_bytes, the stand-alone
+ * kernels). The pointer stays valid until the next failing call on the same context / thread. */
 const char* pdadmm_last_error(const pdadmm_ctx* ctx);
 void pdadmm_destroy(pdadmm_ctx* ctx);
 

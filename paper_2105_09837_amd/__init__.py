@@ -10,6 +10,6 @@ from .binding import (PdadmmError, Config, Context, load_library, library_path, 
                       pdadmm_get_var, pdadmm_iterate, pdadmm_step_phase, pdadmm_sync,
                       pdadmm_objective, pdadmm_residual, pdadmm_stats, pdadmm_plan_info, pdadmm_predict, pdadmm_destroy,
                       pdadmm_timing, pdadmm_timing_read, TIMING_CLASSES,
-                      VAR, PHASE)
+                      VAR, PHASE, RISK, thread_error)
 
 __all__ = [n for n in dir() if not n.startswith("_")]

@@ -35,14 +35,18 @@ class _CConfig(C.Structure):
                 ("q_lo", C.c_float), ("q_hi", C.c_float), ("q_levels", C.c_int32),
                 ("fista_iters", C.c_int32), ("bt_eta", C.c_float), ("tau0", C.c_float),
                 ("theta0", C.c_float), ("bt_max_trials", C.c_int32), ("refresh_every", C.c_int32),
-                ("leaky_slope", C.c_float), ("use_graph", C.c_int32)]
+                ("leaky_slope", C.c_float), ("use_graph", C.c_int32), ("bt_probe_backoff", C.c_int32),
+                ("risk_kind", C.c_int32)]
 
 
 class _CObjective(C.Structure):
     _fields_ = [(n, C.c_double) for n in ("risk", "lin_pen", "act_pen", "dual_lin", "dual_quad", "F", "L_rho")]
 
 
+RISK = {"ce": 0, "ls": 1}
+
 EXPORTS = ["pdadmm_normalize_adj", "pdadmm_augment", "pdadmm_quantize", "pdadmm_gemm_nt", "pdadmm_gemm_tn",
+
            "pdadmm_workspace_bytes", "pdadmm_init", "pdadmm_grow_layers", "pdadmm_set_var", "pdadmm_get_var", "pdadmm_iterate",
            "pdadmm_step_phase", "pdadmm_sync", "pdadmm_objective", "pdadmm_residual", "pdadmm_stats", "pdadmm_plan_info",
            "pdadmm_predict",
@@ -120,13 +124,16 @@ class Config:
     refresh_every: int = 0
     leaky_slope: float = 0.0
     use_graph: int = 0
+    bt_probe_backoff: int = 1
+    risk_kind: int = 0              # 0 cross-entropy, 1 least squares (see RISK)
 
     def to_c(self):
         dims = (C.c_int32 * len(self.dims))(*[int(d) for d in self.dims])
         cc = _CConfig(int(self.n_nodes), len(self.dims) - 1, C.cast(dims, C.POINTER(C.c_int32)),
                       float(self.rho), float(self.nu), int(self.quantize), float(self.q_lo), float(self.q_hi),
                       int(self.q_levels), int(self.fista_iters), float(self.bt_eta), float(self.tau0),
-                      float(self.theta0), int(self.bt_max_trials), int(self.refresh_every), float(self.leaky_slope), int(self.use_graph))
+                      float(self.theta0), int(self.bt_max_trials), int(self.refresh_every), float(self.leaky_slope), int(self.use_graph),
+                      int(self.bt_probe_backoff), int(self.risk_kind))
         cc._keep = dims
         return cc
 
@@ -153,9 +160,14 @@ class Context:
             pass
 
 
+def thread_error() -> str:
+    """Reason of this thread's last failed call that had no context."""
+    return (load_library().pdadmm_last_error(None) or b"").decode()
+
+
 def _check(code, where, ctx: Optional[Context] = None):
     if code != 0:
-        raise PdadmmError(code, where, ctx.last_error() if ctx is not None and ctx.handle else "")
+        raise PdadmmError(code, where, ctx.last_error() if ctx is not None and ctx.handle else thread_error())
 
 
 def _ptr(t):
@@ -270,7 +282,7 @@ def _new_context(cfg, X_aug, labels, W0, b0, train_mask, stream, workspace, sour
     cc = cfg.to_c()
     need = int(lib.pdadmm_workspace_bytes(C.byref(cc)))
     if need == 0:
-        raise PdadmmError(1, "pdadmm_workspace_bytes", "invalid configuration")
+        raise PdadmmError(1, "pdadmm_workspace_bytes", thread_error() or "invalid configuration")
     if workspace is None:
         workspace = torch.empty(need + 256, dtype=torch.uint8, device=X_aug.device)
     base = workspace.data_ptr()
@@ -293,7 +305,7 @@ def _new_context(cfg, X_aug, labels, W0, b0, train_mask, stream, workspace, sour
                                       _ptr(train_mask), source.handle, fl.ctypes.data, Wp, bp, _stream_ptr(stream))
     ctx = Context(handle, cfg, workspace, stream)
     if code != 0:
-        detail = ctx.last_error() if handle else ""
+        detail = ctx.last_error() if handle else thread_error()
         raise PdadmmError(code, what, detail)
     return ctx
 

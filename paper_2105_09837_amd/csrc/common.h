@@ -103,6 +103,8 @@ struct LayerScal {
   int probing;             // -Q: 1 if this update started at tau/eta (a probe of the smaller value)
   int probe_wait;          // -Q: iterations to wait after a rejected probe (1, 2, 4, ... kProbeCap)
   int probe_skip;          // -Q: iterations left until the next probe
+  int pad_;
+  long long products;      // -Q: trial products W d judged for this layer since init (one per backtracking trial)
 };
 constexpr int kProbeCap = 16;
 

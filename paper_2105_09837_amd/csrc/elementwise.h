@@ -315,6 +315,9 @@ __global__ __launch_bounds__(256) void zqu_kernel(const RowSeg* __restrict__ seg
   const int ld4 = S.ld / 4;
   const size_t base = (size_t)local * (256 * kZquUnroll) + threadIdx.x;
   f32x4 Rv[kZquUnroll], zo[kZquUnroll], qo[kZquUnroll], pn[kZquUnroll], uo[kZquUnroll], mm[kZquUnroll];
+  // pad columns (ld is the width rounded up to 4) hold zeros in every input and must stay zero: the closed forms
+  // map zeros to zeros, only the projection of q does not when 0 is no member of Delta
+  const bool ragged = qgrid.levels > 0 && S.ncols != S.ld;
 #pragma unroll
   for (int k = 0; k < kZquUnroll; ++k) {
     const size_t i = base + (size_t)k * 256;
@@ -343,6 +346,12 @@ __global__ __launch_bounds__(256) void zqu_kernel(const RowSeg* __restrict__ seg
         const float rr = pn[k][c] - qq;
         qn[c] = qq;
         un[c] = uo[k][c] + rho * rr;
+      }
+      if (ragged) {
+        const int col0 = (int)(i % (size_t)ld4) * 4;
+#pragma unroll
+        for (int c = 0; c < 4; ++c)
+          if (col0 + c >= S.ncols) { qn[c] = 0.0f; un[c] = 0.0f; }
       }
       stream_store(reinterpret_cast<f32x4*>(S.z) + i, zn);
       stream_store(reinterpret_cast<f32x4*>(S.R) + i, Rn);
@@ -423,6 +432,24 @@ __global__ __launch_bounds__(256) void fista_kernel(float* __restrict__ R, float
   }
 }
 
+// z_L-update for the least-squares risk R(z; y) = 1/2 sum_j ||z_j - e_{y_j}||^2 (Section 3.1 admits any convex
+// continuous risk): the subproblem 1/2 ||z - e_y||^2 + (nu/2)||z - a||^2 of Appendix A 'update z' (l = L) has
+// the closed form z = (e_y + nu a) / (1 + nu); unlabelled nodes take z = a. One thread per element.
+__global__ __launch_bounds__(256) void zlast_ls_kernel(float* __restrict__ R, float* __restrict__ z,
+                                                       const float* __restrict__ m, const int* __restrict__ y,
+                                                       const uint8_t* __restrict__ mask, int rows, int C, int ld,
+                                                       float nu) {
+  const size_t e = (size_t)blockIdx.x * 256 + threadIdx.x;
+  const int node = (int)(e / (size_t)C), c = (int)(e % (size_t)C);
+  if (node >= rows) return;
+  const size_t i = (size_t)node * ld + c;
+  const float a = R[i] - m[c] + z[i];
+  const bool lab = mask ? mask[node] != 0 : true;
+  const float zn = lab ? ((c == y[node] ? 1.0f : 0.0f) + nu * a) / (1.0f + nu) : a;
+  z[i] = zn;
+  R[i] = a - zn;
+}
+
 // ------------------------------------------------------------------------------------------
 // pdADMM-G-Q p-update (Appendix B): p <- argmin_{delta in Delta} |delta - (p - g/tau)|.
 // One backtracking trial: candidate indices, d = candidate - p, per-block ||d||^2.
@@ -498,7 +525,7 @@ __global__ __launch_bounds__(256) void quant_trial_kernel(const QuantSeg* __rest
 // phase 1: judge the trial in flight.
 __global__ __launch_bounds__(256) void select_quant_kernel(const SelectDesc* __restrict__ descs, LayerScal* scal,
                                                            int phase, float rho, float nu, float eta,
-                                                           int max_trials, int* err, int* flags) {
+                                                           int max_trials, int backoff, int* err, int* flags) {
   __shared__ double red[4];
   const SelectDesc D = descs[blockIdx.x];
   LayerScal& sc = scal[D.layer];
@@ -511,8 +538,9 @@ __global__ __launch_bounds__(256) void select_quant_kernel(const SelectDesc* __r
     sc.active = 0;
     if (!(sg == sg) || sg > 1.7e308) atomicOr(err, kErrNonFinite);
     else if (sg > 0.0) {
-      // every trial costs a product W d: tau/eta is only probed when no rejected probe is being waited out
-      const int probing = sc.probe_skip == 0;
+      // every trial costs a product W d: with the back-off schedule tau/eta is only probed when no rejected
+      // probe is being waited out; the plain schedule starts every update at tau/eta
+      const int probing = !backoff || sc.probe_skip == 0;
       if (!probing) sc.probe_skip -= 1;
       sc.probing = probing;
       sc.active = 1;
@@ -527,6 +555,7 @@ __global__ __launch_bounds__(256) void select_quant_kernel(const SelectDesc* __r
   const double st = fixed_order_sum(D.part_t, D.nt, D.stride_t, red);
   if (threadIdx.x != 0) return;
   sc.norm_t = st;
+  sc.products += 1;
   const double t = (double)sc.trial_t;
   if (!(sd == sd) || !(st == st) || sd > 1.7e308 || st > 1.7e308) {
     atomicOr(err, kErrNonFinite);
@@ -536,7 +565,7 @@ __global__ __launch_bounds__(256) void select_quant_kernel(const SelectDesc* __r
     sc.tau = t;
     sc.inv_tau = 1.0f;     // marks "a step was accepted"
     sc.active = 0;
-    if (sc.probing) {      // accepted at once: probe again next time; else back off 1, 2, 4, ... iterations
+    if (backoff && sc.probing) {   // accepted at once: probe again next time; else back off 1, 2, 4, ... iterations
       if (sc.p_trials == 1) sc.probe_wait = 0;
       else {
         sc.probe_wait = min(max(1, 2 * sc.probe_wait), kProbeCap);
@@ -663,20 +692,29 @@ __global__ __launch_bounds__(256) void pair_reduce_kernel(const PairSeg* __restr
   }
 }
 
-// R(z_L; y) = sum over labelled nodes of logsumexp(z) - z_y. One thread per node.
+// R(z_L; y) summed over labelled nodes: logsumexp(z) - z_y (cross-entropy, kind 0) or
+// 1/2 ||z - e_y||^2 (least squares, kind 1). One thread per node.
 __global__ __launch_bounds__(256) void risk_kernel(const float* __restrict__ z, const int* __restrict__ y,
                                                    const uint8_t* __restrict__ mask, int rows, int C, int ld,
-                                                   double* __restrict__ part) {
+                                                   int kind, double* __restrict__ part) {
   __shared__ double red[4];
   const int node = blockIdx.x * 256 + threadIdx.x;
   double v = 0.0;
   if (node < rows && (!mask || mask[node])) {
     const float* zr = z + (size_t)node * ld;
-    float mx = zr[0];
-    for (int c = 1; c < C; ++c) mx = fmaxf(mx, zr[c]);
-    double s = 0.0;
-    for (int c = 0; c < C; ++c) s += exp((double)zr[c] - (double)mx);
-    v = (double)mx + log(s) - (double)zr[y[node]];
+    if (kind == 0) {
+      float mx = zr[0];
+      for (int c = 1; c < C; ++c) mx = fmaxf(mx, zr[c]);
+      double s = 0.0;
+      for (int c = 0; c < C; ++c) s += exp((double)zr[c] - (double)mx);
+      v = (double)mx + log(s) - (double)zr[y[node]];
+    } else {
+      const int label = y[node];
+      for (int c = 0; c < C; ++c) {
+        const double d = (double)zr[c] - (c == label ? 1.0 : 0.0);
+        v += 0.5 * d * d;
+      }
+    }
   }
   const double t = block_sum_256(v, red);
   if (threadIdx.x == 0) part[blockIdx.x] = t;

@@ -154,10 +154,16 @@ struct pdadmm_ctx {
 
 namespace {
 
+// Reason of the calling thread's last failed call that had no context (pdadmm_last_error(NULL)).
+thread_local std::string g_thread_error;
+
 pdadmm_status fail(pdadmm_ctx* c, pdadmm_status s, const std::string& m) {
   if (c) c->msg = m;
+  else g_thread_error = m;
   return s;
 }
+
+
 
 #define HIP_TRY(ctx, call)                                                                   \
   do {                                                                                       \
@@ -239,6 +245,8 @@ bool config_ok(const pdadmm_config* c, std::string* why) {
   if (c->refresh_every < 0) return bad("refresh_every < 0");
   if (!(c->leaky_slope >= 0.f) || !(c->leaky_slope < 1.f)) return bad("leaky_slope must be in [0, 1)");
   if (c->use_graph != 0 && c->use_graph != 1) return bad("use_graph must be 0 or 1");
+  if (c->bt_probe_backoff != 0 && c->bt_probe_backoff != 1) return bad("bt_probe_backoff must be 0 or 1");
+  if (c->risk_kind != 0 && c->risk_kind != 1) return bad("risk_kind must be 0 (cross-entropy) or 1 (least squares)");
   return true;
 }
 
@@ -637,28 +645,30 @@ pdadmm_status phase_p(pdadmm_ctx* c) {
     }
     return PDADMM_OK;
   }
-  // -Q: trial rounds; the host only learns which layers are still searching
+  // -Q: trial rounds. Every kernel of a round leaves at once for layers whose search has ended (LayerScal::active),
+  // so rounds can be enqueued without knowing whether they are needed: two rounds go out per read of the flags
+  // (with the back-off schedule one round settles most updates, with the plain schedule two), and the host only
+  // learns whether any layer is still searching.
+  const int backoff = g.bt_probe_backoff;
   { TIMED(c, kClsSelect); hipLaunchKernelGGL(select_quant_kernel, dim3(L - 1), dim3(256), 0, c->stream, c->sel_p, c->scal, 0, g.rho, g.nu,
-                     g.bt_eta, g.bt_max_trials, c->err, c->flags); }
+                     g.bt_eta, g.bt_max_trials, backoff, c->err, c->flags); }
   LAUNCH_CHECK(c, "select quant arm");
-  for (int round = 0; round <= g.bt_max_trials; ++round) {
+  constexpr int kRoundsPerRead = 2;
+  for (int round = 0; round <= g.bt_max_trials; round += kRoundsPerRead) {
+    for (int r = 0; r < kRoundsPerRead; ++r) {
+      { TIMED(c, kClsQuantTrial); launch_group(c, c->g_quant, quant_trial_kernel, (const LayerScal*)c->scal, c->grid); }
+      LAUNCH_CHECK(c, "quant trial");
+      { TIMED(c, kClsGemmTrial); launch_gemm<true, EpiStoreNorm, true>(c, c->g_ptrial, 1); }
+      LAUNCH_CHECK(c, "gemm qtrial");
+      { TIMED(c, kClsSelect); hipLaunchKernelGGL(select_quant_kernel, dim3(L - 1), dim3(256), 0, c->stream, c->sel_q, c->scal, 1, g.rho, g.nu,
+                         g.bt_eta, g.bt_max_trials, backoff, c->err, c->flags); }
+      LAUNCH_CHECK(c, "select quant judge");
+    }
     HIP_TRY(c, hipMemcpyAsync(c->h_flags, c->flags, sizeof(int) * L, hipMemcpyDeviceToHost, c->stream));
     HIP_TRY(c, hipStreamSynchronize(c->stream));
     bool any = false;
-    for (int i = 1; i < L; ++i) {
-      if (c->h_flags[i] != 0) {
-        any = true;
-        ++c->p_products[i];      // this layer's trial product runs in the launch below
-      }
-    }
+    for (int i = 1; i < L; ++i) any = any || c->h_flags[i] != 0;
     if (!any) break;
-    { TIMED(c, kClsQuantTrial); launch_group(c, c->g_quant, quant_trial_kernel, (const LayerScal*)c->scal, c->grid); }
-    LAUNCH_CHECK(c, "quant trial");
-    { TIMED(c, kClsGemmTrial); launch_gemm<true, EpiStoreNorm, true>(c, c->g_ptrial, 1); }
-    LAUNCH_CHECK(c, "gemm qtrial");
-    { TIMED(c, kClsSelect); hipLaunchKernelGGL(select_quant_kernel, dim3(L - 1), dim3(256), 0, c->stream, c->sel_q, c->scal, 1, g.rho, g.nu,
-                       g.bt_eta, g.bt_max_trials, c->err, c->flags); }
-    LAUNCH_CHECK(c, "select quant judge");
   }
   { TIMED(c, kClsQuantApply); launch_group(c, c->g_quant, quant_apply_kernel, (const LayerScal*)c->scal, c->grid); }
   LAUNCH_CHECK(c, "quant apply");
@@ -694,9 +704,18 @@ pdadmm_status phase_w(pdadmm_ctx* c) {
   return PDADMM_OK;
 }
 
+// z_L-update (Appendix A 'update z', l = L): FISTA for the cross-entropy risk, closed form for least squares.
 pdadmm_status launch_fista(pdadmm_ctx* c) {
   const LayerBufs& b = c->lay[c->L - 1];
   const int C = b.n_out;
+  if (c->cfg.risk_kind == 1) {
+    TIMED(c, kClsFista);
+    const size_t elems = (size_t)c->N * C;
+    hipLaunchKernelGGL(zlast_ls_kernel, dim3((unsigned)((elems + 255) / 256)), dim3(256), 0, c->stream, b.R, b.z, b.m,
+                       c->labels, (const uint8_t*)c->mask, c->N, C, b.ld_out, c->cfg.nu);
+    LAUNCH_CHECK(c, "z_L least squares");
+    return PDADMM_OK;
+  }
   int G = 1;
   while (G < C && G < 64) G <<= 1;
   const int E = cdiv(C, G);
@@ -918,7 +937,11 @@ pdadmm_status pdadmm_gemm_tn(int32_t M, int32_t N, int32_t K, float alpha, const
 }
 
 size_t pdadmm_workspace_bytes(const pdadmm_config* cfg) {
-  if (!config_ok(cfg, nullptr)) return 0;
+  std::string why;
+  if (!config_ok(cfg, &why)) {
+    fail(nullptr, PDADMM_EINVAL, "config: " + why);
+    return 0;
+  }
   pdadmm_ctx tmp;
   tmp.cfg = *cfg;
   tmp.N = cfg->n_nodes;
@@ -937,25 +960,27 @@ pdadmm_status init_common(pdadmm_ctx** out, const pdadmm_config* cfg, void* work
                           const float* X_aug, const int32_t* labels, const uint8_t* train_mask,
                           const float* const* W0, const float* const* b0, void* stream, pdadmm_ctx* from,
                           const int32_t* from_layer) {
-  if (!out) return PDADMM_EINVAL;
+  if (!out) return fail(nullptr, PDADMM_EINVAL, "out is NULL");
   *out = nullptr;
   std::string why;
-  if (!config_ok(cfg, &why)) return PDADMM_EINVAL;
-  if (!workspace || !X_aug || !labels) return PDADMM_EINVAL;
-  if (reinterpret_cast<uintptr_t>(workspace) & 255) return PDADMM_EINVAL;
-  if (from && !from_layer) return PDADMM_EINVAL;
+  if (!config_ok(cfg, &why)) return fail(nullptr, PDADMM_EINVAL, "config: " + why);
+  if (!workspace || !X_aug || !labels) return fail(nullptr, PDADMM_EINVAL, "workspace, X_aug or labels is NULL");
+  if (reinterpret_cast<uintptr_t>(workspace) & 255) return fail(nullptr, PDADMM_EINVAL, "workspace is not 256-byte aligned");
+  if (from && !from_layer) return fail(nullptr, PDADMM_EINVAL, "from_layer is NULL");
   for (int i = 0; i < cfg->n_layers; ++i) {
     const int src = from ? from_layer[i] : 0;
+    const std::string lay = "layer " + std::to_string(i + 1) + ": ";
     if (src == 0) {
-      if (!W0 || !b0 || !W0[i] || !b0[i]) return PDADMM_EINVAL;
+      if (!W0 || !b0 || !W0[i] || !b0[i]) return fail(nullptr, PDADMM_EINVAL, lay + "no starting W, b given");
     } else {
-      if (src < 0 || src > from->L) return PDADMM_EINVAL;
-      if (from->dims[src - 1] != cfg->dims[i] || from->dims[src] != cfg->dims[i + 1]) return PDADMM_EINVAL;
+      if (src < 0 || src > from->L) return fail(nullptr, PDADMM_EINVAL, lay + "source layer out of range");
+      if (from->dims[src - 1] != cfg->dims[i] || from->dims[src] != cfg->dims[i + 1])
+        return fail(nullptr, PDADMM_EINVAL, lay + "source layer has another shape");
     }
   }
   if (from) {   // its pending work writes the arrays copied below
-    if (from->N != cfg->n_nodes) return PDADMM_EINVAL;
-    if (hipStreamSynchronize(from->stream) != hipSuccess) return PDADMM_EHIP;
+    if (from->N != cfg->n_nodes) return fail(nullptr, PDADMM_EINVAL, "source context has another n_nodes");
+    if (hipStreamSynchronize(from->stream) != hipSuccess) return fail(nullptr, PDADMM_EHIP, "synchronising the source context failed");
   }
   pdadmm_ctx* c = new pdadmm_ctx;
   c->cfg = *cfg;
@@ -969,7 +994,8 @@ pdadmm_status init_common(pdadmm_ctx** out, const pdadmm_config* cfg, void* work
   const size_t need = plan(c, nullptr);
   if (workspace_bytes < need) {
     delete c;
-    return PDADMM_ENOMEM;
+    return fail(nullptr, PDADMM_ENOMEM, "workspace holds " + std::to_string(workspace_bytes) + " bytes, " +
+                                            std::to_string(need) + " are needed");
   }
   plan(c, workspace);
   *out = c;   // from here on errors are reported through the context; the caller destroys it
@@ -1035,7 +1061,7 @@ extern "C" {
 pdadmm_status pdadmm_init(pdadmm_ctx** out, const pdadmm_config* cfg, void* workspace, size_t workspace_bytes,
                           const float* X_aug, const int32_t* labels, const uint8_t* train_mask,
                           const float* const* W0, const float* const* b0, void* stream) {
-  if (!W0 || !b0) return PDADMM_EINVAL;
+  if (!W0 || !b0) return fail(nullptr, PDADMM_EINVAL, "W0 or b0 is NULL");
   return init_common(out, cfg, workspace, workspace_bytes, X_aug, labels, train_mask, W0, b0, stream, nullptr, nullptr);
 }
 
@@ -1043,7 +1069,7 @@ pdadmm_status pdadmm_grow_layers(pdadmm_ctx** out, const pdadmm_config* cfg, voi
                                  const float* X_aug, const int32_t* labels, const uint8_t* train_mask,
                                  pdadmm_ctx* from, const int32_t* from_layer, const float* const* W0,
                                  const float* const* b0, void* stream) {
-  if (!from || !from_layer) return PDADMM_EINVAL;
+  if (!from || !from_layer) return fail(nullptr, PDADMM_EINVAL, "from or from_layer is NULL");
   return init_common(out, cfg, workspace, workspace_bytes, X_aug, labels, train_mask, W0, b0, stream, from, from_layer);
 }
 
@@ -1155,8 +1181,12 @@ static pdadmm_status iterate_graph(pdadmm_ctx* c, int32_t n_iters) {
     if (s == PDADMM_OK) s = phase_bzqu(c);
     c->stream = user;
     const hipError_t e = hipStreamEndCapture(c->gstream, &c->graph);
-    if (s != PDADMM_OK) return s;
-    if (e != hipSuccess) return fail(c, PDADMM_EHIP, std::string("hipStreamEndCapture: ") + hipGetErrorString(e));
+    if (s != PDADMM_OK || e != hipSuccess) {     // a phase failed while recording: drop what was captured
+      if (c->graph) (void)hipGraphDestroy(c->graph);
+      c->graph = nullptr;
+      if (s != PDADMM_OK) return s;
+      return fail(c, PDADMM_EHIP, std::string("hipStreamEndCapture: ") + hipGetErrorString(e));
+    }
     HIP_TRY(c, hipGraphInstantiate(&c->graph_exec, c->graph, nullptr, nullptr, 0));
     // capture recorded the launches without running them: the product counters were advanced once
     for (int i = 1; i < c->L; ++i) --c->p_products[i];
@@ -1252,7 +1282,7 @@ pdadmm_status pdadmm_objective(pdadmm_ctx* c, pdadmm_objective_terms* out) {
   if ((s = pair_sums(c, &act, &dl, &dq)) != PDADMM_OK) return s;
   const LayerBufs& bl = c->lay[c->L - 1];
   hipLaunchKernelGGL(risk_kernel, dim3(c->risk_blocks), dim3(256), 0, c->stream, bl.z, c->labels, c->mask, c->N,
-                     bl.n_out, bl.ld_out, c->riskpart);
+                     bl.n_out, bl.ld_out, c->cfg.risk_kind, c->riskpart);
   LAUNCH_CHECK(c, "risk");
   if ((s = sum_partials(c, c->riskpart, c->risk_blocks, &h)) != PDADMM_OK) return s;
   double risk = 0;
@@ -1294,7 +1324,7 @@ pdadmm_status pdadmm_stats(pdadmm_ctx* c, double* tau, double* theta, int32_t* p
     if (theta) theta[i] = hs[i].theta;
     if (p_trials) p_trials[i] = hs[i].p_trials;
     if (w_trials) w_trials[i] = hs[i].w_trials;
-    if (p_products) p_products[i] = c->p_products[i];
+    if (p_products) p_products[i] = c->cfg.quantize ? hs[i].products : c->p_products[i];
   }
   if (r_drift) {
     double lin = 0, drift = 0;
@@ -1386,7 +1416,7 @@ pdadmm_status pdadmm_timing_read(pdadmm_ctx* c, double* ms, int64_t* launches, i
   return PDADMM_OK;
 }
 
-const char* pdadmm_last_error(const pdadmm_ctx* c) { return c ? c->msg.c_str() : "context is NULL"; }
+const char* pdadmm_last_error(const pdadmm_ctx* c) { return c ? c->msg.c_str() : g_thread_error.c_str(); }
 
 void pdadmm_destroy(pdadmm_ctx* c) {
   if (!c) return;

@@ -12,7 +12,7 @@ def config_of(w, **kw) -> P.Config:
     q = w.quant
     base = dict(n_nodes=w.n_nodes, dims=list(w.dims), rho=w.rho, nu=w.nu, quantize=(2 if w.quant_q else 1) if q else 0,
                 q_lo=q[0] if q else -1.0, q_hi=q[1] if q else 1.0, q_levels=q[2] if q else 256,
-                leaky_slope=w.slope)
+                leaky_slope=w.slope, risk_kind=P.RISK[w.risk])
     base.update(kw)
     return P.Config(**base)
 
@@ -22,6 +22,9 @@ def gpu_context(w, inp, st=None, **kw):
     copied in so that both sides start from bit-identical fp32 values."""
     import torch
     dev = torch.device("cuda:0")
+    if st is not None:      # the conventions the oracle state runs under
+        kw.setdefault("bt_probe_backoff", int(st.probe_backoff))
+        kw.setdefault("risk_kind", P.RISK[st.risk_kind])
     cfg = config_of(w, **kw)
     Xa = torch.from_numpy(inp["X_aug"]).to(dev)
     y = torch.from_numpy(inp["y"]).to(dev)
@@ -129,6 +132,128 @@ def compare_state(ctx, st, tol, what="", before=None):
     return ok, worst, "\n".join(lines)
 
 
+EPS32 = float(np.finfo(np.float32).eps)
+
+
+def quant_flips(P_, ctx, before, st, what="", layers=None, layer_of=None, adopt=True):
+    """-Q: indices of every p_l (l >= 2) against the oracle's. They must be equal except where the value
+    that is projected, v = p - grad/tau (Appendix B), lies within rounding of the midpoint between two
+    neighbouring members of Delta: there fp32 products (the HIP path) and fp64 products (the oracle) may
+    fall on different sides. Every differing index is checked for exactly that: one level apart, and the
+    oracle's v within `slack` of the midpoint, where slack bounds the rounding error of v as the HIP path
+    forms it: 4 eps32 times the sum of the magnitudes that enter v (the sums of absolute values behind the
+    dot products W p and W^T r included, so the bound already grows with their length; at full size the worst
+    case seen is 0.1 of this slack).
+    `before` is the oracle state the update started from, `st` the state after it; `layers` the positions
+    in these states to check (default: all but the first), `layer_of` maps a position to the paper's layer
+    number in the context (default: position + 1).
+    At such an element both members are correct results of the update (each is the nearest member of the
+    value its side computed). With adopt=True the oracle state takes the HIP path's member there, so that
+    everything computed from p afterwards (W, b, z, q, u of the same iteration) can be compared with no
+    further allowance. Returns (number of differing indices, number of indices, worst distance / slack)."""
+    g = st.grid
+    mem = g.members().astype(F64)
+    bad = total = 0
+    worst = 0.0
+    for i in (layers if layers is not None else range(1, st.L)):
+        lay = layer_of(i) if layer_of is not None else i + 1
+        idx = P_.pdadmm_get_var(ctx, P_.VAR.PIDX, lay).astype(np.int32)
+        gp = P_.pdadmm_get_var(ctx, P_.VAR.P, lay)
+        assert np.array_equal(gp.view(np.uint32), g.members()[idx].view(np.uint32)), f"{what} p_{i + 1} not in Delta"
+        ref = O.quantize(st.p[i], g)[0]
+        total += idx.size
+        rows, cols = np.nonzero(idx != ref)
+        if rows.size == 0:
+            continue
+        bad += rows.size
+        assert np.all(np.abs(idx[rows, cols] - ref[rows, cols]) == 1), f"{what} p_{i + 1}: an index is more than one level off"
+        p, W, b, z = (np.asarray(a, dtype=F64) for a in (before.p[i], before.W[i], before.b[i], before.z[i]))
+        q, u = np.asarray(before.q[i - 1], dtype=F64), np.asarray(before.u[i - 1], dtype=F64)
+        tau = st.tau[i]
+        pr = p[rows]
+        r = pr @ W.T + b - z[rows]                                              # [k, n_out]
+        mag_r = np.abs(pr) @ np.abs(W).T + np.abs(b) + np.abs(z[rows])
+        Wc = W[:, cols]                                                          # [n_out, k]
+        grad = st.nu * np.einsum("kj,jk->k", r, Wc) + u[rows, cols] + st.rho * (p[rows, cols] - q[rows, cols])
+        mag_g = (st.nu * np.einsum("kj,jk->k", mag_r + np.abs(r), np.abs(Wc)) + np.abs(u[rows, cols])
+                 + st.rho * (np.abs(p[rows, cols]) + np.abs(q[rows, cols])))
+        v = p[rows, cols] - grad / tau
+        mid = 0.5 * (mem[idx[rows, cols]] + mem[ref[rows, cols]])
+        slack = 4.0 * EPS32 * (np.abs(p[rows, cols]) + mag_g / tau + np.abs(g.lo) + np.abs(v))
+        ratio = np.abs(v - mid) / slack
+        worst = max(worst, float(ratio.max()))
+        assert np.all(ratio <= 1.0), (f"{what} p_{i + 1}: {int((ratio > 1).sum())} of {rows.size} differing indices are not at a "
+                                      f"midpoint of Delta (worst distance / slack = {ratio.max():.2f})")
+        if adopt:
+            new_p = np.array(st.p[i], copy=True)
+            new_p[rows, cols] = mem[idx[rows, cols]].astype(new_p.dtype)
+            st.p[i] = new_p
+    return bad, total, worst
+
+
+def q_flips(P_, ctx, before, st, what=""):
+    """Variant with q on Delta as well (Appendix B, last paragraph): the q-update projects
+    v = (rho p_{l+1} + u_l + nu f(z_l)) / (rho + nu), so it has the same midpoint cases as the p-update.
+    `before` is the oracle state ahead of the b/z/q/u phase (it holds the u the update read), `st` the state
+    after it. Every q value of the HIP path must be a member of Delta; where it is not the oracle's member it
+    must be the neighbouring one, with the oracle's v within rounding (4 eps32 times the magnitudes that
+    enter v, including those behind W p + b, from which z_l comes) of the midpoint between the two. There the
+    oracle state takes the HIP path's member and the dual step u_l <- u_l + rho (p_{l+1} - q_l) is redone
+    with it. Returns the number of such elements."""
+    g = st.grid
+    mem32 = g.members()
+    mem = mem32.astype(F64)
+    step = float(g.step32)
+    bad = 0
+    for i in range(st.L - 1):
+        gq = P_.pdadmm_get_var(ctx, P_.VAR.Q, i + 1)
+        assert np.isin(gq, mem32).all(), f"{what} q_{i + 1} not in Delta"
+        rows, cols = np.nonzero(gq != st.q[i].astype(F32))
+        if rows.size == 0:
+            continue
+        bad += rows.size
+        mine, theirs = gq[rows, cols].astype(F64), np.asarray(st.q[i], dtype=F64)[rows, cols]
+        assert np.all(np.abs(np.abs(mine - theirs) - step) <= 1e-4 * step), f"{what} q_{i + 1}: more than one level off"
+        p_next, u_old = np.asarray(st.p[i + 1], dtype=F64)[rows, cols], np.asarray(before.u[i], dtype=F64)[rows, cols]
+        fz = O.act(np.asarray(st.z[i], dtype=F64)[rows, cols], st.slope)
+        v = (st.rho * p_next + u_old + st.nu * fz) / (st.rho + st.nu)
+        mag_a = ((np.abs(np.asarray(st.p[i], dtype=F64)[rows]) * np.abs(np.asarray(st.W[i], dtype=F64)[cols])).sum(axis=1)
+                 + np.abs(np.asarray(st.b[i], dtype=F64)[cols]) + 2.0 * np.abs(np.asarray(before.z[i], dtype=F64)[rows, cols]))
+        slack = 4.0 * EPS32 * ((st.rho * np.abs(p_next) + np.abs(u_old) + st.nu * (np.abs(fz) + mag_a)) / (st.rho + st.nu)
+                                + np.abs(g.lo) + np.abs(v))
+        ratio = np.abs(v - 0.5 * (mine + theirs)) / slack
+        assert np.all(ratio <= 1.0), (f"{what} q_{i + 1}: {int((ratio > 1).sum())} of {rows.size} differing values are not at a "
+                                      f"midpoint of Delta (worst distance / slack = {ratio.max():.2f})")
+        new_q = np.array(st.q[i], copy=True)
+        new_q[rows, cols] = mine
+        new_u = np.array(st.u[i], copy=True)
+        new_u[rows, cols] = u_old + st.rho * (p_next - mine)
+        st.q[i], st.u[i] = new_q, new_u
+    return bad
+
+
+def oracle_state_from_gpu(ctx, like):
+    """An oracle state holding the HIP path's current variables (fp32 values in fp64 arrays), step sizes and
+    probe state, with the conventions of `like`."""
+    st = like.copy()
+    s = P.pdadmm_stats(ctx)
+    for i in range(st.L):
+        l = i + 1
+        st.W[i] = P.pdadmm_get_var(ctx, P.VAR.W, l).astype(F64)
+        st.b[i] = P.pdadmm_get_var(ctx, P.VAR.B, l).astype(F64)
+        st.z[i] = P.pdadmm_get_var(ctx, P.VAR.Z, l).astype(F64)
+        st.theta[i] = float(s["theta"][i])
+        if i >= 1:
+            st.p[i] = P.pdadmm_get_var(ctx, P.VAR.P, l).astype(F64)
+            st.tau[i] = float(s["tau"][i])
+            if st.grid is not None:
+                st.p_wait[i], st.p_skip[i] = P.pdadmm_get_var(ctx, P.VAR.PROBE, l)
+        if i < st.L - 1:
+            st.q[i] = P.pdadmm_get_var(ctx, P.VAR.Q, l).astype(F64)
+            st.u[i] = P.pdadmm_get_var(ctx, P.VAR.U, l).astype(F64)
+    return st
+
+
 def step_sizes(ctx):
     s = P.pdadmm_stats(ctx)
     return s["tau"], s["theta"], s["p_trials"], s["w_trials"]
@@ -152,3 +277,30 @@ def oracle_phase(st, phase):
             O.update_q(st, i)
         for i in range(L - 1):
             O.update_u(st, i)
+
+
+def forward_flips(P_, ctx, ref, what=""):
+    """-Q forward-consistent start (p_{l+1} = nearest member of Delta to f(z_l), layer after layer): the HIP
+    path's indices against the oracle's. The pass is node-wise, so an index that falls on the other side of
+    a midpoint changes that node's rows in all deeper layers and nothing else. Walking down the layers,
+    every node that is still clean must either agree or sit within rounding (4 eps32 times the magnitudes
+    behind W p + b) of a midpoint, after which it is left out. Returns the mask of nodes left out."""
+    g = ref.grid
+    mem = g.members().astype(F64)
+    N = ref.p[0].shape[0]
+    dirty = np.zeros(N, dtype=bool)
+    for i in range(ref.L - 1):
+        idx = P_.pdadmm_get_var(ctx, P_.VAR.PIDX, i + 2).astype(np.int32)
+        gp = P_.pdadmm_get_var(ctx, P_.VAR.P, i + 2)
+        assert np.array_equal(gp.view(np.uint32), g.members()[idx].view(np.uint32)), f"{what} p_{i + 2} not in Delta"
+        want = O.quantize(ref.p[i + 1], g)[0]
+        rows, cols = np.nonzero((idx != want) & ~dirty[:, None])
+        if rows.size:
+            assert np.all(np.abs(idx[rows, cols] - want[rows, cols]) == 1)
+            v = O.act(ref.z[i][rows, cols], ref.slope)
+            mag = (np.abs(ref.p[i][rows]) * np.abs(ref.W[i][cols])).sum(axis=1) + np.abs(ref.b[i][cols])
+            mid = 0.5 * (mem[idx[rows, cols]] + mem[want[rows, cols]])
+            slack = 4.0 * EPS32 * (mag + np.abs(v) + np.abs(g.lo))
+            assert np.all(np.abs(v - mid) <= slack), f"{what} p_{i + 2}: a differing index is not at a midpoint of Delta"
+            dirty[np.unique(rows)] = True
+    return dirty

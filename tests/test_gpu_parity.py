@@ -128,20 +128,22 @@ def test_forward_init_matches_oracle(env, name):
     inp = oracle_inputs(w)
     st = O.init_forward(inp["X_aug"], inp["W"], inp["b"], inp["y"], w.rho, w.nu, grid=grid_of(w))
     ctx = H.gpu_context(w, inp)
+    # -Q: nodes at which an index fell on the other side of a midpoint of Delta (validated) are left out below
+    dirty = H.forward_flips(P, ctx, st, what=w.name) if w.quant is not None else np.zeros(w.n_nodes, dtype=bool)
+    _say(f"  nodes left out after a midpoint flip in the forward pass: {int(dirty.sum())} of {w.n_nodes}")
+    assert dirty.mean() <= 0.01
+    keep = ~dirty
     for i in range(st.L):
         l = i + 1
-        assert rel_l2(P.pdadmm_get_var(ctx, P.VAR.Z, l), st.z[i]) <= 1e-5
+        assert rel_l2(P.pdadmm_get_var(ctx, P.VAR.Z, l)[keep], st.z[i][keep]) <= 1e-5
         if i < st.L - 1:
-            assert rel_l2(P.pdadmm_get_var(ctx, P.VAR.Q, l), st.q[i]) <= 1e-5
+            assert rel_l2(P.pdadmm_get_var(ctx, P.VAR.Q, l)[keep], st.q[i][keep]) <= 1e-5
             assert np.all(P.pdadmm_get_var(ctx, P.VAR.U, l) == 0)
             gp = P.pdadmm_get_var(ctx, P.VAR.P, l + 1)
             if w.quant is None:
                 assert rel_l2(gp, st.p[i + 1]) <= 1e-5
             else:
-                mem = grid_of(w).members()
-                assert np.isin(gp, mem).all()
-                assert np.mean(gp == st.p[i + 1].astype(F32)) > 0.995
-                assert np.max(np.abs(gp - st.p[i + 1])) <= 1.0001 * float(grid_of(w).step32)
+                assert np.array_equal(gp[keep], st.p[i + 1][keep].astype(F32))     # bit for bit
     # a forward-consistent start has a vanishing carried residual
     r = P.pdadmm_get_var(ctx, P.VAR.RESID, 1)
     assert np.max(np.abs(r)) <= 1e-4 * max(1.0, np.max(np.abs(st.z[0])))
@@ -155,6 +157,10 @@ CASES = {
     "C4-small": lambda: scaled_workload("C4", 600, hidden=36, n_layers=12, feat_dim=12),
     "C5-small": lambda: scaled_workload("C5", 1300, hidden=136, n_layers=4, feat_dim=20),
     "C5pq-small": lambda: dataclasses.replace(scaled_workload("C5", 900, hidden=72, n_layers=4, feat_dim=12), quant_q=True),
+    # p and q on a grid that does not contain 0, widths that are no multiples of 4: the pad columns of the
+    # stored arrays must stay 0 (they enter the objective's and the residual's sums)
+    "C5pq-ragged": lambda: dataclasses.replace(scaled_workload("C5", 700, hidden=37, n_layers=4, feat_dim=7),
+                                               quant_q=True, n_classes=5),
     # large enough (> 384 output tiles per launch) for the path that folds the residual updates and the
     # column sums into the product epilogues, with step sizes that still change in the first iterations
     "mid": lambda: scaled_workload("C2", 3300, hidden=260, n_layers=8, feat_dim=10),
@@ -164,6 +170,8 @@ CASES = {
                                               quant=(-1.0, 20.0, 22)),      # Delta = {-1, 0, 1, ..., 20} (Section 5.1)
     "ragged": lambda: dataclasses.replace(scaled_workload("C2", 1037, hidden=131, n_layers=3, feat_dim=7), n_classes=11),
     "leaky-small": lambda: dataclasses.replace(scaled_workload("C2", 1100, hidden=90, n_layers=4, feat_dim=14), slope=0.05),
+    # least-squares risk: closed-form z_L in place of FISTA
+    "ls-small": lambda: dataclasses.replace(scaled_workload("C2", 900, hidden=70, n_layers=3, feat_dim=9), risk="ls"),
     "odd-widths": lambda: dataclasses.replace(scaled_workload("C2", 333, hidden=50, n_layers=3, feat_dim=5),
                                               n_classes=5, hidden=37),
     "one-layer": lambda: scaled_workload("C2", 400, hidden=10, n_layers=1, feat_dim=6),
@@ -206,49 +214,46 @@ def _check_step_sizes(H, ctx, st):
         assert wt[i] == st.w_trials[i]
 
 
-def _quant_index_report(P, ctx, st):
-    """-Q: indices must agree except where the unprojected value sits at a rounding distance
-    from a midpoint; every mismatch must be one level."""
-    g = st.grid
-    bad = 0
-    total = 0
-    for i in range(1, st.L):
-        idx = P.pdadmm_get_var(ctx, P.VAR.PIDX, i + 1).astype(np.int32)
-        ref = O.quantize(st.p[i], g)[0]
-        gp = P.pdadmm_get_var(ctx, P.VAR.P, i + 1)
-        assert np.array_equal(gp.view(np.uint32), g.members()[idx].view(np.uint32))   # p in Delta, bit for bit
-        diff = np.abs(idx - ref)
-        assert diff.max() <= 1
-        bad += int((diff != 0).sum())
-        total += idx.size
-    return bad, total
+def _is_q(case):
+    return CASES[case]().quant is not None
 
 
-@pytest.mark.parametrize("case", list(CASES))
-def test_one_iteration_phase_by_phase(env, case):
+# -Q cases run under both backtracking schedules: the probe back-off (what bench.py times) and the plain
+# schedule (every update starts at the previous tau divided by eta, as pdADMM-G does)
+PHASE_CASES = [(c, "backoff") for c in CASES] + [(c, "plain") for c in CASES if _is_q(c)]
+
+
+@pytest.mark.parametrize("case,schedule", PHASE_CASES)
+def test_one_iteration_phase_by_phase(env, case, schedule):
     torch, P, H = env
     w = CASES[case]()
-    _say(f"one iteration {case}: N={w.n_nodes} dims={w.dims[:3]}..{w.dims[-1]} L={w.n_layers}")
+    _say(f"one iteration {case} ({schedule}): N={w.n_nodes} dims={w.dims[:3]}..{w.dims[-1]} L={w.n_layers}")
     inp = oracle_inputs(w)
-    st = H.round_state_to_fp32(oracle_state(w, inp))
+    st = H.round_state_to_fp32(oracle_state(w, inp, probe_backoff=schedule == "backoff"))
+    if w.quant is not None:
+        # a state in mid-run: some layers are waiting out a rejected probe (the schedules differ only there)
+        for i in range(1, st.L):
+            st.p_wait[i], st.p_skip[i] = (2, 1) if (i % 2 == 1 and schedule == "backoff") else (0, 0)
     ctx = H.gpu_context(w, inp, st)
+    start = st.copy()
     for phase, nm in ((P.PHASE.P, "P"), (P.PHASE.W, "W"), (P.PHASE.BZQU, "BZQU")):
         before = st.copy() if phase == P.PHASE.BZQU else None     # for the tie check of the z-update
         H.oracle_phase(st, phase)
         P.pdadmm_step_phase(ctx, phase)
         P.pdadmm_sync(ctx)
-        if w.quant is None:
-            ok, worst, rep = H.compare_state(ctx, st, TOL_STATE, what=f"{case}/{nm}", before=before)
-            assert ok, rep
-        _check_step_sizes(H, ctx, st)
-    if w.quant is not None:
-        bad, total = _quant_index_report(P, ctx, st)
-        _say(f"  -Q index mismatches after one iteration: {bad} of {total}")
-        assert bad <= max(2, 2e-5 * total)
-        ok, worst, rep = H.compare_state(ctx, st, 2e-3, what=case)   # a flipped level moves p by one step
+        if w.quant is not None and phase == P.PHASE.P:
+            # differing indices are validated as midpoint cases and adopted by the oracle state
+            bad, total, worst_mid = H.quant_flips(P, ctx, start, st, what=case)
+            _say(f"  -Q indices differing from the oracle's after the p-update: {bad} of {total}, all at midpoints of "
+                 f"Delta (worst distance / slack {worst_mid:.2f})")
+            assert bad <= max(2, 2e-5 * total)
+            for l in range(2, st.L + 1):
+                assert P.pdadmm_get_var(ctx, P.VAR.PROBE, l) == (st.p_wait[l - 1], st.p_skip[l - 1])
+        if st.quantize_q and phase == P.PHASE.BZQU:
+            assert H.q_flips(P, ctx, before, st, what=case) <= 2
+        ok, worst, rep = H.compare_state(ctx, st, TOL_STATE, what=f"{case}/{nm}", before=before)
         assert ok, rep
-        for i in range(st.L):                                        # everything not downstream of p is tight
-            assert rel_l2(P.pdadmm_get_var(ctx, P.VAR.W, i + 1), st.W[i]) <= TOL_STATE
+        _check_step_sizes(H, ctx, st)
     # objective and residual of the resulting state
     og, oo = P.pdadmm_objective(ctx), O.objective(st)
     for k in ("risk", "lin_pen", "act_pen", "dual_quad", "F", "L_rho"):
@@ -265,13 +270,10 @@ def _same_step_sizes(H, ctx, st):
 
 
 @pytest.mark.parametrize("case,iters", [("C1-full", 10), ("C2-small", 20), ("C3-small", 20), ("C4-small", 20),
-                                        ("C5-small", 20), ("leaky-small", 20), ("mid", 20)])
+                                        ("leaky-small", 20), ("ls-small", 20), ("mid", 20)])
 def test_trajectories(env, case, iters):
-    """Free-running trajectories of objective and residual. pdADMM-G: within 1e-3 at every iteration and
-    identical step-size decisions. pdADMM-G-Q: rounding noise flips single quantisation indices, the
-    flips multiply from iteration to iteration (the projection is discontinuous) and can eventually flip a
-    backtracking decision, after which the two runs are two different valid trajectories; the 1e-3 bound
-    is therefore required up to the first differing step-size decision, which must not come early."""
+    """pdADMM-G, free-running: objective and residual within 1e-3 of the oracle's at every iteration and
+    identical step-size decisions."""
     torch, P, H = env
     w = CASES[case]()
     _say(f"trajectory {case} x{iters}")
@@ -279,7 +281,6 @@ def test_trajectories(env, case, iters):
     st = H.round_state_to_fp32(oracle_state(w, inp))
     ctx = H.gpu_context(w, inp, st)
     worst_obj = worst_res = 0.0
-    first_flip = None
     for k in range(iters):
         O.iterate(st)
         P.pdadmm_iterate(ctx, 1)
@@ -289,59 +290,65 @@ def test_trajectories(env, case, iters):
         ef = abs(og["F"] - oo["F"]) / abs(oo["F"])
         er = abs(rg - ro) / ro
         _say(f"  it {k + 1}: L_rho {og['L_rho']:.6e} / {oo['L_rho']:.6e}  res {rg:.6e} / {ro:.6e}")
-        if w.quant is None:
-            _check_step_sizes(H, ctx, st)
-        elif first_flip is None and not _same_step_sizes(H, ctx, st):
-            first_flip = k + 1
-            _say(f"  step-size decisions differ from iteration {first_flip} on")
-        if first_flip is None:
-            worst_obj, worst_res = max(worst_obj, eo, ef), max(worst_res, er)
-            # -Q: single flipped indices (values at a rounding distance from a midpoint of Delta) multiply from
-            # iteration to iteration; the residual ||p - q||, a norm of differences of grid values, feels them
-            # first. Free-running, it is held to 1e-3 for the first half of the run and to 1e-2 after; the
-            # step-by-step test below holds every single iteration to 1e-3.
-            tol_res = TOL_TRAJ if (w.quant is None or k < iters // 2) else 10 * TOL_TRAJ
-            assert eo <= TOL_TRAJ and ef <= TOL_TRAJ and er <= tol_res, (k, eo, ef, er)
-        else:
-            assert eo <= 0.25 and np.isfinite(rg), (k, eo, er)   # two valid paths of the same problem
-    assert first_flip is None or first_flip > iters // 2
+        _check_step_sizes(H, ctx, st)
+        worst_obj, worst_res = max(worst_obj, eo, ef), max(worst_res, er)
+        assert eo <= TOL_TRAJ and ef <= TOL_TRAJ and er <= TOL_TRAJ, (k, eo, ef, er)
     s = P.pdadmm_stats(ctx, drift=True)
     _say(f"  worst obj err {worst_obj:.2e}, worst residual err {worst_res:.2e}, carried-residual drift {s['r_drift']:.2e}")
     assert s["r_drift"] < 1e-4
 
 
-@pytest.mark.parametrize("case", ["C5-small", "C5pq-small", "paper-grid", "mid-Q"])
-def test_quantized_trajectory_step_by_step_along_the_oracle_run(env, case):
+def _one_step_against_oracle(P, H, ctx, st, what):
+    """Both sides take one iteration from the same values (`st` holds what the context holds). After the
+    p-updates the indices may differ only at validated midpoints of Delta, where the oracle state then takes
+    the GPU's member (both are nearest members of what their side computed); step sizes, trial counts and
+    probe state agree exactly; at the end of the iteration every variable agrees within 1e-4, objective and
+    residual within 1e-3. Returns the number of differing indices."""
+    start = st.copy()
+    P.pdadmm_iterate(ctx, 1)
+    P.pdadmm_sync(ctx)
+    H.oracle_phase(st, P.PHASE.P)
+    bad, total, worst_mid = H.quant_flips(P, ctx, start, st, what=what)
+    assert bad <= max(3, 3e-5 * total), (what, bad, total)
+    H.oracle_phase(st, P.PHASE.W)
+    before = st.copy()
+    H.oracle_phase(st, P.PHASE.BZQU)
+    if st.quantize_q:                     # the projected q-update has midpoint cases of its own
+        bad_q = H.q_flips(P, ctx, before, st, what=what)
+        assert bad_q <= max(3, 3e-5 * total), (what, bad_q)
+        bad += bad_q
+    _check_step_sizes(H, ctx, st)
+    for l in range(2, st.L + 1):
+        assert P.pdadmm_get_var(ctx, P.VAR.PROBE, l) == (st.p_wait[l - 1], st.p_skip[l - 1])
+    ok, worst, rep = H.compare_state(ctx, st, TOL_STATE, what=what, before=before)
+    assert ok, rep
+    og, oo = P.pdadmm_objective(ctx), O.objective(st)
+    rg, ro = P.pdadmm_residual(ctx)[0], O.residual(st)[0]
+    assert abs(og["L_rho"] - oo["L_rho"]) <= TOL_TRAJ * abs(oo["L_rho"]), what
+    assert abs(og["F"] - oo["F"]) <= TOL_TRAJ * abs(oo["F"]), what
+    assert abs(rg - ro) <= TOL_TRAJ * ro, what
+    return bad
+
+
+Q_STEP_CASES = [(c, s) for c in ("C5-small", "C5pq-small", "C5pq-ragged", "paper-grid", "mid-Q") for s in ("backoff", "plain")]
+
+
+@pytest.mark.parametrize("case,schedule", Q_STEP_CASES)
+def test_quantized_trajectory_step_by_step_along_the_oracle_run(env, case, schedule):
     """pdADMM-G-Q over 20 iterations, one step at a time: the oracle runs its own trajectory (its state
     rounded to fp32 after every iteration); before each iteration that state is copied to the GPU, both
-    take one iteration, and the results must agree (indices up to isolated one-level flips at midpoints,
-    step sizes exactly, objective and residual within 1e-3). Free-running -Q runs drift apart once a
-    flipped index changes a backtracking decision (see test_trajectories); this shows that every step of
-    the GPU is the oracle's step from the same starting values, all the way along the run."""
+    take one iteration, and the results must agree (see _one_step_against_oracle). This shows that every
+    step of the GPU is the oracle's step from the same starting values, all the way along the oracle's run;
+    test_quantized_free_run_is_a_chain_of_oracle_steps shows the same along the GPU's own run."""
     torch, P, H = env
     w = CASES[case]()
     inp = oracle_inputs(w)
-    st = H.round_state_to_fp32(oracle_state(w, inp))
+    st = H.round_state_to_fp32(oracle_state(w, inp, probe_backoff=schedule == "backoff"))
     ctx = H.gpu_context(w, inp, st)
     total_bad = 0
     for k in range(20):
         H.push_state(ctx, st)
-        O.iterate(st)
-        P.pdadmm_iterate(ctx, 1)
-        P.pdadmm_sync(ctx)
-        bad, total = _quant_index_report(P, ctx, st)
-        total_bad += bad
-        assert bad <= max(3, 3e-5 * total), (k, bad, total)
-        _check_step_sizes(H, ctx, st)
-        for l in range(2, st.L + 1):
-            assert P.pdadmm_get_var(ctx, P.VAR.PROBE, l) == (st.p_wait[l - 1], st.p_skip[l - 1])
-        ok, worst, rep = H.compare_state(ctx, st, 2e-3, what=f"step {k + 1}")
-        assert ok, rep
-        og, oo = P.pdadmm_objective(ctx), O.objective(st)
-        rg, ro = P.pdadmm_residual(ctx)[0], O.residual(st)[0]
-        assert abs(og["L_rho"] - oo["L_rho"]) <= TOL_TRAJ * abs(oo["L_rho"])
-        assert abs(og["F"] - oo["F"]) <= TOL_TRAJ * abs(oo["F"])
-        assert abs(rg - ro) <= TOL_TRAJ * ro
+        total_bad += _one_step_against_oracle(P, H, ctx, st, f"{case}/{schedule} step {k + 1}")
         # Lemma (q optimality): u = nu (q - f(z)) after every iteration, on the GPU's own state
         # (not in the variant that projects q: there q is no longer the minimiser of its subproblem)
         for l in range(1, st.L if not w.quant_q else 1):
@@ -355,7 +362,50 @@ def test_quantized_trajectory_step_by_step_along_the_oracle_run(env, case):
             for l in range(1, st.L):
                 assert np.isin(P.pdadmm_get_var(ctx, P.VAR.Q, l), mem).all()
         H.round_state_to_fp32(st)
-    _say(f"  stepwise -Q run: {total_bad} one-level index differences in 20 iterations")
+    _say(f"  stepwise -Q run ({schedule}): {total_bad} one-level index differences at midpoints in 20 iterations")
+
+
+@pytest.mark.parametrize("case,schedule", [("C5-small", "backoff"), ("C5-small", "plain"), ("mid-Q", "backoff")])
+def test_quantized_free_run_is_a_chain_of_oracle_steps(env, case, schedule):
+    """pdADMM-G-Q, free-running over 20 iterations. The projection onto Delta is discontinuous: where the
+    projected value sits within rounding of a midpoint, fp32 and fp64 products land on different members,
+    and from then on the two runs are two different valid runs of the algorithm, whose objective and
+    residual drift apart. Two statements are checked. (a) While no index has differed yet, objective and
+    residual of the free-running GPU agree with the free-running oracle within 1e-3. (b) All along the
+    GPU's OWN run, every iteration is an oracle iteration: the oracle, restarted from the GPU's variables
+    before each iteration, reproduces the GPU's next state (indices up to validated midpoint flips, step
+    sizes exactly, all variables within 1e-4 once the oracle takes the GPU's member at those midpoints,
+    objective and residual within 1e-3).
+    So whatever distance builds up between the two free runs comes from midpoint flips and nothing else;
+    the iterations at which it first exceeds 1e-3 are printed with the cumulative number of flips."""
+    torch, P, H = env
+    w = CASES[case]()
+    _say(f"free-running -Q {case} ({schedule})")
+    inp = oracle_inputs(w)
+    st = H.round_state_to_fp32(oracle_state(w, inp, probe_backoff=schedule == "backoff"))
+    ctx = H.gpu_context(w, inp, st)
+    flips = 0
+    first_over = {}
+    for k in range(20):
+        mirror = H.oracle_state_from_gpu(ctx, st)            # the GPU's own variables, before the iteration
+        O.iterate(st)                                        # the oracle's free run
+        flips_now = _one_step_against_oracle(P, H, ctx, mirror, f"{case}/{schedule} free run, iteration {k + 1}")
+        og, oo = P.pdadmm_objective(ctx), O.objective(st)
+        rg, ro = P.pdadmm_residual(ctx)[0], O.residual(st)[0]
+        errs = dict(L_rho=abs(og["L_rho"] - oo["L_rho"]) / abs(oo["L_rho"]), F=abs(og["F"] - oo["F"]) / abs(oo["F"]),
+                    residual=abs(rg - ro) / ro)
+        same_steps = _same_step_sizes(H, ctx, st)
+        _say(f"  it {k + 1}: L_rho err {errs['L_rho']:.1e}, F err {errs['F']:.1e}, residual err {errs['residual']:.1e}, "
+             f"flips so far {flips} + {flips_now}, step sizes {'equal' if same_steps else 'DIFFER'}")
+        if flips == 0:                                       # nothing has been projected differently before this iteration
+            assert same_steps
+            assert all(e <= TOL_TRAJ for e in errs.values()), (k, errs)
+        for name, e in errs.items():
+            if e > TOL_TRAJ and name not in first_over:
+                first_over[name] = (k + 1, flips + flips_now)
+        flips += flips_now
+        assert np.isfinite(og["L_rho"]) and np.isfinite(rg)
+    _say(f"  {flips} midpoint flips in 20 iterations; first iteration over 1e-3 (iteration, flips until then): {first_over or 'never'}")
 
 
 @pytest.mark.parametrize("case", ["C1-full", "C5-small", "leaky-small", "odd-widths", "one-layer"])
@@ -439,10 +489,21 @@ def test_checkpoint_and_resume(env, case):
     P.pdadmm_sync(b)
     sa, sb = P.pdadmm_stats(a), P.pdadmm_stats(b)
     assert np.array_equal(sa["tau"][1:], sb["tau"][1:]) and np.array_equal(sa["theta"], sb["theta"])
-    tol = 1e-5 if w.quant is None else 2e-3
+    # -Q: the rebuilt residual differs in its last bits, which may move an index across a midpoint of Delta;
+    # every update but that of W and b works node by node, so such a node is left out, the rest is tight
+    keep = np.ones(w.n_nodes, dtype=bool)
+    if w.quant is not None:
+        for l in range(2, L + 1):
+            keep &= (P.pdadmm_get_var(a, P.VAR.PIDX, l) == P.pdadmm_get_var(b, P.VAR.PIDX, l)).all(axis=1)
+        _say(f"  {case}: {int((~keep).sum())} of {w.n_nodes} nodes hold an index that differs after the resume")
+        assert (~keep).mean() <= 0.01
+    tol = 1e-5
+    # W and b are sums over all nodes: they see a node whose index moved by one grid step, diluted by 1/N
+    tol_wb = tol if keep.all() else 1e-3
     for l in range(1, L + 1):
-        for kind in (P.VAR.W, P.VAR.B, P.VAR.Z):
-            assert rel_l2(P.pdadmm_get_var(b, kind, l), P.pdadmm_get_var(a, kind, l)) <= tol, (kind, l)
+        for kind in (P.VAR.W, P.VAR.B):
+            assert rel_l2(P.pdadmm_get_var(b, kind, l), P.pdadmm_get_var(a, kind, l)) <= tol_wb, (kind, l)
+        assert rel_l2(P.pdadmm_get_var(b, P.VAR.Z, l)[keep], P.pdadmm_get_var(a, P.VAR.Z, l)[keep]) <= tol, ("z", l)
     oa, ob = P.pdadmm_objective(a), P.pdadmm_objective(b)
     assert abs(oa["L_rho"] - ob["L_rho"]) <= 1e-5 * abs(oa["L_rho"])
 
@@ -557,9 +618,19 @@ def test_grow_layers_matches_the_oracle(env, quant):
         assert np.array_equal(P.pdadmm_get_var(ctx, P.VAR.W, i + 1), want), f"W{i + 1}"
         assert np.array_equal(P.pdadmm_get_var(ctx, P.VAR.B, i + 1), (st.b[f - 1] if f else bn[i]).astype(F32))
     tol = 1e-4
-    _, worst, rep = H.compare_state(ctx, ref, tol, "grown start")
-    _say(f"  grown start: worst rel-L2 {worst:.2e}")
-    assert worst <= (2e-2 if quant else 1e-5), rep     # -Q: isolated one-level index flips
+    if quant:     # nodes at which the forward pass put an index on the other side of a midpoint are left out
+        dirty = H.forward_flips(P, ctx, ref, what="grown start")
+        _say(f"  grown start: {int(dirty.sum())} of {base.n_nodes} nodes left out after a midpoint flip")
+        assert dirty.mean() <= 0.01
+        for i in range(ref.L):
+            assert rel_l2(P.pdadmm_get_var(ctx, P.VAR.Z, i + 1)[~dirty], ref.z[i][~dirty]) <= 1e-5
+            if i < ref.L - 1:
+                assert rel_l2(P.pdadmm_get_var(ctx, P.VAR.Q, i + 1)[~dirty], ref.q[i][~dirty]) <= 1e-5
+                assert np.array_equal(P.pdadmm_get_var(ctx, P.VAR.P, i + 2)[~dirty], ref.p[i + 1][~dirty].astype(F32))
+    else:
+        _, worst, rep = H.compare_state(ctx, ref, tol, "grown start")
+        _say(f"  grown start: worst rel-L2 {worst:.2e}")
+        assert worst <= 1e-5, rep
     tau, theta, _, _ = H.step_sizes(ctx)
     assert all(t == 1.0 for t in tau[1:]) and all(t == 1.0 for t in theta)
     if not quant:
