@@ -161,6 +161,24 @@ pdadmm_status pdadmm_gemm_tn(int32_t M, int32_t N, int32_t K, float alpha, const
                              const float* B, int32_t ldb, float* C, int32_t ldc, int32_t splitk,
                              float* part, void* stream);
 
+/*
+ * pdadmm_gemm_tn for callers that cannot allocate device memory: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc. The partial products of the K chunks live in a device
+ * array that is part of the library image (PDADMM_STATIC_SCRATCH_FLOATS floats = 64 MiB, held by every
+ * GPU the library runs on until the process ends) instead of a caller buffer. Arguments and result are
+ * those of pdadmm_gemm_tn without `part` (same kernels, same chunking, same order of additions: the
+ * results are equal bit for bit). EINVAL, with a text in pdadmm_last_error(NULL), also when
+ * chunks * M * ldc exceeds the array (chunks = number of K chunks actually used, <= splitk).
+ * The call allocates nothing: no hipMalloc/hipFree and no allocating library routine. Nothing in the
+ * array has to start at zero (every element that is summed is written by the same call first). All
+ * calls on one GPU share that GPU's array: calls that overlap in time on one GPU race; calls on one
+ * stream, or ordered by events, do not.
+ */
+#define PDADMM_STATIC_SCRATCH_FLOATS (16u * 1024u * 1024u)
+pdadmm_status pdadmm_gemm_tn_static(int32_t M, int32_t N, int32_t K, float alpha, const float* A, int32_t lda,
+                                    const float* B, int32_t ldb, float* C, int32_t ldc, int32_t splitk,
+                                    void* stream);
+
 /* Bytes of DEVICE workspace pdadmm_init needs for this configuration (0 if it is invalid). */
 size_t pdadmm_workspace_bytes(const pdadmm_config* cfg);
 

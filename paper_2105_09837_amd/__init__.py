@@ -5,7 +5,7 @@ Every step of the method runs in the HIP library; this package only marshals arg
 """
 from .binding import (PdadmmError, Config, Context, load_library, library_path, exported_symbols,
                       pdadmm_normalize_adj, pdadmm_augment, pdadmm_quantize, pdadmm_gemm_nt,
-                      pdadmm_gemm_tn, pdadmm_workspace_bytes, pdadmm_init, pdadmm_grow_layers,
+                      pdadmm_gemm_tn, pdadmm_gemm_tn_static, pdadmm_workspace_bytes, pdadmm_init, pdadmm_grow_layers,
                       pdadmm_set_var,
                       pdadmm_get_var, pdadmm_iterate, pdadmm_step_phase, pdadmm_sync,
                       pdadmm_objective, pdadmm_residual, pdadmm_stats, pdadmm_plan_info, pdadmm_predict, pdadmm_destroy,

@@ -46,7 +46,7 @@ class _CObjective(C.Structure):
 RISK = {"ce": 0, "ls": 1}
 
 EXPORTS = ["pdadmm_normalize_adj", "pdadmm_augment", "pdadmm_quantize", "pdadmm_gemm_nt", "pdadmm_gemm_tn",
-
+           "pdadmm_gemm_tn_static",
            "pdadmm_workspace_bytes", "pdadmm_init", "pdadmm_grow_layers", "pdadmm_set_var", "pdadmm_get_var", "pdadmm_iterate",
            "pdadmm_step_phase", "pdadmm_sync", "pdadmm_objective", "pdadmm_residual", "pdadmm_stats", "pdadmm_plan_info",
            "pdadmm_predict",
@@ -77,6 +77,7 @@ def load_library():
     lib.pdadmm_quantize.argtypes = [vp, i64, f32, f32, i32, vp, vp, vp]
     lib.pdadmm_gemm_nt.argtypes = [i32, i32, i32, vp, i32, vp, i32, vp, i32, vp]
     lib.pdadmm_gemm_tn.argtypes = [i32, i32, i32, f32, vp, i32, vp, i32, vp, i32, i32, vp, vp]
+    lib.pdadmm_gemm_tn_static.argtypes = [i32, i32, i32, f32, vp, i32, vp, i32, vp, i32, i32, vp]
     lib.pdadmm_workspace_bytes.argtypes = [C.POINTER(_CConfig)]
     lib.pdadmm_workspace_bytes.restype = C.c_size_t
     lib.pdadmm_init.argtypes = [C.POINTER(vp), C.POINTER(_CConfig), vp, C.c_size_t, vp, vp, vp,
@@ -256,6 +257,19 @@ def pdadmm_gemm_tn(A, B, alpha: float = 1.0, splitk: int = 1, out=None, stream=N
     part = torch.empty((max(splitk, 1), M, out.stride(0)), dtype=torch.float32, device=A.device)
     _check(lib.pdadmm_gemm_tn(M, N, K, alpha, _ptr(A), A.stride(0), _ptr(B), B.stride(0), _ptr(out), out.stride(0),
                               splitk, _ptr(part), _stream_ptr(stream)), "pdadmm_gemm_tn")
+    return out
+
+
+def pdadmm_gemm_tn_static(A, B, alpha: float = 1.0, splitk: int = 1, out=None, stream=None):
+    """pdadmm_gemm_tn with the library's built-in scratch: the call itself allocates nothing (pass `out`)."""
+    import torch
+    lib = load_library()
+    K, M = A.shape
+    N = B.shape[1]
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.float32, device=A.device)
+    _check(lib.pdadmm_gemm_tn_static(M, N, K, alpha, _ptr(A), A.stride(0), _ptr(B), B.stride(0), _ptr(out),
+                                     out.stride(0), splitk, _stream_ptr(stream)), "pdadmm_gemm_tn_static")
     return out
 
 

@@ -6,6 +6,7 @@
 #include <cmath>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <string>
 #include <vector>
 
@@ -163,7 +164,30 @@ pdadmm_status fail(pdadmm_ctx* c, pdadmm_status s, const std::string& m) {
   return s;
 }
 
+// Scratch of the entry point that allocates nothing (pdadmm_gemm_tn_static): part of the library image, one
+// copy per GPU. In host code the name of the array is only a handle for hipGetSymbolAddress: the address a
+// kernel may use is looked up once per device and kept in g_scratch_ptr.
+static __device__ __attribute__((used)) __align__(256) float scratch[PDADMM_STATIC_SCRATCH_FLOATS];
+constexpr int kMaxDevices = 64;
+float* g_scratch_ptr[kMaxDevices] = {};
+std::mutex g_scratch_mutex;
 
+pdadmm_status scratch_of_current_device(float** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return fail(nullptr, PDADMM_EHIP, std::string("hipGetDevice: ") + hipGetErrorString(e));
+  if (dev < 0 || dev >= kMaxDevices) return fail(nullptr, PDADMM_EHIP, "device ordinal beyond the table of scratch addresses");
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    float* ptr = nullptr;
+    e = hipGetSymbolAddress((void**)&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !ptr)
+      return fail(nullptr, PDADMM_EHIP, std::string("hipGetSymbolAddress(scratch): ") + hipGetErrorString(e));
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return PDADMM_OK;
+}
 
 #define HIP_TRY(ctx, call)                                                                   \
   do {                                                                                       \
@@ -934,6 +958,26 @@ pdadmm_status pdadmm_gemm_tn(int32_t M, int32_t N, int32_t K, float alpha, const
   R.nblk = (int)std::min<size_t>(2048, std::max<size_t>(1, ((size_t)M * ldc + 1023) / 1024));
   hipLaunchKernelGGL(splitk_reduce_one_kernel, dim3(R.nblk), dim3(256), 0, st, R);
   return hipGetLastError() == hipSuccess ? PDADMM_OK : PDADMM_EHIP;
+}
+
+pdadmm_status pdadmm_gemm_tn_static(int32_t M, int32_t N, int32_t K, float alpha, const float* A, int32_t lda,
+                                    const float* B, int32_t ldb, float* C, int32_t ldc, int32_t splitk,
+                                    void* stream) {
+  if (M < 1 || N < 1 || K < 1 || !A || !B || !C || lda < M || ldb < N || ldc < N || splitk < 1 || splitk > K)
+    return fail(nullptr, PDADMM_EINVAL, "pdadmm_gemm_tn_static: bad size, leading dimension or NULL pointer");
+  const int chunk = cdiv(cdiv(K, splitk), BK) * BK;   // the chunking of pdadmm_gemm_tn
+  const int sk = cdiv(K, chunk);
+  const size_t need = (size_t)sk * (size_t)M * (size_t)ldc;
+  if (need > (size_t)PDADMM_STATIC_SCRATCH_FLOATS)
+    return fail(nullptr, PDADMM_EINVAL, "pdadmm_gemm_tn_static: " + std::to_string(sk) + " chunks x M x ldc = " +
+                                            std::to_string(need) + " floats exceed the built-in scratch of " +
+                                            std::to_string((size_t)PDADMM_STATIC_SCRATCH_FLOATS));
+  float* part = nullptr;
+  const pdadmm_status s = scratch_of_current_device(&part);
+  if (s != PDADMM_OK) return s;
+  // every element of part that the reduction adds up is written by the product kernel of this call first
+  // (rows < M, columns < N of every chunk; what it reads beyond column N is masked before it is used)
+  return pdadmm_gemm_tn(M, N, K, alpha, A, lda, B, ldb, C, ldc, splitk, part, stream);
 }
 
 size_t pdadmm_workspace_bytes(const pdadmm_config* cfg) {
