@@ -95,7 +95,9 @@ enum {
   PDADMM_VAR_U = 5,      /* u_l, l = 1..L-1, [N, n_l] */
   PDADMM_VAR_TAU = 6,    /* tau_l, l = 2..L: one HOST double */
   PDADMM_VAR_THETA = 7,  /* theta_l, l = 1..L: one HOST double */
-  PDADMM_VAR_PIDX = 8,   /* get only, -Q: indices of p_l in Delta, uint8 [N, n_{l-1}], l = 2..L */
+  PDADMM_VAR_PIDX = 8,   /* get only, -Q: indices of p_l in Delta, uint8 [N, n_{l-1}], l = 2..L (this is how the library
+                            keeps p_l in -Q; PDADMM_VAR_P forms the values Delta[index] on the way out and takes
+                            the indices of the nearest members on the way in) */
   /* (diagnostics) read-only internals */
   PDADMM_VAR_RESID = 9,  /* carried W_l p_l + b_l - z_l, [N, n_l] */
   PDADMM_VAR_GRAD_P = 10,/* last gradient of phi in p_l, [N, n_{l-1}], l = 2..L */
@@ -277,8 +279,12 @@ pdadmm_status pdadmm_stats(pdadmm_ctx* ctx, double* tau, double* theta, int32_t*
  * set if the same holds for r -= Gp/theta and its column sums (both variants, same size condition).
  * A clear bit means separate streaming kernels apply that update. wgrad_split (L entries): number of
  * node-range chunks the r p^T product of each layer is split into. wtrial_split: number of chunks the
- * contraction of the G p products is split into (1 = not split). Does not synchronise. */
-pdadmm_status pdadmm_plan_info(pdadmm_ctx* ctx, int32_t* fused_updates, int32_t* wgrad_split, int32_t* wtrial_split);
+ * contraction of the G p products is split into (1 = not split). p_bytes: bytes per element in which p_l
+ * (l >= 2) is resident: 4 (fp32) for pdADMM-G, 1 for -Q, where p_l is a member of Delta and only its 8-bit index is
+ * kept (Appendix B, last paragraph; the values are formed where they are consumed: in the operand loads of the
+ * products and in the streaming kernels). Does not synchronise. */
+pdadmm_status pdadmm_plan_info(pdadmm_ctx* ctx, int32_t* fused_updates, int32_t* wgrad_split, int32_t* wtrial_split,
+                               int32_t* p_bytes);
 
 /*
  * (diagnostics) Per-launch timing with HIP events recorded on the context's stream around the launches of the

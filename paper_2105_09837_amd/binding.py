@@ -92,7 +92,7 @@ def load_library():
     lib.pdadmm_objective.argtypes = [vp, C.POINTER(_CObjective)]
     lib.pdadmm_residual.argtypes = [vp, C.POINTER(C.c_double), vp]
     lib.pdadmm_stats.argtypes = [vp, vp, vp, vp, vp, vp, vp]
-    lib.pdadmm_plan_info.argtypes = [vp, vp, vp, vp]
+    lib.pdadmm_plan_info.argtypes = [vp, vp, vp, vp, vp]
     lib.pdadmm_predict.argtypes = [vp, vp, vp, vp, vp]
     lib.pdadmm_timing.argtypes = [vp, C.c_uint32]
     lib.pdadmm_timing_read.argtypes = [vp, vp, vp, i32]
@@ -415,11 +415,11 @@ def pdadmm_stats(ctx: Context, drift: bool = False) -> dict:
 
 
 def pdadmm_plan_info(ctx: Context) -> dict:
-    fused, wts = C.c_int32(0), C.c_int32(0)
+    fused, wts, pb = C.c_int32(0), C.c_int32(0), C.c_int32(0)
     ws = np.zeros(ctx.L, dtype=np.int32)
-    _check(load_library().pdadmm_plan_info(ctx.handle, C.addressof(fused), ws.ctypes.data, C.addressof(wts)),
-           "pdadmm_plan_info", ctx)
-    return dict(fused_updates=int(fused.value), wgrad_split=ws, wtrial_split=int(wts.value))
+    _check(load_library().pdadmm_plan_info(ctx.handle, C.addressof(fused), ws.ctypes.data, C.addressof(wts),
+                                           C.addressof(pb)), "pdadmm_plan_info", ctx)
+    return dict(fused_updates=int(fused.value), wgrad_split=ws, wtrial_split=int(wts.value), p_bytes=int(pb.value))
 
 
 def pdadmm_predict(ctx: Context, mask=None, want_logits: bool = False) -> dict:

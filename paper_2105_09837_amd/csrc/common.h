@@ -103,7 +103,7 @@ struct LayerScal {
   int probing;             // -Q: 1 if this update started at tau/eta (a probe of the smaller value)
   int probe_wait;          // -Q: iterations to wait after a rejected probe (1, 2, 4, ... kProbeCap)
   int probe_skip;          // -Q: iterations left until the next probe
-  int pad_;
+  int cur;                 // -Q: which of the layer's two index planes holds p_l (the other takes the trial candidates)
   long long products;      // -Q: trial products W d judged for this layer since init (one per backtracking trial)
 };
 constexpr int kProbeCap = 16;
@@ -147,5 +147,17 @@ __device__ __forceinline__ int quant_index(float v, const QuantGrid g) {
 __device__ __forceinline__ float quant_value(int idx, const QuantGrid g) {
   return add_rn(g.lo, mul_rn((float)idx, g.step));
 }
+// Four members of Delta from four packed 8-bit indices (byte j = index of element j). In -Q the library keeps
+// p_l (l >= 2) only as such indices and forms the values where they are consumed; the value is the same
+// fp32 number that quant_value gives, bit for bit.
+__device__ __forceinline__ f32x4 dequant4(uint32_t packed, const QuantGrid g) {
+  f32x4 v;
+  v.x = quant_value((int)(packed & 0xffu), g);
+  v.y = quant_value((int)((packed >> 8) & 0xffu), g);
+  v.z = quant_value((int)((packed >> 16) & 0xffu), g);
+  v.w = quant_value((int)(packed >> 24), g);
+  return v;
+}
+typedef const uint8_t PD_GLOBAL* gcu8;
 
 }  // namespace pdadmm

@@ -174,7 +174,9 @@ struct RowSeg {
   float* z;
   float* q;
   float* u;
-  const float* pnext;   // p_{l+1}
+  const float* pnext;   // p_{l+1} (fp32), or null when it is kept as indices:
+  const uint8_t* pnext8;  // -Q: the two index planes of p_{l+1} (p8_plane bytes each; LayerScal::cur of layer + 1 selects)
+  size_t p8_plane;
   const float* m;       // column means (b-step), [ld]
   double* colpart;      // [row_blocks][ld]
   int rows, ncols, ld;
@@ -304,12 +306,15 @@ __device__ __forceinline__ float z_closed_form(float s, float q, float slope) {
 // projected onto Delta before r and u are formed.
 constexpr int kZquUnroll = 2;   // float4 groups per thread
 
-__global__ __launch_bounds__(256) void zqu_kernel(const RowSeg* __restrict__ segs, const BlockMap map, float rho, float nu,
-                                                  float slope, const QuantGrid qgrid) {
+// pgrid: Delta when p_{l+1} is kept as 8-bit indices (-Q; levels = 0 otherwise); qgrid: Delta when q is projected too.
+__global__ __launch_bounds__(256) void zqu_kernel(const RowSeg* __restrict__ segs, const BlockMap map,
+                                                  const LayerScal* __restrict__ scal, float rho, float nu,
+                                                  float slope, const QuantGrid pgrid, const QuantGrid qgrid) {
   int local;
   const int si = find_group(map, blockIdx.x, &local);
   const RowSeg S = segs[si];
   const float inv_rn = 1.0f / (rho + nu);
+  const uint8_t* p8 = S.pnext8 ? S.pnext8 + (size_t)scal[S.layer + 1].cur * S.p8_plane : nullptr;
   // flat over the [rows, ld] arrays: a block owns 256*kZquUnroll consecutive float4 groups
   const size_t n4 = (size_t)S.rows * (S.ld / 4);
   const int ld4 = S.ld / 4;
@@ -325,7 +330,17 @@ __global__ __launch_bounds__(256) void zqu_kernel(const RowSeg* __restrict__ seg
       Rv[k] = stream_load(reinterpret_cast<const f32x4*>(S.R) + i);
       zo[k] = stream_load(reinterpret_cast<const f32x4*>(S.z) + i);
       qo[k] = stream_load(reinterpret_cast<const f32x4*>(S.q) + i);
-      pn[k] = stream_load(reinterpret_cast<const f32x4*>(S.pnext) + i);
+      if (p8) {
+        pn[k] = dequant4(__builtin_nontemporal_load(reinterpret_cast<const uint32_t*>(p8) + i), pgrid);
+        if (S.ncols != S.ld) {        // index 0 in a pad column stands for no value
+          const int col0 = (int)(i % (size_t)ld4) * 4;
+#pragma unroll
+          for (int c = 0; c < 4; ++c)
+            if (col0 + c >= S.ncols) pn[k][c] = 0.0f;
+        }
+      } else {
+        pn[k] = stream_load(reinterpret_cast<const f32x4*>(S.pnext) + i);
+      }
       uo[k] = stream_load(reinterpret_cast<const f32x4*>(S.u) + i);
       mm[k] = reinterpret_cast<const f32x4*>(S.m)[i % ld4];
     }
@@ -455,10 +470,11 @@ __global__ __launch_bounds__(256) void zlast_ls_kernel(float* __restrict__ R, fl
 // One backtracking trial: candidate indices, d = candidate - p, per-block ||d||^2.
 // ------------------------------------------------------------------------------------------
 struct QuantSeg {
-  float* p;
+  uint8_t* p8;        // the two index planes of p_l, [2][plane]: LayerScal::cur selects the one that holds p_l, the
+                      // other takes the candidate of the trial in flight
+  size_t p8_plane;
   const float* g;
   float* d;
-  uint8_t* idx;       // [rows][ld]
   double* dpart;      // per block
   size_t n4;          // rows*ld/4
   int ncols, ld;
@@ -478,13 +494,16 @@ __global__ __launch_bounds__(256) void quant_trial_kernel(const QuantSeg* __rest
   const QuantSeg S = segs[si];
   if (!scal[S.layer].active) return;
   const float t = scal[S.layer].trial_t;
+  const int cur = scal[S.layer].cur;
+  const uint32_t* pin = reinterpret_cast<const uint32_t*>(S.p8 + (size_t)cur * S.p8_plane);
+  uint32_t* pout = reinterpret_cast<uint32_t*>(S.p8 + (size_t)(cur ^ 1) * S.p8_plane);
   const size_t base = (size_t)local * (256 * kQuantUnroll) + threadIdx.x;
   f32x4 pv[kQuantUnroll], gv[kQuantUnroll];
 #pragma unroll
   for (int j = 0; j < kQuantUnroll; ++j) {
     const size_t i = base + (size_t)j * 256;
     if (i < S.n4) {
-      pv[j] = stream_load(reinterpret_cast<const f32x4*>(S.p) + i);
+      pv[j] = dequant4(__builtin_nontemporal_load(pin + i), grid);
       gv[j] = stream_load(reinterpret_cast<const f32x4*>(S.g) + i);
     }
   }
@@ -512,7 +531,7 @@ __global__ __launch_bounds__(256) void quant_trial_kernel(const QuantSeg* __rest
     PDADMM_QT(x, 0) PDADMM_QT(y, 1) PDADMM_QT(z, 2) PDADMM_QT(w, 3)
 #undef PDADMM_QT
     reinterpret_cast<f32x4*>(S.d)[i] = dv;       // re-read by the product W d that follows
-    reinterpret_cast<uchar4*>(S.idx)[i] = iv;
+    pout[i] = (uint32_t)iv.x | ((uint32_t)iv.y << 8) | ((uint32_t)iv.z << 16) | ((uint32_t)iv.w << 24);
   }
   const double tot = block_sum_256(ds, red);
   if (threadIdx.x == 0) S.dpart[local] = tot;
@@ -565,6 +584,7 @@ __global__ __launch_bounds__(256) void select_quant_kernel(const SelectDesc* __r
     sc.tau = t;
     sc.inv_tau = 1.0f;     // marks "a step was accepted"
     sc.active = 0;
+    sc.cur ^= 1;           // the plane the accepted candidate was written to now holds p_l
     if (backoff && sc.probing) {   // accepted at once: probe again next time; else back off 1, 2, 4, ... iterations
       if (sc.p_trials == 1) sc.probe_wait = 0;
       else {
@@ -583,31 +603,17 @@ __global__ __launch_bounds__(256) void select_quant_kernel(const SelectDesc* __r
   flags[D.layer] = sc.active;
 }
 
-// p <- Delta[idx] for layers whose trial was accepted.
-__global__ __launch_bounds__(256) void quant_apply_kernel(const QuantSeg* __restrict__ segs, const BlockMap map,
-                                                          const LayerScal* __restrict__ scal, QuantGrid grid) {
-  int local;
-  const int si = find_group(map, blockIdx.x, &local);
-  const QuantSeg S = segs[si];
-  if (scal[S.layer].inv_tau == 0.0f) return;
-  const size_t base = (size_t)local * (256 * kQuantUnroll) + threadIdx.x;
-  uchar4 iv[kQuantUnroll];
+// Values of a [rows, ld] array of indices (ncols valid columns, pad columns give 0): p_l for pdadmm_get_var.
+__global__ __launch_bounds__(256) void dequantize_kernel(const uint8_t* __restrict__ idx, size_t n4, int ncols, int ld,
+                                                         QuantGrid grid, float* __restrict__ val) {
+  const size_t stride = (size_t)gridDim.x * 256;
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n4; i += stride) {
+    f32x4 v = dequant4(reinterpret_cast<const uint32_t*>(idx)[i], grid);
+    const int col0 = (int)((i * 4) % (size_t)ld);
 #pragma unroll
-  for (int j = 0; j < kQuantUnroll; ++j) {
-    const size_t i = base + (size_t)j * 256;
-    if (i < S.n4) iv[j] = reinterpret_cast<const uchar4*>(S.idx)[i];
-  }
-#pragma unroll
-  for (int j = 0; j < kQuantUnroll; ++j) {
-    const size_t i = base + (size_t)j * 256;
-    if (i >= S.n4) continue;
-    const int col0 = (int)((i * 4) % (size_t)S.ld);
-    f32x4 pv;
-    pv.x = col0 + 0 < S.ncols ? quant_value(iv[j].x, grid) : 0.0f;
-    pv.y = col0 + 1 < S.ncols ? quant_value(iv[j].y, grid) : 0.0f;
-    pv.z = col0 + 2 < S.ncols ? quant_value(iv[j].z, grid) : 0.0f;
-    pv.w = col0 + 3 < S.ncols ? quant_value(iv[j].w, grid) : 0.0f;
-    reinterpret_cast<f32x4*>(S.p)[i] = pv;
+    for (int c = 0; c < 4; ++c)
+      if (col0 + c >= ncols) v[c] = 0.0f;
+    reinterpret_cast<f32x4*>(val)[i] = v;
   }
 }
 
@@ -654,24 +660,39 @@ struct PairSeg {
   const float* q;
   const float* u;
   const float* pnext;
+  const uint8_t* pnext8;   // -Q: index planes of p_{l+1} in place of pnext (see RowSeg)
+  size_t p8_plane;
+  int next_layer, ncols, ld;
   double* part;       // 3 per block
   size_t n4;
   int blk0, nblk;
 };
 
 __global__ __launch_bounds__(256) void pair_reduce_kernel(const PairSeg* __restrict__ segs, const BlockMap map,
-                                                          float slope) {
+                                                          const LayerScal* __restrict__ scal, float slope,
+                                                          const QuantGrid pgrid) {
   __shared__ double red[4];
   int local;
   const int si = find_group(map, blockIdx.x, &local);
   const PairSeg S = segs[si];
+  const uint8_t* p8 = S.pnext8 ? S.pnext8 + (size_t)scal[S.next_layer].cur * S.p8_plane : nullptr;
   const size_t stride = (size_t)S.nblk * 256;
   double s_act = 0, s_dl = 0, s_dq = 0;
   for (size_t i = (size_t)local * 256 + threadIdx.x; i < S.n4; i += stride) {
     const float4 z = reinterpret_cast<const float4*>(S.z)[i];
     const float4 q = reinterpret_cast<const float4*>(S.q)[i];
     const float4 u = reinterpret_cast<const float4*>(S.u)[i];
-    const float4 p = reinterpret_cast<const float4*>(S.pnext)[i];
+    float4 p;
+    if (p8) {
+      const f32x4 v = dequant4(reinterpret_cast<const uint32_t*>(p8)[i], pgrid);
+      const int col0 = (int)((i * 4) % (size_t)S.ld);
+      p.x = col0 + 0 < S.ncols ? v.x : 0.0f;
+      p.y = col0 + 1 < S.ncols ? v.y : 0.0f;
+      p.z = col0 + 2 < S.ncols ? v.z : 0.0f;
+      p.w = col0 + 3 < S.ncols ? v.w : 0.0f;
+    } else {
+      p = reinterpret_cast<const float4*>(S.pnext)[i];
+    }
 #define PDADMM_PR(c)                                              \
   {                                                               \
     const double a = (double)q.c - (double)act_fn(z.c, slope);    \

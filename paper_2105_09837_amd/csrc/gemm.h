@@ -35,7 +35,14 @@ struct GemmProb {
   double* colpart;    // per row-tile column sums of the updated residual, [tiles_m][ldc] (EpiTrialW)
   float alpha, beta;
   float slope;        // negative-side slope of the activation (epilogues that apply f)
-  QuantGrid grid;     // used by the forward epilogue in -Q mode (levels = 0: off)
+  QuantGrid grid;     // Delta in -Q mode (levels = 0: off): forward epilogue, and wherever p_l is read as indices
+  // -Q: p_l (l >= 2) exists only as 8-bit indices into Delta, in two planes of p8_plane bytes each; the plane
+  // that holds p_l is LayerScal::cur of `layer` (the grouped kernel adds cur * p8_plane to p8 before use).
+  // Which role p8 plays is fixed by the kernel: the k-contiguous A operand or the m-contiguous B operand in
+  // place of A / B (template flag P8), or the epilogue's p input (EpiPGradQ).
+  const uint8_t* p8;
+  size_t p8_plane;
+  uint8_t* o8;        // forward epilogue in -Q mode: indices of p_{l+1} (in place of the values in o2)
 };
 
 // ---- epilogues. For one in-range output element (flat index i = row*ldc + col): load(P, i, col) fetches
@@ -108,6 +115,31 @@ struct EpiPGradT {
 typedef EpiPGradT<false> EpiPGrad;
 typedef EpiPGradT<true> EpiPGradUpd;
 
+// The same gradient in -Q mode, where p_l is read as 8-bit indices into Delta (P.p8) and becomes a value here.
+struct EpiPGradQ {
+  static constexpr int NS = 1, kBatch = 4;
+  static constexpr bool kVec = true, kExtra = false, kColsum = false;
+  static constexpr int kScale = 0;
+  struct In { float u, p, q; };
+  struct In4 { f32x4 u, q; uint32_t p; };
+  __device__ static __forceinline__ In load(const GemmProb& P, size_t i, int) {
+    return In{((gcf)P.e0)[i], quant_value((int)((gcu8)P.p8)[i], P.grid), ((gcf)P.e2)[i]};
+  }
+  __device__ static __forceinline__ void apply(const GemmProb& P, float* C, size_t i, int, float acc, const In& in,
+                                               double& s0, double&) {
+    const float g = P.alpha * acc + in.u + P.beta * (in.p - in.q);
+    ((float PD_GLOBAL*)C)[i] = g;
+    s0 += (double)g * (double)g;
+  }
+  __device__ static __forceinline__ In4 load4(const GemmProb& P, size_t i) {
+    return In4{*reinterpret_cast<gcf4>((gcf)P.e0 + i), *reinterpret_cast<gcf4>((gcf)P.e2 + i),
+               *reinterpret_cast<const uint32_t PD_GLOBAL*>((gcu8)P.p8 + i)};
+  }
+  __device__ static __forceinline__ f32x4 apply4(const GemmProb& P, f32x4 acc, const In4& in, float, f32x4&) {
+    return P.alpha * acc + in.u + P.beta * (dequant4(in.p, P.grid) - in.q);
+  }
+};
+
 // Step-direction products with the residual update folded in (pdADMM-G). T = acc is stored and its norm
 // taken as in EpiStoreNorm; in the same pass the carried residual r = W p + b - z (o1, in place) takes the
 // update r -= s_prev * T with the 1/tau or 1/theta guessed ahead by the previous selection (LayerScal::spec_*:
@@ -166,9 +198,11 @@ struct EpiForward {   // z = acc + b[col]; q = f(z); p_next = f(z) (projected on
     ((float PD_GLOBAL*)C)[i] = z;
     if (P.o1) {
       const float a = act_fn(z, P.slope);
-      const float aq = P.grid.levels > 0 ? quant_value(quant_index(a, P.grid), P.grid) : a;
+      const int id = P.grid.levels > 0 ? quant_index(a, P.grid) : 0;
+      const float aq = P.grid.levels > 0 ? quant_value(id, P.grid) : a;
       ((float PD_GLOBAL*)P.o1)[i] = P.beta != 0.0f ? aq : a;    // beta != 0: q is kept on the grid as well
-      ((float PD_GLOBAL*)P.o2)[i] = aq;
+      if (P.o8) ((uint8_t PD_GLOBAL*)P.o8)[i] = (uint8_t)id;    // -Q: p_{l+1} is kept as indices
+      else ((float PD_GLOBAL*)P.o2)[i] = aq;
     }
   }
 };
@@ -295,13 +329,80 @@ __device__ __forceinline__ void store_operand(float* lds, const f32x4 (&reg)[NV]
   }
 }
 
+// The same two steps for an operand that is stored as 8-bit indices into Delta (p_l in -Q mode; rows of ld
+// bytes, ld a multiple of 4, base 4-byte aligned: the library's own arrays). A thread fetches the four
+// indices of one group as one 32-bit word from an address clamped into the array (whatever a clamped index
+// fetches only reaches output rows/columns that are never stored) and turns them into values when the tile
+// is written to LDS, where entries whose k lies beyond kend become zero.
+template <bool KCONTIG, int ROWS, int BK, int NV>
+__device__ __forceinline__ void load_operand_u8(uint32_t (&reg)[NV], gcu8 base, int ld, int m0, int mlim, int kb,
+                                                int kend, int tid) {
+  if (KCONTIG) {
+    constexpr int KQ = BK / 4;
+    constexpr int RSTEP = 256 / KQ;
+    const int r = tid / KQ, k = kb + (tid % KQ) * 4;
+    const int kc = min(k, (kend - 1) & ~3);
+#pragma unroll
+    for (int h = 0; h < NV; ++h) {
+      const int mc = min(m0 + r + RSTEP * h, mlim - 1);
+      reg[h] = *reinterpret_cast<const uint32_t PD_GLOBAL*>(base + (size_t)mc * ld + kc);
+    }
+  } else {
+    constexpr int MQ = ROWS / 4;
+    constexpr int KSTEP = 256 / MQ;
+    const int kr = tid / MQ;
+    const int mc = min(m0 + (tid % MQ) * 4, ((mlim + 3) & ~3) - 4);
+#pragma unroll
+    for (int h = 0; h < NV; ++h) {
+      const int kc = min(kb + kr + KSTEP * h, kend - 1);
+      reg[h] = *reinterpret_cast<const uint32_t PD_GLOBAL*>(base + (size_t)kc * ld + mc);
+    }
+  }
+}
+
+template <bool KCONTIG, int ROWS, int BK, int LD, int NV>
+__device__ __forceinline__ void store_operand_u8(float* lds, const uint32_t (&reg)[NV], int kb, int kend, int tid,
+                                                 const QuantGrid grid) {
+  if (KCONTIG) {
+    constexpr int KQ = BK / 4;
+    constexpr int RSTEP = 256 / KQ;
+    const int r = tid / KQ, kq = (tid % KQ) * 4;
+    const int rem = kend - (kb + kq);
+    float* dst = lds + lds_pos<LD>(kq, r);
+#pragma unroll
+    for (int h = 0; h < NV; ++h) {
+      const int c = RSTEP * h;
+      const f32x4 v = dequant4(reg[h], grid);
+      dst[0 * LD + c] = rem > 0 ? v.x : 0.f;
+      dst[1 * LD + c] = rem > 1 ? v.y : 0.f;
+      dst[2 * LD + c] = rem > 2 ? v.z : 0.f;
+      dst[3 * LD + c] = rem > 3 ? v.w : 0.f;
+    }
+  } else {
+    constexpr int MQ = ROWS / 4;
+    constexpr int KSTEP = 256 / MQ;
+    const int kr = tid / MQ, mq = (tid % MQ) * 4;
+#pragma unroll
+    for (int h = 0; h < NV; ++h) {
+      f32x4 v = dequant4(reg[h], grid);
+      if (kb + kr + KSTEP * h >= kend) v = f32x4{0.f, 0.f, 0.f, 0.f};
+      *reinterpret_cast<f32x4*>(lds + lds_pos<LD>(kr + KSTEP * h, mq)) = v;
+    }
+  }
+}
+
 constexpr int kVecBatch = 4;   // 16-byte column groups per lane whose inputs are fetched together
+
+template <bool U8> struct OperandReg { typedef f32x4 type; };
+template <> struct OperandReg<true> { typedef uint32_t type; };
 
 template <bool B> struct BoolTag { static constexpr bool value = B; };
 
 // VECC: the output and the epilogue's inputs are [*, ld] arrays with ld % 4 == 0 and 16-byte aligned
 // bases (true for the library's own buffers), which allows the row-contiguous epilogue below.
-template <class Cfg, bool KCONTIG, class Epi, bool VECC>
+// P8: the operand that carries p_l (A in the k-contiguous layout, B in the other) is P.p8, 8-bit indices into
+// P.grid, instead of fp32 values.
+template <class Cfg, bool KCONTIG, class Epi, bool VECC, bool P8 = false>
 __device__ __forceinline__ void gemm_body(const GemmProb& P, const int local, const float escale) {
   constexpr int BM = Cfg::BM, BN = Cfg::BN, BK = Cfg::BK, TM = Cfg::TM, TN = Cfg::TN;
   constexpr int LDA = Cfg::LDA, LDB = Cfg::LDB;
@@ -331,7 +432,9 @@ __device__ __forceinline__ void gemm_body(const GemmProb& P, const int local, co
   const gcf B = (gcf)P.B;
   // the branch-free loader needs 16-byte loads to be legal and, for the m-contiguous layout,
   // whole float4 groups inside the matrix
-  const bool fast = P.vecA && P.vecB && (KCONTIG || (P.M % 4 == 0 && P.M >= 4 && P.N % 4 == 0 && P.N >= 4));
+  constexpr bool A8 = P8 && KCONTIG, B8 = P8 && !KCONTIG;
+  const bool fast = (A8 || P.vecA) && (B8 || P.vecB) &&
+                    (KCONTIG || (P.M % 4 == 0 && P.M >= 4 && (B8 || (P.N % 4 == 0 && P.N >= 4))));
 
   floatx16 acc[TM][TN];
 #pragma unroll
@@ -379,16 +482,23 @@ __device__ __forceinline__ void gemm_body(const GemmProb& P, const int local, co
   // consumed and waits for that set only, not for the loads it has just issued.
   auto main_loop = [&](auto fast_tag) {
     constexpr bool FAST = decltype(fast_tag)::value;
-    f32x4 ra0[NVA], rb0[NVB], ra1[NVA], rb1[NVB];
-    auto load_tile = [&](int kt, f32x4 (&ra)[NVA], f32x4 (&rb)[NVB]) {
+    typedef typename OperandReg<A8>::type RegA;
+    typedef typename OperandReg<B8>::type RegB;
+    RegA ra0[NVA], ra1[NVA];
+    RegB rb0[NVB], rb1[NVB];
+    auto load_tile = [&](int kt, RegA (&ra)[NVA], RegB (&rb)[NVB]) {
       const int kb = kbeg + kt * BK;
-      load_operand<KCONTIG, FAST, BM, BK, NVA>(ra, A, P.lda, m0, P.M, kb, kend, tid);
-      load_operand<KCONTIG, FAST, BN, BK, NVB>(rb, B, P.ldb, n0, P.N, kb, kend, tid);
+      if constexpr (A8) load_operand_u8<KCONTIG, BM, BK, NVA>(ra, (gcu8)P.p8, P.lda, m0, P.M, kb, kend, tid);
+      else load_operand<KCONTIG, FAST, BM, BK, NVA>(ra, A, P.lda, m0, P.M, kb, kend, tid);
+      if constexpr (B8) load_operand_u8<KCONTIG, BN, BK, NVB>(rb, (gcu8)P.p8, P.ldb, n0, P.N, kb, kend, tid);
+      else load_operand<KCONTIG, FAST, BN, BK, NVB>(rb, B, P.ldb, n0, P.N, kb, kend, tid);
     };
-    auto store_tile = [&](int kt, int buf, const f32x4 (&ra)[NVA], const f32x4 (&rb)[NVB]) {
+    auto store_tile = [&](int kt, int buf, const RegA (&ra)[NVA], const RegB (&rb)[NVB]) {
       const int kb = kbeg + kt * BK;
-      store_operand<KCONTIG, FAST, BM, BK, LDA, NVA>(As + buf * BUFA, ra, kb, kend, tid);
-      store_operand<KCONTIG, FAST, BN, BK, LDB, NVB>(Bs + buf * BUFB, rb, kb, kend, tid);
+      if constexpr (A8) store_operand_u8<KCONTIG, BM, BK, LDA, NVA>(As + buf * BUFA, ra, kb, kend, tid, P.grid);
+      else store_operand<KCONTIG, FAST, BM, BK, LDA, NVA>(As + buf * BUFA, ra, kb, kend, tid);
+      if constexpr (B8) store_operand_u8<KCONTIG, BN, BK, LDB, NVB>(Bs + buf * BUFB, rb, kb, kend, tid, P.grid);
+      else store_operand<KCONTIG, FAST, BN, BK, LDB, NVB>(Bs + buf * BUFB, rb, kb, kend, tid);
     };
     load_tile(0, ra0, rb0);
     load_tile(1, ra1, rb1);
@@ -534,7 +644,7 @@ __device__ __forceinline__ void gemm_body(const GemmProb& P, const int local, co
 // Grouped launch: block -> (problem, tile) through the table; blocks of one die are contiguous.
 // The second launch bound asks for 3 waves per SIMD (3 blocks per compute unit, 768 on the chip, which the
 // launch plans count on): the compiler then keeps accumulators and staging registers within 168 in all.
-template <class Cfg, bool KCONTIG, class Epi, bool VECC = false>
+template <class Cfg, bool KCONTIG, class Epi, bool VECC = false, bool P8 = false>
 __global__ __launch_bounds__(256, 3) void gemm_kernel(const GemmProb* __restrict__ probs, const BlockMap map,
                                                    const LayerScal* __restrict__ scal, int predicated,
                                                    int panel) {
@@ -542,20 +652,22 @@ __global__ __launch_bounds__(256, 3) void gemm_kernel(const GemmProb* __restrict
   if (lb >= map.total) return;
   int local;
   const int pi = find_group(map, lb, &local);
-  const GemmProb P = probs[pi];
+  GemmProb P = probs[pi];
   if (predicated && !scal[P.layer].active) return;
   float escale = 0.0f;
   if (Epi::kScale == 1) escale = scal[P.layer].spec_tau;
   if (Epi::kScale == 2) escale = scal[P.layer].spec_theta;
-  gemm_body<Cfg, KCONTIG, Epi, VECC>(P, local, escale);
+  if (P.p8) P.p8 += (size_t)scal[P.layer].cur * P.p8_plane;     // the plane that holds p_l right now
+  gemm_body<Cfg, KCONTIG, Epi, VECC, P8>(P, local, escale);
 }
 
 // Single problem with the descriptor passed by value (no table in device memory needed).
-template <class Cfg, bool KCONTIG, class Epi>
+// (P.p8, if used, must already point at the plane that holds p_l.)
+template <class Cfg, bool KCONTIG, class Epi, bool P8 = false>
 __global__ __launch_bounds__(256) void gemm_one_kernel(const GemmProb P, int panel) {
   const int lb = xcd_remap(blockIdx.x, panel);
   if (lb >= P.nblk) return;
-  gemm_body<Cfg, KCONTIG, Epi, false>(P, lb, 0.0f);
+  gemm_body<Cfg, KCONTIG, Epi, false, P8>(P, lb, 0.0f);
 }
 
 // Sum the split-K partial products in a fixed order: G = alpha * sum_s part[s]; also write the

@@ -59,9 +59,11 @@ struct LayerBufs {
   float *W, *Wt, *b, *z, *R, *T, *G, *m, *Gpart;
   float* Tpart;             // small problems: partial products of G p over chunks of n_in
   int wt_split, wt_chunk;   // number of such chunks (1 = the product is not split) and their length
-  float* p;                 // input of the layer, [N, ld_in]
+  float* p;                 // input of the layer, [N, ld_in] fp32 (null for l >= 2 in -Q: p_l is kept as indices)
   float *g, *d;             // l >= 2: gradient of phi in p, -Q trial direction
-  uint8_t* pidx;            // l >= 2, -Q
+  uint8_t* pidx;            // l >= 2, -Q: two planes of 8-bit indices into Delta, [2][idx_plane]; LayerScal::cur tells
+                            // which one holds p_l, the other takes the candidates of the backtracking trials
+  size_t idx_plane;         // bytes per plane (N * ld_in rounded up to 256)
   float *q, *u;             // l < L
   double *part_a, *part_b, *part_c, *colpart, *pairpart;
   int splitk, k_chunk;
@@ -121,7 +123,10 @@ struct pdadmm_ctx {
   int risk_blocks = 0;
   QuantGrid grid{0.f, 0.f, 0};
   // descriptor tables in device memory, each with the block maps of its launches
+  // Products over ALL layers come as two groups in -Q: layer 1 reads p_1 = X as fp32 (`..._f`, which holds every
+  // layer in pdADMM-G), the layers above read their p_l as indices (`..._q`, its own kernel instance).
   Group<GemmProb> g_pgrad, g_ptrial, g_wgrad, g_wtrial, g_resid, g_resid_obj;
+  Group<GemmProb> g_wgrad_q, g_wtrial_q, g_resid_q, g_resid_obj_q;
   std::vector<GemmProb> fwd;          // forward pass of the starting point: one by-value launch per layer
   Group<ReduceProb> g_red, g_tred;
   bool spec_p = false;        // pdADMM-G, not small: the p-step and r -= Wg/tau ride in the product epilogues with
@@ -358,12 +363,13 @@ size_t plan(pdadmm_ctx* c, void* base) {
     b.z = cv.take<float>(out_sz);
     b.R = cv.take<float>(out_sz);
     b.T = cv.take<float>(out_sz);
-    b.p = cv.take<float>(in_sz);
+    b.p = (i == 0 || !Q) ? cv.take<float>(in_sz) : nullptr;
     if (i >= 1) {
       b.g = cv.take<float>(in_sz);
       if (Q) {
         b.d = cv.take<float>(in_sz);
-        b.pidx = cv.take<uint8_t>(in_sz);
+        b.idx_plane = (in_sz + 255) & ~size_t(255);
+        b.pidx = cv.take<uint8_t>(2 * b.idx_plane);
       }
     }
     if (i < L - 1) {
@@ -392,6 +398,10 @@ size_t plan(pdadmm_ctx* c, void* base) {
   c->g_wtrial.dev = cv.take<GemmProb>(L);
   c->g_resid.dev = cv.take<GemmProb>(L);
   c->g_resid_obj.dev = cv.take<GemmProb>(L);
+  c->g_wgrad_q.dev = cv.take<GemmProb>(L);
+  c->g_wtrial_q.dev = cv.take<GemmProb>(L);
+  c->g_resid_q.dev = cv.take<GemmProb>(L);
+  c->g_resid_obj_q.dev = cv.take<GemmProb>(L);
   c->g_red.dev = cv.take<ReduceProb>(L);
   c->g_tred.dev = cv.take<ReduceProb>(L);
   c->g_pstep.dev = cv.take<AxpySeg>(2 * L);
@@ -426,6 +436,9 @@ GemmProb make_nt(const float* A, int lda, const float* B, int ldb, float* C, int
   P.beta = 0.f;
   P.slope = 0.f;
   P.layer = 0;
+  P.p8 = nullptr;
+  P.p8_plane = 0;
+  P.o8 = nullptr;
   return P;
 }
 
@@ -451,6 +464,13 @@ pdadmm_status build_tables(pdadmm_ctx* c) {
   const float rho = c->cfg.rho, nu = c->cfg.nu;
   const bool Q = c->cfg.quantize != 0;
   std::vector<GemmProb> pgrad, ptrial, wgrad, wtrial, resid, resid_obj, fwd;
+  std::vector<GemmProb> wgrad_q, wtrial_q, resid_q, resid_obj_q;     // -Q: the layers whose p_l is kept as indices
+  // give a product descriptor its p_l as indices (operand or epilogue input, by the kernel it is launched with)
+  auto as_indices = [&](GemmProb& P, const LayerBufs& b) {
+    P.p8 = b.pidx;
+    P.p8_plane = b.idx_plane;
+    P.grid = c->grid;
+  };
   std::vector<ReduceProb> red, tred;
   std::vector<AxpySeg> pstep, pfix, qapply_r;
   std::vector<SelectDesc> sel_p, sel_w, sel_q;
@@ -466,6 +486,7 @@ pdadmm_status build_tables(pdadmm_ctx* c) {
       GemmProb P = make_nt(b.R, b.ld_out, b.Wt, b.ld_out, b.g, b.ld_in, N, b.n_in, b.n_out);
       P.e0 = c->lay[i - 1].u; P.e1 = b.p; P.e2 = c->lay[i - 1].q;
       P.alpha = nu; P.beta = rho; P.part = b.part_a; P.layer = i;
+      if (Q) as_indices(P, b);                   // the epilogue reads p_l as indices
       if (c->spec_p) P.o1 = b.p;                 // p -= g / tau_prev in the epilogue
       pgrad.push_back(P);
       // image of the step direction under W_l: T = dir W^T (dir = g, or d in -Q)
@@ -488,13 +509,13 @@ pdadmm_status build_tables(pdadmm_ctx* c) {
         r.nblk = std::min(1024, chunk_blocks(r.n4, 1));
         pfix.push_back(a);
         pfix.push_back(r);
-      } else {
+      } else if (!Q) {                         // (-Q takes its step through the projection)
         pstep.push_back(a);
         pstep.push_back(r);
       }
       if (Q) {
         QuantSeg qs{};
-        qs.p = b.p; qs.g = b.g; qs.d = b.d; qs.idx = b.pidx; qs.dpart = b.part_c;
+        qs.p8 = b.pidx; qs.p8_plane = b.idx_plane; qs.g = b.g; qs.d = b.d; qs.dpart = b.part_c;
         qs.n4 = (size_t)N * b.ld_in / 4; qs.ncols = b.n_in; qs.ld = b.ld_in;
         qs.nblk = chunk_blocks(qs.n4, kQuantUnroll); qs.layer = i;
         quant.push_back(qs);
@@ -509,7 +530,9 @@ pdadmm_status build_tables(pdadmm_ctx* c) {
     // gradient of phi in W_l: G = nu * R^T p  (contraction over the nodes, split in chunks)
     GemmProb Wg = make_tn(b.R, b.ld_out, b.p, b.ld_in, b.Gpart, b.ld_in, b.n_out, b.n_in, N, b.splitk, b.k_chunk);
     Wg.layer = i;
-    wgrad.push_back(Wg);
+    const bool as_idx = Q && i >= 1;
+    if (as_idx) as_indices(Wg, b);
+    (as_idx ? wgrad_q : wgrad).push_back(Wg);
     ReduceProb rp{};
     rp.part = b.Gpart; rp.G = b.G; rp.norm_part = b.part_a; rp.M = b.n_out; rp.N = b.n_in; rp.ld = b.ld_in;
     rp.splitk = b.splitk; rp.alpha = nu; rp.vec = 1;
@@ -536,7 +559,8 @@ pdadmm_status build_tables(pdadmm_ctx* c) {
       tred.push_back(tr);
       t_partials = tr.nblk;
     }
-    wtrial.push_back(Wt_);
+    if (as_idx) as_indices(Wt_, b);
+    (as_idx ? wtrial_q : wtrial).push_back(Wt_);
     SelectDesc sw{};
     sw.part_g = b.part_a; sw.ng = rp.nblk; sw.part_t = b.part_b; sw.nt = t_partials; sw.stride_t = 1; sw.layer = i;
     sel_w.push_back(sw);
@@ -547,14 +571,16 @@ pdadmm_status build_tables(pdadmm_ctx* c) {
     // carried residual from scratch: R = p W^T + b - z
     GemmProb Rf = make_nt(b.p, b.ld_in, b.W, b.ld_in, b.R, b.ld_out, N, b.n_out, b.n_in);
     Rf.e0 = b.b; Rf.e1 = b.z; Rf.e2 = nullptr; Rf.part = b.part_b; Rf.layer = i;
-    resid.push_back(Rf);
+    if (as_idx) as_indices(Rf, b);
+    (as_idx ? resid_q : resid).push_back(Rf);
     GemmProb Ro = Rf;
     Ro.C = b.T; Ro.e2 = b.R;
-    resid_obj.push_back(Ro);
+    (as_idx ? resid_obj_q : resid_obj).push_back(Ro);
     // forward pass of the starting point
     GemmProb Fw = make_nt(b.p, b.ld_in, b.W, b.ld_in, b.z, b.ld_out, N, b.n_out, b.n_in);
     Fw.e0 = b.b;
-    if (i < L - 1) { Fw.o1 = b.q; Fw.o2 = c->lay[i + 1].p; }
+    if (i < L - 1) { Fw.o1 = b.q; Fw.o2 = c->lay[i + 1].p; Fw.o8 = Q ? c->lay[i + 1].pidx : nullptr; }
+    if (as_idx) as_indices(Fw, b);             // plane 0 holds p_l at the start (LayerScal::cur = 0)
     Fw.grid = Q ? c->grid : QuantGrid{0.f, 0.f, 0};
     Fw.beta = c->cfg.quantize == 2 ? 1.0f : 0.0f;
     Fw.slope = c->cfg.leaky_slope;
@@ -563,6 +589,8 @@ pdadmm_status build_tables(pdadmm_ctx* c) {
     RowSeg rs{};
     rs.R = b.R; rs.T = b.T; rs.z = b.z; rs.q = b.q; rs.u = b.u;
     rs.pnext = i < L - 1 ? c->lay[i + 1].p : nullptr;
+    rs.pnext8 = (Q && i < L - 1) ? c->lay[i + 1].pidx : nullptr;
+    rs.p8_plane = (Q && i < L - 1) ? c->lay[i + 1].idx_plane : 0;
     rs.m = b.m; rs.colpart = b.colpart;
     rs.rows = N; rs.ncols = b.n_out; rs.ld = b.ld_out;
     rs.cw = b.cw; rs.col_blocks = b.col_blocks; rs.row_blocks = b.row_blocks; rs.nblk = b.col_blocks * b.row_blocks;
@@ -576,6 +604,8 @@ pdadmm_status build_tables(pdadmm_ctx* c) {
     if (i < L - 1) {
       PairSeg ps{};
       ps.z = b.z; ps.q = b.q; ps.u = b.u; ps.pnext = c->lay[i + 1].p; ps.part = b.pairpart;
+      ps.pnext8 = Q ? c->lay[i + 1].pidx : nullptr; ps.p8_plane = Q ? c->lay[i + 1].idx_plane : 0;
+      ps.next_layer = i + 1; ps.ncols = b.n_out; ps.ld = b.ld_out;
       ps.n4 = (size_t)N * b.ld_out / 4; ps.nblk = flat_blocks(ps.n4);
       pair.push_back(ps);
     }
@@ -598,6 +628,7 @@ pdadmm_status build_tables(pdadmm_ctx* c) {
   } while (0)
   UP(c->g_pgrad, pgrad); UP(c->g_ptrial, ptrial); UP(c->g_wgrad, wgrad); UP(c->g_wtrial, wtrial);
   UP(c->g_resid, resid); UP(c->g_resid_obj, resid_obj); UP(c->g_red, red); UP(c->g_tred, tred);
+  UP(c->g_wgrad_q, wgrad_q); UP(c->g_wtrial_q, wtrial_q); UP(c->g_resid_q, resid_q); UP(c->g_resid_obj_q, resid_obj_q);
   UP(c->g_pstep, pstep); UP(c->g_pfix, pfix); UP(c->g_qapply_r, qapply_r);
   UP(c->g_w, wseg); UP(c->g_rows_all, rows); UP(c->g_bias, bias); UP(c->g_quant, quant); UP(c->g_pair, pair);
 #undef UP
@@ -624,22 +655,30 @@ void launch_group(pdadmm_ctx* c, const Group<T>& g, K kernel, Args... args) {
 
 // VECC = true: every problem of the group writes (and reads its epilogue inputs from) workspace arrays,
 // which are 16-byte aligned with leading dimensions that are multiples of 4.
-template <bool KC, class Epi, bool VECC = false>
+// P8: the operand that carries p_l is read as 8-bit indices (the `..._q` groups of a -Q context).
+template <bool KC, class Epi, bool VECC = false, bool P8 = false>
 void launch_gemm(pdadmm_ctx* c, const Group<GemmProb>& g, int predicated) {
   const int panel = KC ? c->panel : c->panel_tn;
   for (size_t k = 0; k < g.maps.size(); ++k) {
     if (g.maps[k].total <= 0) continue;
-    hipLaunchKernelGGL((gemm_kernel<Tile, KC, Epi, VECC>), dim3(xcd_padded(g.maps[k].total, panel)), dim3(256), 0,
+    hipLaunchKernelGGL((gemm_kernel<Tile, KC, Epi, VECC, P8>), dim3(xcd_padded(g.maps[k].total, panel)), dim3(256), 0,
                        c->stream, (const GemmProb*)(g.dev + g.start[k]), g.maps[k], (const LayerScal*)c->scal,
                        predicated, panel);
   }
+}
+
+// A product over all layers: the group that reads p_l as fp32 and, in -Q, the group that reads it as indices.
+template <bool KC, class Epi, bool VECC>
+void launch_gemm_all(pdadmm_ctx* c, const Group<GemmProb>& f, const Group<GemmProb>& q) {
+  launch_gemm<KC, Epi, VECC, false>(c, f, 0);
+  if (q.count > 0) launch_gemm<KC, Epi, VECC, true>(c, q, 0);
 }
 
 pdadmm_status refresh_residual(pdadmm_ctx* c) {
   // transposed weights, then R = p W^T + b - z for every layer
   { TIMED(c, kClsRefresh); launch_group(c, c->g_w, w_step_kernel, (const LayerScal*)c->scal, 1); }
   LAUNCH_CHECK(c, "w_step(copy)");
-  { TIMED(c, kClsRefresh); launch_gemm<true, EpiResid>(c, c->g_resid, 0); }
+  { TIMED(c, kClsRefresh); launch_gemm_all<true, EpiResid, false>(c, c->g_resid, c->g_resid_q); }
   LAUNCH_CHECK(c, "gemm resid");
   c->dirty = false;
   return PDADMM_OK;
@@ -650,6 +689,7 @@ pdadmm_status phase_p(pdadmm_ctx* c) {
   if (L < 2) return PDADMM_OK;
   const pdadmm_config& g = c->cfg;
   if (c->spec_p) { TIMED(c, kClsGemmPGrad); launch_gemm<true, EpiPGradUpd, true>(c, c->g_pgrad, 0); }
+  else if (g.quantize) { TIMED(c, kClsGemmPGrad); launch_gemm<true, EpiPGradQ, true>(c, c->g_pgrad, 0); }
   else { TIMED(c, kClsGemmPGrad); launch_gemm<true, EpiPGrad, true>(c, c->g_pgrad, 0); }
   LAUNCH_CHECK(c, "gemm pgrad");
   if (!g.quantize) {
@@ -694,8 +734,8 @@ pdadmm_status phase_p(pdadmm_ctx* c) {
     for (int i = 1; i < L; ++i) any = any || c->h_flags[i] != 0;
     if (!any) break;
   }
-  { TIMED(c, kClsQuantApply); launch_group(c, c->g_quant, quant_apply_kernel, (const LayerScal*)c->scal, c->grid); }
-  LAUNCH_CHECK(c, "quant apply");
+  // the accepted candidate already sits in the index plane that the selection has made current; what is left
+  // is the residual r += W d of the layers that took a step
   { TIMED(c, kClsQuantApply); launch_group(c, c->g_qapply_r, axpy_kernel, (const LayerScal*)c->scal); }
   LAUNCH_CHECK(c, "quant apply R");
   return PDADMM_OK;
@@ -704,20 +744,20 @@ pdadmm_status phase_p(pdadmm_ctx* c) {
 pdadmm_status phase_w(pdadmm_ctx* c) {
   const int L = c->L;
   const pdadmm_config& g = c->cfg;
-  { TIMED(c, kClsGemmWGrad); launch_gemm<false, EpiStore, true>(c, c->g_wgrad, 0); }
+  { TIMED(c, kClsGemmWGrad); launch_gemm_all<false, EpiStore, true>(c, c->g_wgrad, c->g_wgrad_q); }
   LAUNCH_CHECK(c, "gemm wgrad");
   { TIMED(c, kClsSplitkReduce); launch_group(c, c->g_red, splitk_reduce_kernel); }
   LAUNCH_CHECK(c, "splitk reduce");
   if (c->small_wtrial) {
-    { TIMED(c, kClsGemmTrial); launch_gemm<true, EpiStore, true>(c, c->g_wtrial, 0); }
+    { TIMED(c, kClsGemmTrial); launch_gemm_all<true, EpiStore, true>(c, c->g_wtrial, c->g_wtrial_q); }
     LAUNCH_CHECK(c, "gemm wtrial (chunks)");
     { TIMED(c, kClsSplitkReduce); launch_group(c, c->g_tred, splitk_reduce_kernel); }
     LAUNCH_CHECK(c, "wtrial chunk sum");
   } else if (c->spec_w) {
-    { TIMED(c, kClsGemmTrial); launch_gemm<true, EpiTrialW, true>(c, c->g_wtrial, 0); }
+    { TIMED(c, kClsGemmTrial); launch_gemm_all<true, EpiTrialW, true>(c, c->g_wtrial, c->g_wtrial_q); }
     LAUNCH_CHECK(c, "gemm wtrial");
   } else {
-    { TIMED(c, kClsGemmTrial); launch_gemm<true, EpiStoreNorm, true>(c, c->g_wtrial, 0); }
+    { TIMED(c, kClsGemmTrial); launch_gemm_all<true, EpiStoreNorm, true>(c, c->g_wtrial, c->g_wtrial_q); }
     LAUNCH_CHECK(c, "gemm wtrial");
   }
   { TIMED(c, kClsSelect); hipLaunchKernelGGL(select_step_kernel, dim3(L), dim3(256), 0, c->stream, c->sel_w, c->scal, 1, g.rho, g.nu,
@@ -768,7 +808,8 @@ pdadmm_status phase_bzqu(pdadmm_ctx* c) {
   { TIMED(c, kClsBias); launch_group(c, c->g_bias, bias_step_kernel); }
   LAUNCH_CHECK(c, "bias step");
   if (L > 1) {
-    { TIMED(c, kClsZqu); launch_group(c, c->g_rows_hidden, zqu_kernel, g.rho, g.nu, g.leaky_slope,
+    { TIMED(c, kClsZqu); launch_group(c, c->g_rows_hidden, zqu_kernel, (const LayerScal*)c->scal, g.rho, g.nu, g.leaky_slope,
+                                      g.quantize ? c->grid : QuantGrid{0.f, 0.f, 0},
                                       g.quantize == 2 ? c->grid : QuantGrid{0.f, 0.f, 0}); }
     LAUNCH_CHECK(c, "zqu");
   }
@@ -782,6 +823,15 @@ pdadmm_status check_device_flags(pdadmm_ctx* c) {
   e = c->h_flags[0];
   if (e & kErrNonFinite) return fail(c, PDADMM_ENONFINITE, "a step-size norm became NaN/Inf");
   if (e & kErrBacktrack) return fail(c, PDADMM_EBACKTRACK, "bt_max_trials exceeded");
+  return PDADMM_OK;
+}
+
+// Which index plane of layer i (0-based, >= 1, -Q) holds p_l. Synchronises.
+pdadmm_status current_plane(pdadmm_ctx* c, int i, int* cur) {
+  HIP_TRY(c, hipMemcpyAsync(c->h_flags, reinterpret_cast<const char*>(c->scal + i) + offsetof(LayerScal, cur), sizeof(int),
+                            hipMemcpyDeviceToHost, c->stream));
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  *cur = c->h_flags[0] & 1;
   return PDADMM_OK;
 }
 
@@ -799,7 +849,8 @@ pdadmm_status locate(pdadmm_ctx* c, int kind, int layer, bool writing, VarRef* v
   switch (kind) {
     case PDADMM_VAR_P:
       if (writing && layer == 1) return fail(c, PDADMM_EINVAL, "p_1 = X is fixed");
-      *v = {b.p, c->N, b.n_in, b.ld_in, sizeof(float)};
+      // -Q, l >= 2: p_l exists as indices only; values pass through the trial-direction buffer of the layer
+      *v = {b.p ? b.p : b.d, c->N, b.n_in, b.ld_in, sizeof(float)};
       return PDADMM_OK;
     case PDADMM_VAR_W: *v = {b.W, b.n_out, b.n_in, b.ld_in, sizeof(float)}; return PDADMM_OK;
     case PDADMM_VAR_B: *v = {b.b, 1, b.n_out, b.ld_out, sizeof(float)}; return PDADMM_OK;
@@ -811,7 +862,7 @@ pdadmm_status locate(pdadmm_ctx* c, int kind, int layer, bool writing, VarRef* v
       return PDADMM_OK;
     case PDADMM_VAR_PIDX:
       if (writing || !c->cfg.quantize || layer < 2) return fail(c, PDADMM_EINVAL, "PIDX: get only, -Q, l >= 2");
-      *v = {b.pidx, c->N, b.n_in, b.ld_in, 1};
+      *v = {b.pidx, c->N, b.n_in, b.ld_in, 1};      // plane 0; the caller adds the current plane
       return PDADMM_OK;
     case PDADMM_VAR_RESID:
       if (writing) return fail(c, PDADMM_EINVAL, "read-only variable");
@@ -1073,20 +1124,16 @@ pdadmm_status init_common(pdadmm_ctx** out, const pdadmm_config* cfg, void* work
   pdadmm_status s = build_tables(c);
   if (s != PDADMM_OK) return s;
   // forward-consistent start, layer after layer
+  // (-Q: the epilogue of layer l writes p_{l+1} as indices, which the product of layer l+1 then reads)
   for (int i = 0; i < L; ++i) {
     const GemmProb& F = c->fwd[i];
-    hipLaunchKernelGGL((gemm_one_kernel<Tile, true, EpiForward>), dim3(xcd_padded(F.nblk, c->panel)), dim3(256), 0,
-                       c->stream, F, c->panel);
+    if (F.p8)
+      hipLaunchKernelGGL((gemm_one_kernel<Tile, true, EpiForward, true>), dim3(xcd_padded(F.nblk, c->panel)), dim3(256),
+                         0, c->stream, F, c->panel);
+    else
+      hipLaunchKernelGGL((gemm_one_kernel<Tile, true, EpiForward, false>), dim3(xcd_padded(F.nblk, c->panel)), dim3(256),
+                         0, c->stream, F, c->panel);
     LAUNCH_CHECK(c, "gemm forward");
-  }
-  if (cfg->quantize) {
-    for (int i = 1; i < L; ++i) {
-      const LayerBufs& b = c->lay[i];
-      const size_t n4 = (size_t)N * b.ld_in / 4;
-      hipLaunchKernelGGL(quantize_kernel, dim3(flat_blocks(n4)), dim3(256), 0, c->stream, b.p, n4, b.n_in, b.ld_in,
-                         c->grid, b.pidx, (float*)nullptr);
-      LAUNCH_CHECK(c, "quantize idx");
-    }
   }
   c->dirty = true;
   HIP_TRY(c, hipStreamSynchronize(c->stream));
@@ -1152,11 +1199,13 @@ pdadmm_status pdadmm_set_var(pdadmm_ctx* c, int32_t kind, int32_t layer, const v
                        c->grid, (uint8_t*)nullptr, b.q);
     LAUNCH_CHECK(c, "quantize set_var q");
   }
-  if (kind == PDADMM_VAR_P && c->cfg.quantize) {
+  if (kind == PDADMM_VAR_P && c->cfg.quantize) {     // the values sit in the layer's d buffer: keep their indices
     const LayerBufs& b = c->lay[layer - 1];
     const size_t n4 = (size_t)c->N * b.ld_in / 4;
-    hipLaunchKernelGGL(quantize_kernel, dim3(flat_blocks(n4)), dim3(256), 0, c->stream, b.p, n4, b.n_in, b.ld_in,
-                       c->grid, b.pidx, b.p);
+    int cur = 0;
+    if ((s = current_plane(c, layer - 1, &cur)) != PDADMM_OK) return s;
+    hipLaunchKernelGGL(quantize_kernel, dim3(flat_blocks(n4)), dim3(256), 0, c->stream, (const float*)b.d, n4, b.n_in,
+                       b.ld_in, c->grid, b.pidx + (size_t)cur * b.idx_plane, (float*)nullptr);
     LAUNCH_CHECK(c, "quantize set_var");
   }
   HIP_TRY(c, hipStreamSynchronize(c->stream));
@@ -1188,6 +1237,20 @@ pdadmm_status pdadmm_get_var(pdadmm_ctx* c, int32_t kind, int32_t layer, void* d
   if (s != PDADMM_OK) return s;
   if (kind == PDADMM_VAR_RESID && c->dirty) {
     if ((s = refresh_residual(c)) != PDADMM_OK) return s;
+  }
+  if ((kind == PDADMM_VAR_P || kind == PDADMM_VAR_PIDX) && c->cfg.quantize && layer >= 2) {
+    const LayerBufs& b = c->lay[layer - 1];
+    int cur = 0;
+    if ((s = current_plane(c, layer - 1, &cur)) != PDADMM_OK) return s;
+    const uint8_t* plane = b.pidx + (size_t)cur * b.idx_plane;
+    if (kind == PDADMM_VAR_PIDX) {
+      v.ptr = const_cast<uint8_t*>(plane);
+    } else {                                        // values into the layer's d buffer (scratch between iterations)
+      const size_t n4 = (size_t)c->N * b.ld_in / 4;
+      hipLaunchKernelGGL(dequantize_kernel, dim3(flat_blocks(n4)), dim3(256), 0, c->stream, plane, n4, b.n_in, b.ld_in,
+                         c->grid, b.d);
+      LAUNCH_CHECK(c, "dequantize get_var");
+    }
   }
   HIP_TRY(c, hipMemcpy2DAsync(dst, (size_t)v.cols * v.elem, v.ptr, (size_t)v.ld * v.elem, (size_t)v.cols * v.elem,
                               v.rows, hipMemcpyDefault, c->stream));
@@ -1280,7 +1343,8 @@ static pdadmm_status pair_sums(pdadmm_ctx* c, std::vector<double>* act, std::vec
   dl->assign(L, 0.0);
   dq->assign(L, 0.0);
   if (L < 2) return PDADMM_OK;
-  launch_group(c, c->g_pair, pair_reduce_kernel, c->cfg.leaky_slope);
+  launch_group(c, c->g_pair, pair_reduce_kernel, (const LayerScal*)c->scal, c->cfg.leaky_slope,
+               c->cfg.quantize ? c->grid : QuantGrid{0.f, 0.f, 0});
   LAUNCH_CHECK(c, "pair reduce");
   std::vector<double> h;
   for (int i = 0; i < L - 1; ++i) {
@@ -1301,7 +1365,7 @@ static pdadmm_status pair_sums(pdadmm_ctx* c, std::vector<double>* act, std::vec
 static pdadmm_status fresh_residual_sums(pdadmm_ctx* c, double* lin, double* drift) {
   pdadmm_status s;
   if (c->dirty && (s = refresh_residual(c)) != PDADMM_OK) return s;
-  launch_gemm<true, EpiResid>(c, c->g_resid_obj, 0);
+  launch_gemm_all<true, EpiResid, false>(c, c->g_resid_obj, c->g_resid_obj_q);
   LAUNCH_CHECK(c, "gemm resid objective");
   *lin = 0.0;
   *drift = 0.0;
@@ -1379,8 +1443,10 @@ pdadmm_status pdadmm_stats(pdadmm_ctx* c, double* tau, double* theta, int32_t* p
   return check_device_flags(c);
 }
 
-pdadmm_status pdadmm_plan_info(pdadmm_ctx* c, int32_t* fused_updates, int32_t* wgrad_split, int32_t* wtrial_split) {
+pdadmm_status pdadmm_plan_info(pdadmm_ctx* c, int32_t* fused_updates, int32_t* wgrad_split, int32_t* wtrial_split,
+                               int32_t* p_bytes) {
   if (!c) return PDADMM_EINVAL;
+  if (p_bytes) *p_bytes = c->cfg.quantize ? 1 : 4;
   if (fused_updates) *fused_updates = (c->spec_p ? 1 : 0) | (c->spec_w ? 2 : 0);
   if (wgrad_split)
     for (int i = 0; i < c->L; ++i) wgrad_split[i] = c->lay[i].splitk;
