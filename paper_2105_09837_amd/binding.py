@@ -298,9 +298,9 @@ def _new_context(cfg, X_aug, labels, W0, b0, train_mask, stream, workspace, sour
     if need == 0:
         raise PdadmmError(1, "pdadmm_workspace_bytes", thread_error() or "invalid configuration")
     if workspace is None:
-        workspace = torch.empty(need + 256, dtype=torch.uint8, device=X_aug.device)
+        workspace = torch.empty(need + 4096, dtype=torch.uint8, device=X_aug.device)
     base = workspace.data_ptr()
-    aligned = (base + 255) & ~255
+    aligned = (base + 4095) & ~4095           # the library asks for 256; 4 KiB lets its arrays start on page boundaries
     avail = workspace.numel() - (aligned - base)
     L = len(cfg.dims) - 1
     Wp = (C.c_void_p * L)(*[_ptr(w) for w in W0])

@@ -304,7 +304,11 @@ __device__ __forceinline__ float z_closed_form(float s, float q, float slope) {
 //   q = (rho p_{l+1} + u + nu f(z)) / (rho + nu); r = p_{l+1} - q; u <- u + rho r.
 // In the variant that keeps q on the grid as well (Appendix B, last paragraph) the closed-form q is
 // projected onto Delta before r and u are formed.
-constexpr int kZquUnroll = 2;   // float4 groups per thread
+// One float4 group per thread: a block covers 4 KiB of each of its nine arrays (at 680 MB per array 9.82 ms against
+// 10.07 ms with two groups and 10.16 ms with four; with cached instead of nontemporal loads or stores 10.6-10.8 ms).
+constexpr int kZquUnroll = 1;
+__device__ __forceinline__ f32x4 zqu_load(const f32x4* p) { return __builtin_nontemporal_load(p); }
+__device__ __forceinline__ void zqu_store(f32x4* p, f32x4 v) { __builtin_nontemporal_store(v, p); }
 
 // pgrid: Delta when p_{l+1} is kept as 8-bit indices (-Q; levels = 0 otherwise); qgrid: Delta when q is projected too.
 __global__ __launch_bounds__(256) void zqu_kernel(const RowSeg* __restrict__ segs, const BlockMap map,
@@ -327,9 +331,9 @@ __global__ __launch_bounds__(256) void zqu_kernel(const RowSeg* __restrict__ seg
   for (int k = 0; k < kZquUnroll; ++k) {
     const size_t i = base + (size_t)k * 256;
     if (i < n4) {
-      Rv[k] = stream_load(reinterpret_cast<const f32x4*>(S.R) + i);
-      zo[k] = stream_load(reinterpret_cast<const f32x4*>(S.z) + i);
-      qo[k] = stream_load(reinterpret_cast<const f32x4*>(S.q) + i);
+      Rv[k] = zqu_load(reinterpret_cast<const f32x4*>(S.R) + i);
+      zo[k] = zqu_load(reinterpret_cast<const f32x4*>(S.z) + i);
+      qo[k] = zqu_load(reinterpret_cast<const f32x4*>(S.q) + i);
       if (p8) {
         pn[k] = dequant4(__builtin_nontemporal_load(reinterpret_cast<const uint32_t*>(p8) + i), pgrid);
         if (S.ncols != S.ld) {        // index 0 in a pad column stands for no value
@@ -339,9 +343,9 @@ __global__ __launch_bounds__(256) void zqu_kernel(const RowSeg* __restrict__ seg
             if (col0 + c >= S.ncols) pn[k][c] = 0.0f;
         }
       } else {
-        pn[k] = stream_load(reinterpret_cast<const f32x4*>(S.pnext) + i);
+        pn[k] = zqu_load(reinterpret_cast<const f32x4*>(S.pnext) + i);
       }
-      uo[k] = stream_load(reinterpret_cast<const f32x4*>(S.u) + i);
+      uo[k] = zqu_load(reinterpret_cast<const f32x4*>(S.u) + i);
       mm[k] = reinterpret_cast<const f32x4*>(S.m)[i % ld4];
     }
   }
@@ -368,10 +372,10 @@ __global__ __launch_bounds__(256) void zqu_kernel(const RowSeg* __restrict__ seg
         for (int c = 0; c < 4; ++c)
           if (col0 + c >= S.ncols) { qn[c] = 0.0f; un[c] = 0.0f; }
       }
-      stream_store(reinterpret_cast<f32x4*>(S.z) + i, zn);
-      stream_store(reinterpret_cast<f32x4*>(S.R) + i, Rn);
-      stream_store(reinterpret_cast<f32x4*>(S.q) + i, qn);
-      stream_store(reinterpret_cast<f32x4*>(S.u) + i, un);
+      zqu_store(reinterpret_cast<f32x4*>(S.z) + i, zn);
+      zqu_store(reinterpret_cast<f32x4*>(S.R) + i, Rn);
+      zqu_store(reinterpret_cast<f32x4*>(S.q) + i, qn);
+      zqu_store(reinterpret_cast<f32x4*>(S.u) + i, un);
     }
   }
 }
@@ -484,7 +488,7 @@ struct QuantSeg {
 
 // A block owns kQuantUnroll * 256 consecutive float4 groups (one contiguous chunk per array); all loads of a
 // thread are issued before the first projection.
-constexpr int kQuantUnroll = 4;
+constexpr int kQuantUnroll = 2;
 
 __global__ __launch_bounds__(256) void quant_trial_kernel(const QuantSeg* __restrict__ segs, const BlockMap map,
                                                           const LayerScal* __restrict__ scal, QuantGrid grid) {
