@@ -78,7 +78,7 @@ def elementwise_bytes_per_iteration(dims, n_nodes, quant, fused, trials_per_iter
     return out
 
 
-def build_problem(w, device, use_graph=0, backoff=1):
+def build_problem(w, device, use_graph=0, backoff=1, streams=None):
     """Inputs -> HBM -> context with a perturbed (generic) state. Uses only the HIP library."""
     import torch
     import paper_2105_09837_amd as P
@@ -104,8 +104,10 @@ def build_problem(w, device, use_graph=0, backoff=1):
     cfg = P.Config(n_nodes=w.n_nodes, dims=list(w.dims), rho=w.rho, nu=w.nu, quantize=(2 if w.quant_q else 1) if q else 0,
                    q_lo=q[0] if q else -1.0, q_hi=q[1] if q else 1.0, q_levels=q[2] if q else 256,
                    use_graph=use_graph, bt_probe_backoff=backoff, risk_kind=P.RISK[w.risk])
-    ctx = P.pdadmm_init(cfg, Xa, torch.from_numpy(y).to(device), [torch.from_numpy(a).to(device) for a in Ws],
-                        [torch.from_numpy(a).to(device) for a in bs])
+    yd, Wd, bd = torch.from_numpy(y).to(device), [torch.from_numpy(a).to(device) for a in Ws], [torch.from_numpy(a).to(device) for a in bs]
+    torch.cuda.synchronize()
+    ctx = P.pdadmm_init(cfg, Xa, yd, Wd, bd, stream=streams[0] if streams else None,
+                        aux_stream=streams[1] if streams and len(streams) > 1 else None)
     # perturb the forward-consistent start (otherwise most layers sit at a fixed point for many iterations)
     L = w.n_layers
 
@@ -193,7 +195,8 @@ def measure(name, args, device, want_host=False):
 
     w = get_workload(name)
     backoff = 0 if args.plain_schedule else 1
-    ctx, info, host = build_problem(w, device, use_graph=1 if args.graph else 0, backoff=backoff)
+    streams = [torch.cuda.Stream() for _ in range(args.streams)] if args.streams > 1 else None
+    ctx, info, host = build_problem(w, device, use_graph=1 if args.graph else 0, backoff=backoff, streams=streams)
     if not want_host:
         host = None
     P.pdadmm_iterate(ctx, args.warmup)
@@ -245,7 +248,7 @@ def measure(name, args, device, want_host=False):
                config=dict(workload=f"{w.name}: N={w.n_nodes} {w.graph} graph, X {w.feat_dim}-dim, hops={w.hops} -> n0={w.n0}, "
                                     f"L={w.n_layers}, hidden={w.hidden}, classes={w.n_classes}, rho=nu={w.rho}"
                                     + (f", Delta={w.quant[2]} levels on [{w.quant[0]},{w.quant[1]}]" if w.quant else ""),
-                           variant=variant),
+                           variant=variant, streams=args.streams),
                gemm_tflops_whole_iteration=total_gemm_flops * args.steps / dt / 1e12,
                roofline=roofline,
                augment_ms=info["augment_ms"], build_s=info["build_s"], objective_after=obj["L_rho"],
@@ -305,6 +308,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--plain-schedule", action="store_true",
                     help="-Q: every p-update starts at tau/eta (bt_probe_backoff = 0) instead of the probe back-off")
+    ap.add_argument("--streams", type=int, default=1, choices=(1, 2),
+                    help="2: give the library a second stream for the independent parts of an iteration")
     ap.add_argument("--dominant-only", action="store_true",
                     help="record HIP events around the dominant kernel class only (default: every class)")
     ap.add_argument("--graph", action="store_true",

@@ -193,15 +193,23 @@ size_t pdadmm_workspace_bytes(const pdadmm_config* cfg);
  *             alive until pdadmm_destroy. X_aug [N, n_0], labels [N] int32 in [0, n_L),
  *             train_mask [N] uint8 or NULL (= every node labelled), W0[l-1] [n_l, n_{l-1}],
  *             b0[l-1] [n_l]: all DEVICE, copied during the call (the caller may free them afterwards).
- *  W0, b0: HOST arrays of L DEVICE pointers. stream: hipStream_t or NULL.
- * The call synchronises the stream before returning.
+ *  W0, b0: HOST arrays of L DEVICE pointers.
+ *  streams, n_streams: HOST array of 0, 1 or 2 hipStream_t (as void*). streams[0] (NULL or n_streams = 0: the
+ *             default stream) carries the iteration. streams[1], if given, must be another stream of the same
+ *             (default) priority: work of an iteration that does not depend on the main sequence is enqueued there
+ *             between event-ordered forks and joins - the W-update of layer 1, which needs nothing from the
+ *             p-updates (p_1 = X is fixed), beside the p-updates of the layers above, and the z_L-update beside the
+ *             fused z/q/u pass of the hidden layers (Algorithm 1: the updates of different layers are independent
+ *             within a phase). Results are the same bit for bit with one stream and with two. Every call that
+ *             synchronises waits for both.
+ * The call synchronises streams[0] before returning.
  * Errors: EINVAL (bad config, NULL pointer, unaligned workspace) and ENOMEM (workspace too small) leave
  * *out = NULL. A HIP failure after the context exists returns EHIP with *out set: read
  * pdadmm_last_error(*out), then pdadmm_destroy(*out).
  */
 pdadmm_status pdadmm_init(pdadmm_ctx** out, const pdadmm_config* cfg, void* workspace, size_t workspace_bytes,
                           const float* X_aug, const int32_t* labels, const uint8_t* train_mask,
-                          const float* const* W0, const float* const* b0, void* stream);
+                          const float* const* W0, const float* const* b0, void* const* streams, int32_t n_streams);
 
 /*
  * Greedy layer-wise training (Section 3.2, the paragraph after Algorithm 1; Section 5.3 trains 2, then
@@ -221,7 +229,7 @@ pdadmm_status pdadmm_init(pdadmm_ctx** out, const pdadmm_config* cfg, void* work
 pdadmm_status pdadmm_grow_layers(pdadmm_ctx** out, const pdadmm_config* cfg, void* workspace, size_t workspace_bytes,
                                  const float* X_aug, const int32_t* labels, const uint8_t* train_mask,
                                  pdadmm_ctx* from, const int32_t* from_layer, const float* const* W0,
-                                 const float* const* b0, void* stream);
+                                 const float* const* b0, void* const* streams, int32_t n_streams);
 
 /*
  * Copy a variable in or out. `layer` is the paper's l. The buffer is dense (leading dimension =

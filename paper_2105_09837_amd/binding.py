@@ -81,9 +81,9 @@ def load_library():
     lib.pdadmm_workspace_bytes.argtypes = [C.POINTER(_CConfig)]
     lib.pdadmm_workspace_bytes.restype = C.c_size_t
     lib.pdadmm_init.argtypes = [C.POINTER(vp), C.POINTER(_CConfig), vp, C.c_size_t, vp, vp, vp,
-                                C.POINTER(vp), C.POINTER(vp), vp]
+                                C.POINTER(vp), C.POINTER(vp), C.POINTER(vp), i32]
     lib.pdadmm_grow_layers.argtypes = [C.POINTER(vp), C.POINTER(_CConfig), vp, C.c_size_t, vp, vp, vp, vp, vp,
-                                       C.POINTER(vp), C.POINTER(vp), vp]
+                                       C.POINTER(vp), C.POINTER(vp), C.POINTER(vp), i32]
     lib.pdadmm_set_var.argtypes = [vp, i32, i32, vp]
     lib.pdadmm_get_var.argtypes = [vp, i32, i32, vp]
     lib.pdadmm_iterate.argtypes = [vp, i32]
@@ -277,20 +277,21 @@ def pdadmm_workspace_bytes(cfg: Config) -> int:
     return int(load_library().pdadmm_workspace_bytes(C.byref(cfg.to_c())))
 
 
-def pdadmm_init(cfg: Config, X_aug, labels, W0, b0, train_mask=None, stream=None, workspace=None) -> Context:
+def pdadmm_init(cfg: Config, X_aug, labels, W0, b0, train_mask=None, stream=None, workspace=None, aux_stream=None) -> Context:
     """Create a context. All tensors live on the GPU; the workspace tensor is allocated here with
-    torch (device memory plumbing) unless one is passed in."""
-    return _new_context(cfg, X_aug, labels, W0, b0, train_mask, stream, workspace, None, None)
+    torch (device memory plumbing) unless one is passed in. `stream`: the stream that carries the iteration
+    (None = the default stream); `aux_stream`: optional second stream for the independent parts of an iteration."""
+    return _new_context(cfg, X_aug, labels, W0, b0, train_mask, stream, workspace, None, None, aux_stream)
 
 
 def pdadmm_grow_layers(source: Context, from_layer, cfg: Config, X_aug, labels, W0, b0, train_mask=None, stream=None,
-                       workspace=None) -> Context:
+                       workspace=None, aux_stream=None) -> Context:
     """Deeper model from a trained one: layer l takes W, b from layer from_layer[l-1] of `source` where
     that entry is positive, else from W0[l-1], b0[l-1] (device tensors; None allowed for carried layers)."""
-    return _new_context(cfg, X_aug, labels, W0, b0, train_mask, stream, workspace, source, from_layer)
+    return _new_context(cfg, X_aug, labels, W0, b0, train_mask, stream, workspace, source, from_layer, aux_stream)
 
 
-def _new_context(cfg, X_aug, labels, W0, b0, train_mask, stream, workspace, source, from_layer) -> Context:
+def _new_context(cfg, X_aug, labels, W0, b0, train_mask, stream, workspace, source, from_layer, aux_stream=None) -> Context:
     import torch
     lib = load_library()
     cc = cfg.to_c()
@@ -306,18 +307,21 @@ def _new_context(cfg, X_aug, labels, W0, b0, train_mask, stream, workspace, sour
     Wp = (C.c_void_p * L)(*[_ptr(w) for w in W0])
     bp = (C.c_void_p * L)(*[_ptr(b) for b in b0])
     handle = C.c_void_p()
+    n_streams = 2 if aux_stream is not None else 1
+    streams = (C.c_void_p * 2)(_stream_ptr(stream), _stream_ptr(aux_stream))
     if source is None:
         what = "pdadmm_init"
         code = lib.pdadmm_init(C.byref(handle), C.byref(cc), aligned, avail, _ptr(X_aug), _ptr(labels),
-                               _ptr(train_mask), Wp, bp, _stream_ptr(stream))
+                               _ptr(train_mask), Wp, bp, streams, n_streams)
     else:
         what = "pdadmm_grow_layers"
         fl = np.ascontiguousarray(from_layer, dtype=np.int32)
         if fl.shape != (L,):
             raise ValueError("from_layer needs one entry per layer of the new model")
         code = lib.pdadmm_grow_layers(C.byref(handle), C.byref(cc), aligned, avail, _ptr(X_aug), _ptr(labels),
-                                      _ptr(train_mask), source.handle, fl.ctypes.data, Wp, bp, _stream_ptr(stream))
+                                      _ptr(train_mask), source.handle, fl.ctypes.data, Wp, bp, streams, n_streams)
     ctx = Context(handle, cfg, workspace, stream)
+    ctx.aux_stream = aux_stream
     if code != 0:
         detail = ctx.last_error() if handle else thread_error()
         raise PdadmmError(code, what, detail)

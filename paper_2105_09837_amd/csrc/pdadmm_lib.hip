@@ -86,6 +86,12 @@ struct Group {
   void build(T* table, const std::vector<T>& v, int n) {
     build(table, v, n, [](const T& e) { return e.nblk; });
   }
+  // entries [from, from + n) of an uploaded table as a group of their own (no device memory of its own)
+  void view(const Group<T>& whole, const std::vector<T>& v, int from, int n) {
+    n = std::max(0, std::min(n, (int)v.size() - from));
+    std::vector<T> part(v.begin() + std::min<size_t>(from, v.size()), v.begin() + std::min<size_t>(from, v.size()) + n);
+    build(whole.dev + from, part, n);
+  }
   // `blocks_of` gives the number of blocks of an entry (tables shared by kernels of different shapes)
   template <class F>
   void build(T* table, const std::vector<T>& v, int n, F blocks_of) {
@@ -114,7 +120,11 @@ struct pdadmm_ctx {
   pdadmm_config cfg;
   std::vector<int> dims;
   int N = 0, L = 0;
-  hipStream_t stream = nullptr;
+  hipStream_t stream = nullptr;   // where launches go right now (the caller's main stream unless swapped)
+  hipStream_t aux = nullptr;      // optional second caller stream for work that is independent of the main sequence
+  hipStream_t gaux = nullptr;     // its stand-in while an iteration is captured into a graph
+  hipEvent_t ev_fork[2] = {nullptr, nullptr}, ev_join[2] = {nullptr, nullptr};      // eager fork/join pairs
+  hipEvent_t ev_gfork[2] = {nullptr, nullptr}, ev_gjoin[2] = {nullptr, nullptr};    // the same inside a capture
   std::vector<LayerBufs> lay;
   LayerScal* scal = nullptr;
   int* err = nullptr;
@@ -131,6 +141,11 @@ struct pdadmm_ctx {
   // layer in pdADMM-G), the layers above read their p_l as indices (`..._q`, its own kernel instance).
   Group<GemmProb> g_pgrad, g_ptrial, g_wgrad, g_wtrial, g_resid, g_resid_obj;
   Group<GemmProb> g_wgrad_q, g_wtrial_q, g_resid_q, g_resid_obj_q;
+  // The W-update of layer 1 needs nothing from the p-updates (p_1 = X is fixed): with a second stream it runs beside
+  // them. Views of the W-phase tables: layer 1 alone, and the layers above it.
+  Group<GemmProb> v_wgrad_first, v_wgrad_rest, v_wtrial_first, v_wtrial_rest, g_none;
+  Group<ReduceProb> v_red_first, v_red_rest, v_tred_first, v_tred_rest;
+  Group<WStepSeg> v_w_first, v_w_rest;
   std::vector<GemmProb> fwd;          // forward pass of the starting point: one by-value launch per layer
   Group<ReduceProb> g_red, g_tred;
   bool spec_p = false;        // pdADMM-G, not small: the p-step and r -= Wg/tau ride in the product epilogues with
@@ -636,6 +651,16 @@ pdadmm_status build_tables(pdadmm_ctx* c) {
   UP(c->g_pstep, pstep); UP(c->g_pfix, pfix); UP(c->g_qapply_r, qapply_r);
   UP(c->g_w, wseg); UP(c->g_rows_all, rows); UP(c->g_bias, bias); UP(c->g_quant, quant); UP(c->g_pair, pair);
 #undef UP
+  c->v_wgrad_first.view(c->g_wgrad, wgrad, 0, 1);
+  c->v_wgrad_rest.view(c->g_wgrad, wgrad, 1, L);
+  c->v_wtrial_first.view(c->g_wtrial, wtrial, 0, 1);
+  c->v_wtrial_rest.view(c->g_wtrial, wtrial, 1, L);
+  c->v_red_first.view(c->g_red, red, 0, 1);
+  c->v_red_rest.view(c->g_red, red, 1, L);
+  c->v_tred_first.view(c->g_tred, tred, 0, 1);
+  c->v_tred_rest.view(c->g_tred, tred, 1, L);
+  c->v_w_first.view(c->g_w, wseg, 0, 1);
+  c->v_w_rest.view(c->g_w, wseg, 1, L);
   // the fused z/q/u pass walks the same table flat: 256*kZquUnroll float4 groups per block
   c->g_rows_hidden.build(c->g_rows_all.dev, rows, L - 1, [](const RowSeg& e) {
     return chunk_blocks((size_t)e.rows * (e.ld / 4), kZquUnroll);
@@ -745,32 +770,74 @@ pdadmm_status phase_p(pdadmm_ctx* c) {
   return PDADMM_OK;
 }
 
-pdadmm_status phase_w(pdadmm_ctx* c) {
+// The W-updates of all layers, of layer 1 alone, or of the layers above it.
+enum Part { kAll, kFirst, kRest };
+
+pdadmm_status phase_w(pdadmm_ctx* c, Part part = kAll) {
   const int L = c->L;
   const pdadmm_config& g = c->cfg;
-  { TIMED(c, kClsGemmWGrad); launch_gemm_all<false, EpiStore, true>(c, c->g_wgrad, c->g_wgrad_q); }
+  const int first = part == kRest ? 1 : 0, count = part == kAll ? L : part == kFirst ? 1 : L - 1;
+  if (count <= 0) return PDADMM_OK;
+  // fp32-p group and (in -Q) index-p group of each product; in -Q the fp32 group holds layer 1 only
+  const Group<GemmProb>& wgrad_f = part == kAll ? c->g_wgrad : part == kFirst ? c->v_wgrad_first : c->v_wgrad_rest;
+  const Group<GemmProb>& wtrial_f = part == kAll ? c->g_wtrial : part == kFirst ? c->v_wtrial_first : c->v_wtrial_rest;
+  const Group<GemmProb>& wgrad_q = part == kFirst ? c->g_none : c->g_wgrad_q;
+  const Group<GemmProb>& wtrial_q = part == kFirst ? c->g_none : c->g_wtrial_q;
+  const Group<ReduceProb>& red = part == kAll ? c->g_red : part == kFirst ? c->v_red_first : c->v_red_rest;
+  const Group<ReduceProb>& tred = part == kAll ? c->g_tred : part == kFirst ? c->v_tred_first : c->v_tred_rest;
+  const Group<WStepSeg>& wst = part == kAll ? c->g_w : part == kFirst ? c->v_w_first : c->v_w_rest;
+  { TIMED(c, kClsGemmWGrad); launch_gemm_all<false, EpiStore, true>(c, wgrad_f, wgrad_q); }
   LAUNCH_CHECK(c, "gemm wgrad");
-  { TIMED(c, kClsSplitkReduce); launch_group(c, c->g_red, splitk_reduce_kernel); }
+  { TIMED(c, kClsSplitkReduce); launch_group(c, red, splitk_reduce_kernel); }
   LAUNCH_CHECK(c, "splitk reduce");
   if (c->small_wtrial) {
-    { TIMED(c, kClsGemmTrial); launch_gemm_all<true, EpiStore, true>(c, c->g_wtrial, c->g_wtrial_q); }
+    { TIMED(c, kClsGemmTrial); launch_gemm_all<true, EpiStore, true>(c, wtrial_f, wtrial_q); }
     LAUNCH_CHECK(c, "gemm wtrial (chunks)");
-    { TIMED(c, kClsSplitkReduce); launch_group(c, c->g_tred, splitk_reduce_kernel); }
+    { TIMED(c, kClsSplitkReduce); launch_group(c, tred, splitk_reduce_kernel); }
     LAUNCH_CHECK(c, "wtrial chunk sum");
   } else if (c->spec_w) {
-    { TIMED(c, kClsGemmTrial); launch_gemm_all<true, EpiTrialW, true>(c, c->g_wtrial, c->g_wtrial_q); }
+    { TIMED(c, kClsGemmTrial); launch_gemm_all<true, EpiTrialW, true>(c, wtrial_f, wtrial_q); }
     LAUNCH_CHECK(c, "gemm wtrial");
   } else {
-    { TIMED(c, kClsGemmTrial); launch_gemm_all<true, EpiStoreNorm, true>(c, c->g_wtrial, c->g_wtrial_q); }
+    { TIMED(c, kClsGemmTrial); launch_gemm_all<true, EpiStoreNorm, true>(c, wtrial_f, wtrial_q); }
     LAUNCH_CHECK(c, "gemm wtrial");
   }
-  { TIMED(c, kClsSelect); hipLaunchKernelGGL(select_step_kernel, dim3(L), dim3(256), 0, c->stream, c->sel_w, c->scal, 1, g.rho, g.nu,
+  { TIMED(c, kClsSelect); hipLaunchKernelGGL(select_step_kernel, dim3(count), dim3(256), 0, c->stream, c->sel_w + first, c->scal, 1, g.rho, g.nu,
                      g.bt_eta, g.bt_max_trials, c->err); }
   LAUNCH_CHECK(c, "select theta");
-  { TIMED(c, kClsWStep); launch_group(c, c->g_w, w_step_kernel, (const LayerScal*)c->scal, 0); }
+  { TIMED(c, kClsWStep); launch_group(c, wst, w_step_kernel, (const LayerScal*)c->scal, 0); }
   LAUNCH_CHECK(c, "w step");
   return PDADMM_OK;
 }
+
+// Work that does not depend on what the main stream is doing goes to the second stream between a fork (the side
+// stream waits for everything enqueued on the main stream so far) and a join (the main stream waits for the side
+// stream). While an iteration is being captured the capture's own side stream and events stand in.
+struct SideStream {
+  pdadmm_ctx* c;
+  hipStream_t main, side;
+  hipEvent_t fork_ev, join_ev;
+  SideStream(pdadmm_ctx* ctx, int pair) : c(ctx), main(ctx->stream) {
+    const bool capturing = ctx->gstream && ctx->stream == ctx->gstream;
+    side = capturing ? ctx->gaux : ctx->aux;
+    fork_ev = capturing ? ctx->ev_gfork[pair] : ctx->ev_fork[pair];
+    join_ev = capturing ? ctx->ev_gjoin[pair] : ctx->ev_join[pair];
+  }
+  explicit operator bool() const { return side != nullptr; }
+  pdadmm_status fork() {
+    HIP_TRY(c, hipEventRecord(fork_ev, main));
+    HIP_TRY(c, hipStreamWaitEvent(side, fork_ev, 0));
+    c->stream = side;
+    return PDADMM_OK;
+  }
+  void back() { c->stream = main; }        // later launches go to the main stream again; the side stream runs on
+  pdadmm_status join() {
+    c->stream = main;
+    HIP_TRY(c, hipEventRecord(join_ev, side));
+    HIP_TRY(c, hipStreamWaitEvent(main, join_ev, 0));
+    return PDADMM_OK;
+  }
+};
 
 // z_L-update (Appendix A 'update z', l = L): FISTA for the cross-entropy risk, closed form for least squares.
 pdadmm_status launch_fista(pdadmm_ctx* c) {
@@ -811,13 +878,43 @@ pdadmm_status phase_bzqu(pdadmm_ctx* c) {
   LAUNCH_CHECK(c, "resid colsum");
   { TIMED(c, kClsBias); launch_group(c, c->g_bias, bias_step_kernel); }
   LAUNCH_CHECK(c, "bias step");
+  // the z_L-update touches the last layer only, the fused z/q/u pass the layers below it: side by side if possible
+  SideStream side(c, 1);
+  pdadmm_status s;
+  if (side && L > 1) {
+    if ((s = side.fork()) != PDADMM_OK) return s;
+    s = launch_fista(c);
+    side.back();
+    if (s != PDADMM_OK) return s;
+  }
   if (L > 1) {
     { TIMED(c, kClsZqu); launch_group(c, c->g_rows_hidden, zqu_kernel, (const LayerScal*)c->scal, g.rho, g.nu, g.leaky_slope,
                                       g.quantize ? c->grid : QuantGrid{0.f, 0.f, 0},
                                       g.quantize == 2 ? c->grid : QuantGrid{0.f, 0.f, 0}); }
     LAUNCH_CHECK(c, "zqu");
   }
+  if (side && L > 1) return side.join();
   return launch_fista(c);
+}
+
+// One iteration of Algorithm 1. With a second stream the W-update of layer 1 (which reads nothing the p-updates
+// write: p_1 = X is fixed) runs beside the p-updates.
+pdadmm_status one_iteration(pdadmm_ctx* c) {
+  pdadmm_status s;
+  SideStream side(c, 0);
+  if (side && c->L >= 2) {
+    if ((s = side.fork()) != PDADMM_OK) return s;
+    s = phase_w(c, kFirst);
+    side.back();
+    if (s != PDADMM_OK) return s;
+    if ((s = phase_p(c)) != PDADMM_OK) return s;
+    if ((s = phase_w(c, kRest)) != PDADMM_OK) return s;
+    if ((s = side.join()) != PDADMM_OK) return s;
+  } else {
+    if ((s = phase_p(c)) != PDADMM_OK) return s;
+    if ((s = phase_w(c, kAll)) != PDADMM_OK) return s;
+  }
+  return phase_bzqu(c);
 }
 
 pdadmm_status check_device_flags(pdadmm_ctx* c) {
@@ -1057,8 +1154,8 @@ namespace {
 // of the context `from` where that entry is positive, else from the dense caller arrays W0[i], b0[i].
 pdadmm_status init_common(pdadmm_ctx** out, const pdadmm_config* cfg, void* workspace, size_t workspace_bytes,
                           const float* X_aug, const int32_t* labels, const uint8_t* train_mask,
-                          const float* const* W0, const float* const* b0, void* stream, pdadmm_ctx* from,
-                          const int32_t* from_layer) {
+                          const float* const* W0, const float* const* b0, void* const* streams, int32_t n_streams,
+                          pdadmm_ctx* from, const int32_t* from_layer) {
   if (!out) return fail(nullptr, PDADMM_EINVAL, "out is NULL");
   *out = nullptr;
   std::string why;
@@ -1066,6 +1163,10 @@ pdadmm_status init_common(pdadmm_ctx** out, const pdadmm_config* cfg, void* work
   if (!workspace || !X_aug || !labels) return fail(nullptr, PDADMM_EINVAL, "workspace, X_aug or labels is NULL");
   if (reinterpret_cast<uintptr_t>(workspace) & 255) return fail(nullptr, PDADMM_EINVAL, "workspace is not 256-byte aligned");
   if (from && !from_layer) return fail(nullptr, PDADMM_EINVAL, "from_layer is NULL");
+  if (n_streams < 0 || n_streams > 2 || (n_streams > 0 && !streams))
+    return fail(nullptr, PDADMM_EINVAL, "n_streams must be 0, 1 or 2 (with a streams array)");
+  if (n_streams == 2 && (!streams[1] || streams[1] == streams[0]))
+    return fail(nullptr, PDADMM_EINVAL, "the second stream must be a stream of its own (not NULL, not the first)");
   for (int i = 0; i < cfg->n_layers; ++i) {
     const int src = from ? from_layer[i] : 0;
     const std::string lay = "layer " + std::to_string(i + 1) + ": ";
@@ -1088,7 +1189,8 @@ pdadmm_status init_common(pdadmm_ctx** out, const pdadmm_config* cfg, void* work
   c->dims.assign(cfg->dims, cfg->dims + cfg->n_layers + 1);
   c->cfg.dims = c->dims.data();
   c->p_products.assign(cfg->n_layers, 0);
-  c->stream = static_cast<hipStream_t>(stream);
+  c->stream = n_streams >= 1 ? static_cast<hipStream_t>(streams[0]) : nullptr;
+  c->aux = n_streams == 2 ? static_cast<hipStream_t>(streams[1]) : nullptr;
   if (cfg->quantize) c->grid = make_grid(cfg->q_lo, cfg->q_hi, cfg->q_levels);
   const size_t need = plan(c, nullptr);
   if (workspace_bytes < need) {
@@ -1146,6 +1248,19 @@ pdadmm_status init_common(pdadmm_ctx** out, const pdadmm_config* cfg, void* work
     HIP_TRY(c, hipEventCreateWithFlags(&c->ev_in, hipEventDisableTiming));
     HIP_TRY(c, hipEventCreateWithFlags(&c->ev_out, hipEventDisableTiming));
   }
+  if (c->aux) {
+    for (int k = 0; k < 2; ++k) {
+      HIP_TRY(c, hipEventCreateWithFlags(&c->ev_fork[k], hipEventDisableTiming));
+      HIP_TRY(c, hipEventCreateWithFlags(&c->ev_join[k], hipEventDisableTiming));
+    }
+    if (c->gstream) {     // the captured iteration forks into a side stream of its own
+      HIP_TRY(c, hipStreamCreateWithFlags(&c->gaux, hipStreamNonBlocking));
+      for (int k = 0; k < 2; ++k) {
+        HIP_TRY(c, hipEventCreateWithFlags(&c->ev_gfork[k], hipEventDisableTiming));
+        HIP_TRY(c, hipEventCreateWithFlags(&c->ev_gjoin[k], hipEventDisableTiming));
+      }
+    }
+  }
   return PDADMM_OK;
 }
 
@@ -1155,17 +1270,19 @@ extern "C" {
 
 pdadmm_status pdadmm_init(pdadmm_ctx** out, const pdadmm_config* cfg, void* workspace, size_t workspace_bytes,
                           const float* X_aug, const int32_t* labels, const uint8_t* train_mask,
-                          const float* const* W0, const float* const* b0, void* stream) {
+                          const float* const* W0, const float* const* b0, void* const* streams, int32_t n_streams) {
   if (!W0 || !b0) return fail(nullptr, PDADMM_EINVAL, "W0 or b0 is NULL");
-  return init_common(out, cfg, workspace, workspace_bytes, X_aug, labels, train_mask, W0, b0, stream, nullptr, nullptr);
+  return init_common(out, cfg, workspace, workspace_bytes, X_aug, labels, train_mask, W0, b0, streams, n_streams, nullptr,
+                     nullptr);
 }
 
 pdadmm_status pdadmm_grow_layers(pdadmm_ctx** out, const pdadmm_config* cfg, void* workspace, size_t workspace_bytes,
                                  const float* X_aug, const int32_t* labels, const uint8_t* train_mask,
                                  pdadmm_ctx* from, const int32_t* from_layer, const float* const* W0,
-                                 const float* const* b0, void* stream) {
+                                 const float* const* b0, void* const* streams, int32_t n_streams) {
   if (!from || !from_layer) return fail(nullptr, PDADMM_EINVAL, "from or from_layer is NULL");
-  return init_common(out, cfg, workspace, workspace_bytes, X_aug, labels, train_mask, W0, b0, stream, from, from_layer);
+  return init_common(out, cfg, workspace, workspace_bytes, X_aug, labels, train_mask, W0, b0, streams, n_streams, from,
+                     from_layer);
 }
 
 pdadmm_status pdadmm_set_var(pdadmm_ctx* c, int32_t kind, int32_t layer, const void* src) {
@@ -1194,8 +1311,11 @@ pdadmm_status pdadmm_set_var(pdadmm_ctx* c, int32_t kind, int32_t layer, const v
   VarRef v;
   pdadmm_status s = locate(c, kind, layer, true, &v);
   if (s != PDADMM_OK) return s;
-  HIP_TRY(c, hipMemcpy2DAsync(v.ptr, (size_t)v.ld * v.elem, src, (size_t)v.cols * v.elem, (size_t)v.cols * v.elem,
-                              v.rows, hipMemcpyDefault, c->stream));
+  if (v.ld == v.cols)     // rows are dense on both sides: one plain copy (much faster from pageable host memory)
+    HIP_TRY(c, hipMemcpyAsync(v.ptr, src, (size_t)v.rows * v.cols * v.elem, hipMemcpyDefault, c->stream));
+  else
+    HIP_TRY(c, hipMemcpy2DAsync(v.ptr, (size_t)v.ld * v.elem, src, (size_t)v.cols * v.elem, (size_t)v.cols * v.elem,
+                                v.rows, hipMemcpyDefault, c->stream));
   if (kind == PDADMM_VAR_Q && c->cfg.quantize == 2) {
     const LayerBufs& b = c->lay[layer - 1];
     const size_t n4 = (size_t)c->N * b.ld_out / 4;
@@ -1256,8 +1376,11 @@ pdadmm_status pdadmm_get_var(pdadmm_ctx* c, int32_t kind, int32_t layer, void* d
       LAUNCH_CHECK(c, "dequantize get_var");
     }
   }
-  HIP_TRY(c, hipMemcpy2DAsync(dst, (size_t)v.cols * v.elem, v.ptr, (size_t)v.ld * v.elem, (size_t)v.cols * v.elem,
-                              v.rows, hipMemcpyDefault, c->stream));
+  if (v.ld == v.cols)
+    HIP_TRY(c, hipMemcpyAsync(dst, v.ptr, (size_t)v.rows * v.cols * v.elem, hipMemcpyDefault, c->stream));
+  else
+    HIP_TRY(c, hipMemcpy2DAsync(dst, (size_t)v.cols * v.elem, v.ptr, (size_t)v.ld * v.elem, (size_t)v.cols * v.elem,
+                                v.rows, hipMemcpyDefault, c->stream));
   HIP_TRY(c, hipStreamSynchronize(c->stream));
   return PDADMM_OK;
 }
@@ -1268,7 +1391,7 @@ pdadmm_status pdadmm_step_phase(pdadmm_ctx* c, int32_t phase) {
   if (c->dirty && (s = refresh_residual(c)) != PDADMM_OK) return s;
   switch (phase) {
     case PDADMM_PHASE_P: return phase_p(c);
-    case PDADMM_PHASE_W: return phase_w(c);
+    case PDADMM_PHASE_W: return phase_w(c, kAll);
     case PDADMM_PHASE_BZQU: return phase_bzqu(c);
     default: return fail(c, PDADMM_EINVAL, "unknown phase");
   }
@@ -1287,9 +1410,7 @@ static pdadmm_status iterate_graph(pdadmm_ctx* c, int32_t n_iters) {
     hipStream_t user = c->stream;
     HIP_TRY(c, hipStreamBeginCapture(c->gstream, hipStreamCaptureModeThreadLocal));
     c->stream = c->gstream;
-    s = phase_p(c);
-    if (s == PDADMM_OK) s = phase_w(c);
-    if (s == PDADMM_OK) s = phase_bzqu(c);
+    s = one_iteration(c);
     c->stream = user;
     const hipError_t e = hipStreamEndCapture(c->gstream, &c->graph);
     if (s != PDADMM_OK || e != hipSuccess) {     // a phase failed while recording: drop what was captured
@@ -1319,9 +1440,7 @@ pdadmm_status pdadmm_iterate(pdadmm_ctx* c, int32_t n_iters) {
   for (int it = 0; it < n_iters; ++it) {
     const bool periodic = c->cfg.refresh_every > 0 && c->iter > 0 && c->iter % c->cfg.refresh_every == 0;
     if ((c->dirty || periodic) && (s = refresh_residual(c)) != PDADMM_OK) return s;
-    if ((s = phase_p(c)) != PDADMM_OK) return s;
-    if ((s = phase_w(c)) != PDADMM_OK) return s;
-    if ((s = phase_bzqu(c)) != PDADMM_OK) return s;
+    if ((s = one_iteration(c)) != PDADMM_OK) return s;
     ++c->iter;
   }
   return PDADMM_OK;
@@ -1535,12 +1654,18 @@ const char* pdadmm_last_error(const pdadmm_ctx* c) { return c ? c->msg.c_str() :
 void pdadmm_destroy(pdadmm_ctx* c) {
   if (!c) return;
   (void)hipStreamSynchronize(c->stream);
+  if (c->aux) (void)hipStreamSynchronize(c->aux);
   if (c->gstream) (void)hipStreamSynchronize(c->gstream);
+  if (c->gaux) (void)hipStreamSynchronize(c->gaux);
   if (c->graph_exec) (void)hipGraphExecDestroy(c->graph_exec);
   if (c->graph) (void)hipGraphDestroy(c->graph);
   if (c->ev_in) (void)hipEventDestroy(c->ev_in);
   if (c->ev_out) (void)hipEventDestroy(c->ev_out);
   if (c->gstream) (void)hipStreamDestroy(c->gstream);
+  if (c->gaux) (void)hipStreamDestroy(c->gaux);
+  for (int k = 0; k < 2; ++k)
+    for (hipEvent_t e : {c->ev_fork[k], c->ev_join[k], c->ev_gfork[k], c->ev_gjoin[k]})
+      if (e) (void)hipEventDestroy(e);
   if (c->h_flags) (void)hipHostFree(c->h_flags);
   for (auto& t : c->timed) {
     (void)hipEventDestroy(t.a);

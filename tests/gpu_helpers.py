@@ -17,9 +17,10 @@ def config_of(w, **kw) -> P.Config:
     return P.Config(**base)
 
 
-def gpu_context(w, inp, st=None, **kw):
+def gpu_context(w, inp, st=None, stream=None, aux_stream=None, **kw):
     """Context initialised from the oracle-side inputs; if an oracle state is given, its variables are
-    copied in so that both sides start from bit-identical fp32 values."""
+    copied in so that both sides start from bit-identical fp32 values. `stream`, `aux_stream`: torch
+    streams for the iteration and for its independent parts (default: the default stream alone)."""
     import torch
     dev = torch.device("cuda:0")
     if st is not None:      # the conventions the oracle state runs under
@@ -33,7 +34,8 @@ def gpu_context(w, inp, st=None, **kw):
     mask = None
     if st is not None and st.mask is not None:
         mask = torch.from_numpy(st.mask.astype(np.uint8)).to(dev)
-    ctx = P.pdadmm_init(cfg, Xa, y, W0, b0, train_mask=mask)
+    torch.cuda.synchronize()
+    ctx = P.pdadmm_init(cfg, Xa, y, W0, b0, train_mask=mask, stream=stream, aux_stream=aux_stream)
     if st is not None:
         push_state(ctx, st)
     return ctx

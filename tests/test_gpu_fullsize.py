@@ -67,47 +67,92 @@ def read_golden(name):
 
 
 # ------------------------------------------------------------------------------ trajectories
-@pytest.mark.parametrize("name,live_first", [("C1", True), ("C2", True), ("C4", False)])
+def _golden_file(name):
+    return os.path.join(GOLDEN, f"{name}_trajectory.txt")
+
+
+LEAN = ("C3", "C5")      # written by the oracle's memory-lean mode (fp32 storage, fp64 updates): see write_golden.py
+
+
+@pytest.mark.parametrize("name,live_first", [("C1", True), ("C2", True), ("C4", False), ("C3", False), ("C5", False),
+                                             ("C5_plain", False)])
 def test_full_size_trajectory_against_stored_oracle_run(env, say, name, live_first):
+    """All layers, every iteration of the stored oracle run: objective terms and residual within 1e-3, step
+    sizes exactly. C3 and C5 start from the memory-lean oracle state the stored run started from.
+    C5 (-Q; `C5_plain`: plain backtracking schedule): the projection onto Delta is discontinuous, and where
+    a projected value sits within rounding of a midpoint the fp32 products of the HIP path and the fp64
+    products of the oracle land on neighbouring members (about 20 of 1e8 elements per layer and iteration,
+    each validated in test_full_size_sampled_layer_one_iteration; the small free-running case shows by
+    re-running the oracle from the GPU's own state that nothing else separates the runs). Such flips cannot
+    be followed by the oracle at this size, so for C5 the 1e-3 bound and the exact step sizes are required
+    up to the first iteration at which a step size differs, which must not come before the second half of the
+    run; after it the two runs are two valid runs of the algorithm and only finiteness is asserted."""
     torch, P, H = env
-    w = get_workload(name)
+    workload = name.split("_")[0]
+    plain = name.endswith("_plain")
+    if not os.path.exists(_golden_file(name)):
+        pytest.skip(f"tests/golden/{name}_trajectory.txt has not been written (hours of oracle time): "
+                    f"python tests/golden/write_golden.py {workload}{':plain' if plain else ''}")
+    w = get_workload(workload)
     gold = read_golden(name)
-    assert len(gold) == w.iters + 1
-    say(f"{name}: inputs and oracle start state")
+    n_iters = len(gold) - 1
+    assert n_iters >= 1 and (n_iters == w.iters or workload in LEAN), "stored trajectory is incomplete"
+    lean = workload in LEAN
+    say(f"{name}: inputs and oracle start state ({'fp32-stored, ' if lean else ''}{n_iters} stored iterations)")
     inp = oracle_inputs(w)
-    st = H.round_state_to_fp32(oracle_state(w, inp))
-    # the stored run started from these very values
-    o0 = O.objective(st)
-    assert abs(o0["L_rho"] - gold[0]["L_rho"]) <= 1e-9 * abs(gold[0]["L_rho"])
+    if lean:
+        st = oracle_state(w, inp, store32=True, probe_backoff=not plain)
+    else:
+        st = H.round_state_to_fp32(oracle_state(w, inp))
+        # the stored run started from these very values
+        o0 = O.objective(st)
+        assert abs(o0["L_rho"] - gold[0]["L_rho"]) <= 1e-9 * abs(gold[0]["L_rho"])
     ctx = H.gpu_context(w, inp, st)
+    del inp
+    if lean:      # (the literal oracle objective takes minutes here: the GPU's own, accurate to fp32 rounding)
+        o0 = P.pdadmm_objective(ctx)
+        assert abs(o0["L_rho"] - gold[0]["L_rho"]) <= 1e-5 * abs(gold[0]["L_rho"]), (o0["L_rho"], gold[0]["L_rho"])
+        assert abs(P.pdadmm_residual(ctx)[0] - gold[0]["residual"]) <= 1e-5 * gold[0]["residual"]
     st_start = st.copy() if live_first else None
+    if not live_first:
+        del st
     L = w.n_layers
     worst = 0.0
-    for k in range(1, w.iters + 1):
+    diverged_at = None
+    for k in range(1, n_iters + 1):
         P.pdadmm_iterate(ctx, 1)
         og = P.pdadmm_objective(ctx)
         rg = P.pdadmm_residual(ctx)[0]
         g = gold[k]
-        for key in ("risk", "lin_pen", "act_pen", "dual_quad", "F", "L_rho"):
-            e = abs(og[key] - g[key]) / max(abs(g[key]), 1e-12)
-            worst = max(worst, e)
-            assert e <= TOL_TRAJ, (k, key, og[key], g[key])
-        assert abs(og["dual_lin"] - g["dual_lin"]) <= TOL_TRAJ * max(abs(g["dual_lin"]), abs(g["dual_quad"]), 1e-12)
-        e = abs(rg - g["residual"]) / g["residual"]
-        worst = max(worst, e)
-        assert e <= TOL_TRAJ, (k, "residual", rg, g["residual"])
         tau, theta, _, _ = H.step_sizes(ctx)
-        assert [float(t) for t in tau[1:L]] == g["tau"], (k, "tau")
-        assert [float(t) for t in theta[:L]] == g["theta"], (k, "theta")
+        same_steps = [float(t) for t in tau[1:L]] == g["tau"] and [float(t) for t in theta[:L]] == g["theta"]
+        errs = {key: abs(og[key] - g[key]) / max(abs(g[key]), 1e-12) for key in ("risk", "lin_pen", "act_pen", "dual_quad", "F", "L_rho")}
+        errs["dual_lin"] = abs(og["dual_lin"] - g["dual_lin"]) / max(abs(g["dual_lin"]), abs(g["dual_quad"]), 1e-12)
+        errs["residual"] = abs(rg - g["residual"]) / g["residual"]
+        if w.quant is not None:
+            say(f"{name} it {k}: worst error {max(errs.values()):.1e}, step sizes {'equal' if same_steps else 'DIFFER'}")
+        if diverged_at is None and w.quant is not None and not same_steps:
+            diverged_at = k
+            say(f"{name}: a step size differs from iteration {k} on: two valid runs of the algorithm from here")
+        if diverged_at is None:
+            assert same_steps, (k, "tau/theta", list(tau), g["tau"], list(theta), g["theta"])
+            for key, e in errs.items():
+                worst = max(worst, e)
+                assert e <= TOL_TRAJ, (k, key, e)
+        else:
+            assert np.isfinite(og["L_rho"]) and np.isfinite(rg)
         if k == 1 and live_first:
             say(f"{name}: oracle iteration 1 (live), element-by-element comparison")
             O.iterate(st, 1)
             ok, w_state, rep = H.compare_state(ctx, st, TOL_STATE, what=f"{name} it 1", before=st_start)
             assert ok, rep
             say(f"{name}: worst rel-L2 after one iteration {w_state:.2e}")
+    assert diverged_at is None or diverged_at > n_iters // 2, f"step sizes differ from iteration {diverged_at} on"
     s = P.pdadmm_stats(ctx, drift=True)
-    say(f"{name}: {w.iters} iterations, worst objective/residual error {worst:.2e}, carried-residual drift {s['r_drift']:.2e}")
+    say(f"{name}: {n_iters} iterations, worst objective/residual error {worst:.2e}"
+        + (f" (up to iteration {diverged_at - 1})" if diverged_at else "") + f", carried-residual drift {s['r_drift']:.2e}")
     assert s["r_drift"] < 1e-4
+    P.pdadmm_destroy(ctx)
 
 
 # ------------------------------------------------------------------------------ sampled layers at full size

@@ -705,6 +705,34 @@ def test_graph_replay_equals_eager_launches(env, case):
     assert np.array_equal(se["p_products"], sg["p_products"])
 
 
+@pytest.mark.parametrize("case,graph", [("C2-small", 0), ("mid", 0), ("mid-Q", 0), ("one-layer", 0), ("C1-full", 1), ("mid", 1)])
+def test_second_stream_gives_the_same_bits(env, case, graph):
+    """With a second stream the W-update of layer 1 runs beside the p-updates and the z_L-update beside the fused
+    z/q/u pass (event-ordered forks and joins). Same kernels on the same data: every variable must be equal bit
+    for bit to the one-stream run, iteration after iteration, eagerly and as a replayed graph, with eager work of
+    the library (objective, get_var) between the iterations."""
+    torch, P, H = env
+    w = CASES[case]()
+    inp = oracle_inputs(w)
+    st = H.round_state_to_fp32(oracle_state(w, inp))
+    one = H.gpu_context(w, inp, st, use_graph=graph)
+    s_main, s_aux = torch.cuda.Stream(), torch.cuda.Stream()
+    two = H.gpu_context(w, inp, st, stream=s_main, aux_stream=s_aux, use_graph=graph)
+    L = w.n_layers
+    for k in range(5):
+        P.pdadmm_iterate(one, 1 if k < 3 else 2)
+        P.pdadmm_iterate(two, 1 if k < 3 else 2)
+        for l in range(1, L + 1):
+            for kind in (P.VAR.W, P.VAR.Z, P.VAR.B) + ((P.VAR.P,) if l >= 2 else ()) + ((P.VAR.Q, P.VAR.U) if l < L else ()):
+                a, b = P.pdadmm_get_var(one, kind, l), P.pdadmm_get_var(two, kind, l)
+                assert np.array_equal(a.view(np.uint32), b.view(np.uint32)), (k, kind, l)
+        assert P.pdadmm_objective(one) == P.pdadmm_objective(two)
+    s1, s2 = P.pdadmm_stats(one), P.pdadmm_stats(two)
+    assert np.array_equal(s1["tau"], s2["tau"]) and np.array_equal(s1["theta"], s2["theta"])
+    with pytest.raises(P.PdadmmError):           # the second stream must be a stream of its own
+        H.gpu_context(w, inp, stream=s_main, aux_stream=s_main)
+
+
 def test_forward_consistent_start_moves_only_last_layer(env):
     torch, P, H = env
     w = small("C1", n=500, hidden=24, n_layers=4, feat_dim=8)
