@@ -16,8 +16,10 @@ Floating-point numbers are printed with 17 significant digits (round-trip exact 
 C3 and C5 do not fit the host memory in fp64: they run in the oracle's memory-lean mode (variables
 stored as fp32 between updates, every update computed in fp64), and, because one oracle iteration of
 theirs takes a quarter of an hour on one core, with the updates of different layers of one phase running
-side by side in threads (`--workers N`; within a phase of Algorithm 1 the layers are independent, every
-update is still the oracle's own function call). `<name>:plain` runs a -Q workload with
+side by side in forked child processes (`--workers N`; within a phase of Algorithm 1 the layers are
+independent, every update is still the oracle's own function call, and a child hands back what its update
+replaced). Processes, not threads: numpy's BLAS returns wrong products when large matrix products are
+issued from several threads of one process at the same time. `<name>:plain` runs a -Q workload with
 the plain backtracking schedule (every p-update starts at the previous tau divided by eta) instead of
 the probe back-off and writes `<name>_plain_trajectory.txt`.
 """
@@ -26,7 +28,8 @@ from __future__ import annotations
 import os
 import sys
 import time
-from concurrent.futures import ThreadPoolExecutor
+import multiprocessing as mp
+from multiprocessing.connection import wait as wait_for
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(os.path.dirname(HERE))
@@ -51,24 +54,65 @@ def line(k, st):
 LEAN = ("C3", "C5", "C5pq")     # state too large for fp64 storage on the host
 
 
+PER_LAYER = ("W", "b", "z", "p", "q", "u", "tau", "theta", "p_trials", "w_trials", "p_wait", "p_skip")
+_FORK = mp.get_context("fork")
+
+
+def _run_update(conn, st, fn, i):
+    """Child process: one update of one layer on the state as it was at the fork (shared copy-on-write); sends
+    back every per-layer entry of position i that the update rebound (arrays) or may have changed (scalars)."""
+    try:
+        before = {f: getattr(st, f)[i] for f in PER_LAYER if i < len(getattr(st, f))}
+        fn(st, i)
+        out = {}
+        for f, old in before.items():
+            new = getattr(st, f)[i]
+            if not hasattr(new, "shape") or new is not old:
+                out[f] = new
+        conn.send(out)
+    except BaseException as e:          # the parent re-raises
+        conn.send(e)
+    finally:
+        conn.close()
+
+
+def run_phase(st, fn, layers, workers: int) -> None:
+    """fn(st, i) for every i in `layers`, at most `workers` at a time, each in a forked child; the results are
+    written into `st` as they arrive. The updates of one phase read and write disjoint variables (Algorithm 1)."""
+    todo, running = list(layers), {}
+    while todo or running:
+        while todo and len(running) < workers:
+            i = todo.pop(0)
+            recv, send = _FORK.Pipe(duplex=False)
+            proc = _FORK.Process(target=_run_update, args=(send, st, fn, i))
+            proc.start()
+            send.close()
+            running[recv] = (proc, i)
+        for recv in wait_for(list(running)):
+            proc, i = running.pop(recv)
+            got = recv.recv()
+            recv.close()
+            proc.join()
+            if isinstance(got, BaseException):
+                raise got
+            for f, val in got.items():
+                getattr(st, f)[i] = val
+
+
 def iterate_layers_side_by_side(st, workers: int) -> None:
     """One iteration of Algorithm 1, phase after phase as O.iterate does it, with the per-layer updates of a
-    phase spread over `workers` threads (they read and write disjoint variables)."""
+    phase spread over `workers` child processes."""
     L = st.L
-    with ThreadPoolExecutor(max_workers=workers) as ex:
-        def phase(fn, layers):
-            for _ in ex.map(lambda i: fn(st, i), layers):
-                pass
-        phase(O.update_p, range(1, L))
-        phase(O.update_W, range(L))
-        phase(O.update_b, range(L))
-        phase(O.update_z_hidden, range(L - 1))
-        O.update_z_last(st)
-        phase(O.update_q, range(L - 1))
-        phase(O.update_u, range(L - 1))
+    run_phase(st, O.update_p, range(1, L), workers)
+    run_phase(st, O.update_W, range(L), workers)
+    run_phase(st, O.update_b, range(L), workers)
+    run_phase(st, O.update_z_hidden, range(L - 1), workers)
+    O.update_z_last(st)
+    run_phase(st, O.update_q, range(L - 1), workers)
+    run_phase(st, O.update_u, range(L - 1), workers)
 
 
-def write(spec: str, workers: int = 1) -> str:
+def write(spec: str, workers: int = 1, max_iters: int = 0) -> str:
     name, _, mode = spec.partition(":")
     if mode not in ("", "plain"):
         raise SystemExit(f"unknown mode {mode!r}")
@@ -92,7 +136,7 @@ def write(spec: str, workers: int = 1) -> str:
                 f"{'; variables stored as fp32 between updates, updates in fp64' if lean else ''}\n")
         f.write("# k " + " ".join(KEYS) + " residual | tau_2..tau_L | theta_1..theta_L\n")
         f.write(line(0, st) + "\n")
-        for k in range(1, w.iters + 1):
+        for k in range(1, (min(max_iters, w.iters) if max_iters else w.iters) + 1):
             if workers > 1:
                 iterate_layers_side_by_side(st, workers)
             else:
@@ -110,5 +154,10 @@ if __name__ == "__main__":
         k = args.index("--workers")
         n_workers = int(args[k + 1])
         del args[k:k + 2]
+    n_iters = 0                      # --iters K: stop after K iterations (an incomplete file says so by its length)
+    if "--iters" in args:
+        k = args.index("--iters")
+        n_iters = int(args[k + 1])
+        del args[k:k + 2]
     for nm in args or ["C1", "C2"]:
-        print(write(nm, n_workers))
+        print(write(nm, n_workers, n_iters))

@@ -903,8 +903,8 @@ def test_least_squares_risk_whole_iteration_properties():
 
 
 def test_golden_writer_runs_layers_side_by_side_with_the_same_result():
-    # tests/golden/write_golden.py spreads the per-layer updates of a phase over threads for the two largest
-    # workloads: same function calls, same order of phases, so the same run as O.iterate
+    # tests/golden/write_golden.py spreads the per-layer updates of a phase over forked child processes for the two
+    # largest workloads: same function calls, same order of phases, so the same run as O.iterate
     import importlib.util
     import os
     path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "write_golden.py")
