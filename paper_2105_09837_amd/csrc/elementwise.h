@@ -307,11 +307,15 @@ __device__ __forceinline__ float z_closed_form(float s, float q, float slope) {
 // One float4 group per thread: a block covers 4 KiB of each of its nine arrays (at 680 MB per array 9.82 ms against
 // 10.07 ms with two groups and 10.16 ms with four; with cached instead of nontemporal loads or stores 10.6-10.8 ms).
 constexpr int kZquUnroll = 1;
+#ifndef PDADMM_ZQU_THREADS
+#define PDADMM_ZQU_THREADS 256
+#endif
+constexpr int kZquThreads = PDADMM_ZQU_THREADS;   // threads per block of the z/q/u kernel
 __device__ __forceinline__ f32x4 zqu_load(const f32x4* p) { return __builtin_nontemporal_load(p); }
 __device__ __forceinline__ void zqu_store(f32x4* p, f32x4 v) { __builtin_nontemporal_store(v, p); }
 
 // pgrid: Delta when p_{l+1} is kept as 8-bit indices (-Q; levels = 0 otherwise); qgrid: Delta when q is projected too.
-__global__ __launch_bounds__(256) void zqu_kernel(const RowSeg* __restrict__ segs, const BlockMap map,
+__global__ __launch_bounds__(kZquThreads) void zqu_kernel(const RowSeg* __restrict__ segs, const BlockMap map,
                                                   const LayerScal* __restrict__ scal, float rho, float nu,
                                                   float slope, const QuantGrid pgrid, const QuantGrid qgrid) {
   int local;
@@ -322,14 +326,14 @@ __global__ __launch_bounds__(256) void zqu_kernel(const RowSeg* __restrict__ seg
   // flat over the [rows, ld] arrays: a block owns 256*kZquUnroll consecutive float4 groups
   const size_t n4 = (size_t)S.rows * (S.ld / 4);
   const int ld4 = S.ld / 4;
-  const size_t base = (size_t)local * (256 * kZquUnroll) + threadIdx.x;
+  const size_t base = (size_t)local * (kZquThreads * kZquUnroll) + threadIdx.x;
   f32x4 Rv[kZquUnroll], zo[kZquUnroll], qo[kZquUnroll], pn[kZquUnroll], uo[kZquUnroll], mm[kZquUnroll];
   // pad columns (ld is the width rounded up to 4) hold zeros in every input and must stay zero: the closed forms
   // map zeros to zeros, only the projection of q does not when 0 is no member of Delta
   const bool ragged = qgrid.levels > 0 && S.ncols != S.ld;
 #pragma unroll
   for (int k = 0; k < kZquUnroll; ++k) {
-    const size_t i = base + (size_t)k * 256;
+    const size_t i = base + (size_t)k * kZquThreads;
     if (i < n4) {
       Rv[k] = zqu_load(reinterpret_cast<const f32x4*>(S.R) + i);
       zo[k] = zqu_load(reinterpret_cast<const f32x4*>(S.z) + i);
@@ -351,7 +355,7 @@ __global__ __launch_bounds__(256) void zqu_kernel(const RowSeg* __restrict__ seg
   }
 #pragma unroll
   for (int k = 0; k < kZquUnroll; ++k) {
-    const size_t i = base + (size_t)k * 256;
+    const size_t i = base + (size_t)k * kZquThreads;
     if (i < n4) {
       f32x4 zn, Rn, qn, un;
 #pragma unroll

@@ -663,7 +663,8 @@ pdadmm_status build_tables(pdadmm_ctx* c) {
   c->v_w_rest.view(c->g_w, wseg, 1, L);
   // the fused z/q/u pass walks the same table flat: 256*kZquUnroll float4 groups per block
   c->g_rows_hidden.build(c->g_rows_all.dev, rows, L - 1, [](const RowSeg& e) {
-    return chunk_blocks((size_t)e.rows * (e.ld / 4), kZquUnroll);
+    const size_t per_block = (size_t)kZquThreads * kZquUnroll;
+    return (int)std::max<size_t>(((size_t)e.rows * (e.ld / 4) + per_block - 1) / per_block, 1);
   });
   if ((s = upload(c, c->sel_p, sel_p)) != PDADMM_OK) return s;
   if ((s = upload(c, c->sel_w, sel_w)) != PDADMM_OK) return s;
@@ -673,13 +674,17 @@ pdadmm_status build_tables(pdadmm_ctx* c) {
 }
 
 // Launch a grouped kernel once per chunk of its table: kernel(table + first entry, block map, args...).
-template <class T, class K, class... Args>
-void launch_group(pdadmm_ctx* c, const Group<T>& g, K kernel, Args... args) {
+template <int THREADS, class T, class K, class... Args>
+void launch_group_threads(pdadmm_ctx* c, const Group<T>& g, K kernel, Args... args) {
   for (size_t k = 0; k < g.maps.size(); ++k) {
     if (g.maps[k].total <= 0) continue;
-    hipLaunchKernelGGL(kernel, dim3(g.maps[k].total), dim3(256), 0, c->stream, (const T*)(g.dev + g.start[k]),
+    hipLaunchKernelGGL(kernel, dim3(g.maps[k].total), dim3(THREADS), 0, c->stream, (const T*)(g.dev + g.start[k]),
                        g.maps[k], args...);
   }
+}
+template <class T, class K, class... Args>
+void launch_group(pdadmm_ctx* c, const Group<T>& g, K kernel, Args... args) {
+  launch_group_threads<256>(c, g, kernel, args...);
 }
 
 // VECC = true: every problem of the group writes (and reads its epilogue inputs from) workspace arrays,
@@ -888,7 +893,7 @@ pdadmm_status phase_bzqu(pdadmm_ctx* c) {
     if (s != PDADMM_OK) return s;
   }
   if (L > 1) {
-    { TIMED(c, kClsZqu); launch_group(c, c->g_rows_hidden, zqu_kernel, (const LayerScal*)c->scal, g.rho, g.nu, g.leaky_slope,
+    { TIMED(c, kClsZqu); launch_group_threads<kZquThreads>(c, c->g_rows_hidden, zqu_kernel, (const LayerScal*)c->scal, g.rho, g.nu, g.leaky_slope,
                                       g.quantize ? c->grid : QuantGrid{0.f, 0.f, 0},
                                       g.quantize == 2 ? c->grid : QuantGrid{0.f, 0.f, 0}); }
     LAUNCH_CHECK(c, "zqu");

@@ -136,6 +136,7 @@ def write(spec: str, workers: int = 1, max_iters: int = 0) -> str:
                 f"{'; variables stored as fp32 between updates, updates in fp64' if lean else ''}\n")
         f.write("# k " + " ".join(KEYS) + " residual | tau_2..tau_L | theta_1..theta_L\n")
         f.write(line(0, st) + "\n")
+        f.flush()
         for k in range(1, (min(max_iters, w.iters) if max_iters else w.iters) + 1):
             if workers > 1:
                 iterate_layers_side_by_side(st, workers)

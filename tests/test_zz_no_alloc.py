@@ -21,10 +21,12 @@ def test_static_scratch_entry_point_matches_gemm_tn_on_two_calls_in_a_row():
         B = torch.from_numpy(rng.standard_normal((K, N)).astype(np.float32)).cuda()
         out = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda")      # output: the caller's
         torch.cuda.synchronize()
-        before = torch.cuda.memory_allocated()
+        # cumulative number of allocations torch has made (frees by a garbage collection of earlier tests' tensors
+        # during the call must not count against it)
+        before = torch.cuda.memory_stats().get("allocation.all.allocated", 0)
         P.pdadmm_gemm_tn_static(A, B, alpha=0.5, splitk=splitk, out=out)
         torch.cuda.synchronize()
-        assert torch.cuda.memory_allocated() == before                                 # no torch allocation either
+        assert torch.cuda.memory_stats().get("allocation.all.allocated", 0) == before  # no torch allocation either
         ref = P.pdadmm_gemm_tn(A, B, alpha=0.5, splitk=splitk)
         torch.cuda.synchronize()
         assert torch.equal(out, ref)
