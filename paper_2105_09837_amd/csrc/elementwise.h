@@ -20,7 +20,8 @@ struct AxpySeg {
   int layer, which;
 };
 
-__global__ __launch_bounds__(256) void axpy_kernel(const AxpySeg* __restrict__ segs, const BlockMap map,
+constexpr int kAxpyThreads = 64;   // one wave per block, one float4 group per lane (C5, r += W d: 2.60 -> 2.49 ms against 256)
+__global__ __launch_bounds__(kAxpyThreads) void axpy_kernel(const AxpySeg* __restrict__ segs, const BlockMap map,
                                                    const LayerScal* __restrict__ scal) {
   int local;
   const int si = find_group(map, blockIdx.x, &local);
@@ -32,7 +33,7 @@ __global__ __launch_bounds__(256) void axpy_kernel(const AxpySeg* __restrict__ s
   else s = sc.inv_tau != 0.0f ? -1.0f : 0.0f;
   if (s == 0.0f) return;
   // one float4 group per thread, consecutive blocks own consecutive 4 KiB chunks: a pure stream
-  const size_t i = (size_t)local * 256 + threadIdx.x;
+  const size_t i = (size_t)local * kAxpyThreads + threadIdx.x;
   if (i >= S.n4) return;
   f32x4* y = reinterpret_cast<f32x4*>(S.y) + i;
   const f32x4 a = stream_load(y);
@@ -304,13 +305,11 @@ __device__ __forceinline__ float z_closed_form(float s, float q, float slope) {
 //   q = (rho p_{l+1} + u + nu f(z)) / (rho + nu); r = p_{l+1} - q; u <- u + rho r.
 // In the variant that keeps q on the grid as well (Appendix B, last paragraph) the closed-form q is
 // projected onto Delta before r and u are formed.
-// One float4 group per thread: a block covers 4 KiB of each of its nine arrays (at 680 MB per array 9.82 ms against
-// 10.07 ms with two groups and 10.16 ms with four; with cached instead of nontemporal loads or stores 10.6-10.8 ms).
+// Blocks of ONE wave with one float4 group per lane: a block covers 1 KiB of each of its nine arrays. Measured at
+// 680 MB per array (C3), threads x groups per thread: 64x1 9.21 ms, 256x1 9.63, 128x1 10.08, 512x1 10.01, 256x2 10.07,
+// 256x4 10.16, 64x2 9.95, 64x4 9.76; with cached instead of nontemporal loads or stores 10.6-10.8 ms.
 constexpr int kZquUnroll = 1;
-#ifndef PDADMM_ZQU_THREADS
-#define PDADMM_ZQU_THREADS 256
-#endif
-constexpr int kZquThreads = PDADMM_ZQU_THREADS;   // threads per block of the z/q/u kernel
+constexpr int kZquThreads = 64;
 __device__ __forceinline__ f32x4 zqu_load(const f32x4* p) { return __builtin_nontemporal_load(p); }
 __device__ __forceinline__ void zqu_store(f32x4* p, f32x4 v) { __builtin_nontemporal_store(v, p); }
 
@@ -492,9 +491,12 @@ struct QuantSeg {
 
 // A block owns kQuantUnroll * 256 consecutive float4 groups (one contiguous chunk per array); all loads of a
 // thread are issued before the first projection.
+// 256 threads x 2 groups (C5: 3.36 ms; 256x1 3.53, 256x4 3.45, one-wave blocks 4.49 / 4.08 / 3.49 ms for 1 / 2 / 4 groups:
+// the launches of a round that no layer needs any more are cheaper with fewer blocks)
 constexpr int kQuantUnroll = 2;
+constexpr int kQtThreads = 256;
 
-__global__ __launch_bounds__(256) void quant_trial_kernel(const QuantSeg* __restrict__ segs, const BlockMap map,
+__global__ __launch_bounds__(kQtThreads) void quant_trial_kernel(const QuantSeg* __restrict__ segs, const BlockMap map,
                                                           const LayerScal* __restrict__ scal, QuantGrid grid) {
   __shared__ double red[4];
   int local;
@@ -505,11 +507,11 @@ __global__ __launch_bounds__(256) void quant_trial_kernel(const QuantSeg* __rest
   const int cur = scal[S.layer].cur;
   const uint32_t* pin = reinterpret_cast<const uint32_t*>(S.p8 + (size_t)cur * S.p8_plane);
   uint32_t* pout = reinterpret_cast<uint32_t*>(S.p8 + (size_t)(cur ^ 1) * S.p8_plane);
-  const size_t base = (size_t)local * (256 * kQuantUnroll) + threadIdx.x;
+  const size_t base = (size_t)local * (kQtThreads * kQuantUnroll) + threadIdx.x;
   f32x4 pv[kQuantUnroll], gv[kQuantUnroll];
 #pragma unroll
   for (int j = 0; j < kQuantUnroll; ++j) {
-    const size_t i = base + (size_t)j * 256;
+    const size_t i = base + (size_t)j * kQtThreads;
     if (i < S.n4) {
       pv[j] = dequant4(__builtin_nontemporal_load(pin + i), grid);
       gv[j] = stream_load(reinterpret_cast<const f32x4*>(S.g) + i);
@@ -518,7 +520,7 @@ __global__ __launch_bounds__(256) void quant_trial_kernel(const QuantSeg* __rest
   double ds = 0.0;
 #pragma unroll
   for (int j = 0; j < kQuantUnroll; ++j) {
-    const size_t i = base + (size_t)j * 256;
+    const size_t i = base + (size_t)j * kQtThreads;
     if (i >= S.n4) continue;
     const int col0 = (int)((i * 4) % (size_t)S.ld);
     f32x4 dv;
@@ -541,7 +543,7 @@ __global__ __launch_bounds__(256) void quant_trial_kernel(const QuantSeg* __rest
     reinterpret_cast<f32x4*>(S.d)[i] = dv;       // re-read by the product W d that follows
     pout[i] = (uint32_t)iv.x | ((uint32_t)iv.y << 8) | ((uint32_t)iv.z << 16) | ((uint32_t)iv.w << 24);
   }
-  const double tot = block_sum_256(ds, red);
+  const double tot = kQtThreads == 64 ? wave_sum(ds) : block_sum_256(ds, red);
   if (threadIdx.x == 0) S.dpart[local] = tot;
 }
 

@@ -53,6 +53,11 @@ inline int chunk_blocks(size_t n4, int per_thread) {
   const size_t per_block = (size_t)256 * per_thread;
   return (int)std::max<size_t>((n4 + per_block - 1) / per_block, 1);
 }
+inline int axpy_blocks(size_t n4) { return (int)std::max<size_t>((n4 + kAxpyThreads - 1) / kAxpyThreads, 1); }
+inline int qt_blocks(size_t n4) {
+  const size_t per_block = (size_t)kQtThreads * kQuantUnroll;
+  return (int)std::max<size_t>((n4 + per_block - 1) / per_block, 1);
+}
 inline int flat_blocks(size_t n4) {
   size_t b = (n4 + 1023) / 1024;
   return (int)std::min<size_t>(std::max<size_t>(b, 1), 2048);
@@ -273,11 +278,11 @@ bool config_ok(const pdadmm_config* c, std::string* why) {
     if (c->dims[i] < 1) return bad("a layer width is < 1");
   if (c->dims[c->n_layers] > 1024) return bad("n_L > 1024 classes is not supported");
   {
-    // a grouped streaming launch covers up to kMaxGroup layers with one block per 256 float4 groups:
+    // a grouped streaming launch covers up to kMaxGroup layers with one block per 64 float4 groups:
     // the block count must fit the 31-bit grid size
     int widest = 0;
     for (int i = 0; i <= c->n_layers; ++i) widest = std::max(widest, c->dims[i]);
-    const double blocks = (double)c->n_nodes * ((widest + 3) / 4) / 256.0 * std::min(c->n_layers * 2, 2 * kMaxGroup);
+    const double blocks = (double)c->n_nodes * ((widest + 3) / 4) / 64.0 * std::min(c->n_layers * 2, 2 * kMaxGroup);
     if (blocks > 2.0e9) return bad("n_nodes x layer width is too large for one grouped launch");
   }
   if (!(c->rho > 0.f) || !(c->nu > 0.f)) return bad("rho and nu must be > 0");
@@ -399,7 +404,7 @@ size_t plan(pdadmm_ctx* c, void* base) {
     b.part_a = cv.take<double>(np);
     b.part_b = cv.take<double>(np);
     // -Q: one partial of ||d||^2 per block of the projection kernel
-    b.part_c = cv.take<double>(Q && i >= 1 ? std::max(np, (size_t)chunk_blocks(in_sz / 4, kQuantUnroll)) : np);
+    b.part_c = cv.take<double>(Q && i >= 1 ? std::max(np, (size_t)qt_blocks(in_sz / 4)) : np);
     b.colpart = cv.take<double>((size_t)b.row_blocks * b.ld_out);
     b.pairpart = cv.take<double>(3 * 2048);
   }
@@ -517,10 +522,10 @@ pdadmm_status build_tables(pdadmm_ctx* c) {
       s.part_g = b.part_a; s.ng = P.nblk; s.part_t = b.part_b; s.nt = T.nblk; s.stride_t = 1; s.layer = i;
       sel_p.push_back(s);
       AxpySeg a{};
-      a.y = b.p; a.x = b.g; a.n4 = (size_t)N * b.ld_in / 4; a.nblk = chunk_blocks(a.n4, 1); a.layer = i;
+      a.y = b.p; a.x = b.g; a.n4 = (size_t)N * b.ld_in / 4; a.nblk = axpy_blocks(a.n4); a.layer = i;
       a.which = kScaleInvTau;
       AxpySeg r{};
-      r.y = b.R; r.x = b.T; r.n4 = (size_t)N * b.ld_out / 4; r.nblk = chunk_blocks(r.n4, 1); r.layer = i;
+      r.y = b.R; r.x = b.T; r.n4 = (size_t)N * b.ld_out / 4; r.nblk = axpy_blocks(r.n4); r.layer = i;
       r.which = kScaleInvTau;
       if (c->spec_p) {                         // only the correction tau_new vs tau_prev is left for p and r
         a.which = r.which = kScaleFixTau;
@@ -536,7 +541,7 @@ pdadmm_status build_tables(pdadmm_ctx* c) {
         QuantSeg qs{};
         qs.p8 = b.pidx; qs.p8_plane = b.idx_plane; qs.g = b.g; qs.d = b.d; qs.dpart = b.part_c;
         qs.n4 = (size_t)N * b.ld_in / 4; qs.ncols = b.n_in; qs.ld = b.ld_in;
-        qs.nblk = chunk_blocks(qs.n4, kQuantUnroll); qs.layer = i;
+        qs.nblk = qt_blocks(qs.n4); qs.layer = i;
         quant.push_back(qs);
         SelectDesc sq{};
         sq.part_g = b.part_c; sq.ng = qs.nblk; sq.part_t = b.part_b; sq.nt = T.nblk; sq.stride_t = 1; sq.layer = i;
@@ -735,7 +740,7 @@ pdadmm_status phase_p(pdadmm_ctx* c) {
                        g.bt_eta, g.bt_max_trials, c->err); }
     LAUNCH_CHECK(c, "select tau");
     if (!c->spec_p) {
-      { TIMED(c, kClsPStep); launch_group(c, c->g_pstep, axpy_kernel, (const LayerScal*)c->scal); }
+      { TIMED(c, kClsPStep); launch_group_threads<kAxpyThreads>(c, c->g_pstep, axpy_kernel, (const LayerScal*)c->scal); }
       LAUNCH_CHECK(c, "p step");
     } else {
       { TIMED(c, kClsPStep); launch_group(c, c->g_pfix, axpy_fix_kernel, (const LayerScal*)c->scal); }
@@ -754,7 +759,7 @@ pdadmm_status phase_p(pdadmm_ctx* c) {
   constexpr int kRoundsPerRead = 2;
   for (int round = 0; round <= g.bt_max_trials; round += kRoundsPerRead) {
     for (int r = 0; r < kRoundsPerRead; ++r) {
-      { TIMED(c, kClsQuantTrial); launch_group(c, c->g_quant, quant_trial_kernel, (const LayerScal*)c->scal, c->grid); }
+      { TIMED(c, kClsQuantTrial); launch_group_threads<kQtThreads>(c, c->g_quant, quant_trial_kernel, (const LayerScal*)c->scal, c->grid); }
       LAUNCH_CHECK(c, "quant trial");
       { TIMED(c, kClsGemmTrial); launch_gemm<true, EpiStoreNorm, true>(c, c->g_ptrial, 1); }
       LAUNCH_CHECK(c, "gemm qtrial");
@@ -770,7 +775,7 @@ pdadmm_status phase_p(pdadmm_ctx* c) {
   }
   // the accepted candidate already sits in the index plane that the selection has made current; what is left
   // is the residual r += W d of the layers that took a step
-  { TIMED(c, kClsQuantApply); launch_group(c, c->g_qapply_r, axpy_kernel, (const LayerScal*)c->scal); }
+  { TIMED(c, kClsQuantApply); launch_group_threads<kAxpyThreads>(c, c->g_qapply_r, axpy_kernel, (const LayerScal*)c->scal); }
   LAUNCH_CHECK(c, "quant apply R");
   return PDADMM_OK;
 }
