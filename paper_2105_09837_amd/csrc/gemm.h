@@ -221,9 +221,10 @@ struct EpiBiasAct {   // C = acc + b[col], passed through f when beta != 0 (forw
 
 // Tile configuration: block tile BM x BN x BK, 4 waves arranged WM x WN, each wave owns
 // (BM/WM) x (BN/WN) as a grid of 32x32 MFMA blocks.
-template <int BM_, int BN_, int BK_, int WM_, int WN_>
+// MINB: blocks per compute unit the kernel is compiled for (bounds the registers per lane).
+template <int BM_, int BN_, int BK_, int WM_, int WN_, int MINB_ = 3>
 struct TileCfg {
-  static constexpr int BM = BM_, BN = BN_, BK = BK_, WM = WM_, WN = WN_;
+  static constexpr int BM = BM_, BN = BN_, BK = BK_, WM = WM_, WN = WN_, MINB = MINB_;
   static constexpr int TM = BM / WM / 32, TN = BN / WN / 32;   // MFMA blocks per wave
   static constexpr int LDA = BM + 4, LDB = BN + 4;              // LDS row strides (floats)
   static_assert(WM * WN == 4, "256 threads = 4 waves");
@@ -530,19 +531,24 @@ __device__ __forceinline__ void gemm_body(const GemmProb& P, const int local, co
     // Row-contiguous epilogue: every wave passes its 64x64 sub-tile through LDS (32 rows at a time, the
     // operand buffers are free now) and then owns whole 16-byte column groups, so all global accesses
     // of the epilogue are coalesced 16-byte loads and stores, a quarter as many as element by element.
-    static_assert(TN * 32 == 64 && 4 * 32 * 64 <= 2 * BUFA + 2 * BUFB, "staging area");
+    // (a wave whose sub-tile is wider than 64 columns takes it 64 columns at a time)
+    static_assert(TN % 2 == 0 && 4 * 32 * 64 <= 2 * BUFA + 2 * BUFB, "staging area");
+    constexpr int CW = BN / Cfg::WN;                   // columns of one wave
+    __shared__ double colred[Epi::kColsum ? 4 : 1][Epi::kColsum ? CW : 1];
     __syncthreads();                                   // all waves are done with the operand buffers
     float* stage = smem + wave * (32 * 64);
     const int rr = lane >> 4, c4 = (lane & 15) * 4;    // row (mod 4) and first column of this lane's groups
-    const int col = n0 + wn * (BN / Cfg::WN) + c4;
+#pragma unroll
+    for (int jj = 0; jj < TN; jj += 2) {
+    const int col = n0 + wn * CW + jj * 32 + c4;
     const int nvalid = P.N - col;                      // columns of the group inside the matrix (>= 4: all)
     double cs0 = 0.0, cs1 = 0.0, cs2 = 0.0, cs3 = 0.0; // column sums of the second output (kColsum)
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
 #pragma unroll
-      for (int j = 0; j < TN; ++j)
+      for (int j = 0; j < 2; ++j)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) stage[(8 * (v >> 2) + 4 * lh + (v & 3)) * 64 + j * 32 + li] = acc[i][j][v];
+        for (int v = 0; v < 16; ++v) stage[(8 * (v >> 2) + 4 * lh + (v & 3)) * 64 + j * 32 + li] = acc[i][jj + j][v];
       __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
       __builtin_amdgcn_wave_barrier();
       __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
@@ -588,21 +594,25 @@ __device__ __forceinline__ void gemm_body(const GemmProb& P, const int local, co
       __builtin_amdgcn_wave_barrier();
     }
     if constexpr (Epi::kColsum) {
-      // lanes l, l+16, l+32, l+48 own the same columns (rows differ): add them up, then the two waves that
-      // share the columns (wm = 0, 1) through LDS; fixed order, one value per column and row tile
-      __shared__ double colred[4][64];
+      // lanes l, l+16, l+32, l+48 own the same columns (rows differ): add them up
       cs0 += __shfl_xor(cs0, 16, kWave); cs1 += __shfl_xor(cs1, 16, kWave);
       cs2 += __shfl_xor(cs2, 16, kWave); cs3 += __shfl_xor(cs3, 16, kWave);
       cs0 += __shfl_xor(cs0, 32, kWave); cs1 += __shfl_xor(cs1, 32, kWave);
       cs2 += __shfl_xor(cs2, 32, kWave); cs3 += __shfl_xor(cs3, 32, kWave);
       if (lane < 16) {
-        colred[wave][c4 + 0] = cs0; colred[wave][c4 + 1] = cs1;
-        colred[wave][c4 + 2] = cs2; colred[wave][c4 + 3] = cs3;
+        colred[wave][jj * 32 + c4 + 0] = cs0; colred[wave][jj * 32 + c4 + 1] = cs1;
+        colred[wave][jj * 32 + c4 + 2] = cs2; colred[wave][jj * 32 + c4 + 3] = cs3;
       }
+    }
+    }
+    if constexpr (Epi::kColsum) {
+      // then the waves that share the columns (wm = 0, 1) through LDS; fixed order, one value per column and
+      // row tile
+      static_assert(Cfg::WM == 2 && BN <= 256, "two waves per column, one thread per column");
       __syncthreads();
       if (tid < BN) {
-        const int w = tid >> 6, c = tid & 63;          // wn, column inside the wave's 64
-        const int gcol = n0 + w * 64 + c;
+        const int w = tid / CW, c = tid % CW;          // wn, column inside the wave's share
+        const int gcol = n0 + tid;
         if (gcol < P.ldc) P.colpart[(size_t)tm * P.ldc + gcol] = colred[w][c] + colred[Cfg::WN + w][c];
       }
     }
@@ -642,10 +652,11 @@ __device__ __forceinline__ void gemm_body(const GemmProb& P, const int local, co
 }
 
 // Grouped launch: block -> (problem, tile) through the table; blocks of one die are contiguous.
-// The second launch bound asks for 3 waves per SIMD (3 blocks per compute unit, 768 on the chip, which the
-// launch plans count on): the compiler then keeps accumulators and staging registers within 168 in all.
+// The second launch bound asks for Cfg::MINB waves per SIMD (for the 128x128 tile 3 blocks per compute unit, 768 on
+// the chip, which the launch plans count on): the compiler then keeps accumulators and staging registers within
+// 168 in all.
 template <class Cfg, bool KCONTIG, class Epi, bool VECC = false, bool P8 = false>
-__global__ __launch_bounds__(256, 3) void gemm_kernel(const GemmProb* __restrict__ probs, const BlockMap map,
+__global__ __launch_bounds__(256, Cfg::MINB) void gemm_kernel(const GemmProb* __restrict__ probs, const BlockMap map,
                                                    const LayerScal* __restrict__ scal, int predicated,
                                                    int panel) {
   const int lb = xcd_remap(blockIdx.x, panel);

@@ -22,7 +22,20 @@ using Tile = TileCfg<128, 128, 16, 2, 2>;
 constexpr int BM = Tile::BM, BN = Tile::BN, BK = Tile::BK;
 // Product blocks resident on the chip at once: 256 compute units x 3 blocks (one wave per SIMD each,
 // 164 registers per lane).
-constexpr int kGemmSlots = 256 * 3;
+constexpr int kGemmSlots = 256 * Tile::MINB;
+// Wide tile for the W-gradient products (contraction over the nodes) of a context whose p_l are fp32: a
+// block's two operand panels are 128 and 256 columns of node-major arrays, so a 128 x 256 output tile reads a
+// quarter less per product than two 128 x 128 tiles, and a wave issues 8 MFMAs per 6 fragment reads instead
+// of 4 per 4. 256 registers per lane: 2 blocks per compute unit. (Measured 4-5 % faster than the square tile
+// at 170k nodes x 1000 columns, where the launch's HBM fetches fall from 5.8 to 1.4 times its operands, and
+// 1-2 % faster at 20k nodes; with p_l as 8-bit indices, whose conversion adds vector work between the MFMAs,
+// 9 % slower, hence the square tile there.)
+using TileWide = TileCfg<128, 256, 16, 2, 2, 2>;
+constexpr int kGemmSlotsWide = 256 * TileWide::MINB;
+// Fewest rounds of resident blocks a wide-tile split plan may have: with one or two rounds the blocks start and
+// end together and nothing hides their prologues and epilogues (measured: 12 % slower than the square tile
+// with one round, faster from four on).
+constexpr int kWideMinRounds = 4;
 
 namespace {
 
@@ -165,6 +178,7 @@ struct pdadmm_ctx {
   Group<QuantSeg> g_quant;
   Group<PairSeg> g_pair;
   int panel = 4;              // tiles per die-local panel in the grouped product launches
+  int tn_bn = 128;            // width of the output tiles of the W-gradient products (128, or 256: TileWide)
   int panel_tn = 16;          // the same for the W-gradient products (all tiles of one node chunk)
   bool dirty = true;
   long iter = 0;
@@ -317,26 +331,36 @@ size_t plan(pdadmm_ctx* c, void* base) {
   const int N = c->N, L = c->L;
   const bool Q = c->cfg.quantize != 0;
   c->lay.assign(L, LayerBufs{});
-  // Split plan of the W-gradient products (contraction over the nodes): every 128x128 output tile of
+  // Split plan of the W-gradient products (contraction over the nodes): every output tile of
   // every layer is cut into the same number of node chunks, so all blocks of the grouped launch take
-  // the same time. The chip holds kGemmSlots product blocks at once (MI355X: 256 CUs x 3 blocks, set
+  // the same time. The chip holds kGemmSlots product blocks at once (MI355X: 256 CUs x 3 blocks, 2 of the wide tile, set
   // by the kernel's register use); the number of chunks is chosen so that the blocks fill whole
   // rounds of that many as exactly as possible, while a block still runs long enough to amortise
   // its start-up (about 1.6 k-tiles, measured).
+  // Tile width: the wide tile unless p_l are indices or its padding (n_in rounded up to 256 instead of 128)
+  // would add more MFMA work than it saves elsewhere (more than 5 %).
+  size_t area_sq = 0, area_wide = 0;
+  for (int i = 0; i < L; ++i) {
+    area_sq += (size_t)cdiv(c->dims[i + 1], BM) * cdiv(c->dims[i], BN) * BN;
+    area_wide += (size_t)cdiv(c->dims[i + 1], BM) * cdiv(c->dims[i], TileWide::BN) * TileWide::BN;
+  }
+  const bool wide = !Q && area_wide * 20 <= area_sq * 21;
+  c->tn_bn = wide ? TileWide::BN : BN;
+  const int slots_tn = wide ? kGemmSlotsWide : kGemmSlots;
   size_t tiles_total = 0;
-  for (int i = 0; i < L; ++i) tiles_total += (size_t)cdiv(c->dims[i + 1], BM) * cdiv(c->dims[i], BN);
+  for (int i = 0; i < L; ++i) tiles_total += (size_t)cdiv(c->dims[i + 1], BM) * cdiv(c->dims[i], c->tn_bn);
   int chunk = cdiv(N, BK) * BK;
   {
     double best = -1.0;
-    for (int rounds = 1; rounds <= 12; ++rounds) {
-      const long want = (long)rounds * kGemmSlots / (long)tiles_total;
+    for (int rounds = wide ? kWideMinRounds : 1; rounds <= 12; ++rounds) {
+      const long want = (long)rounds * slots_tn / (long)tiles_total;
       if (want < 1) continue;
       const int sk = (int)std::min<long>(want, 64);
       int ch = cdiv(cdiv(N, sk), BK) * BK;
       ch = std::max(ch, std::min(256, cdiv(N, BK) * BK));
       const int parts = cdiv(N, ch);
       const double blocks = (double)tiles_total * parts;
-      const double fill = blocks / (std::ceil(blocks / kGemmSlots) * kGemmSlots);
+      const double fill = blocks / (std::ceil(blocks / slots_tn) * slots_tn);
       const double nkt = (double)ch / BK;
       const double eff = fill * nkt / (nkt + 1.6) - 1e-3 * parts;   // small bias towards fewer partial sums
       if (eff > best) {
@@ -467,8 +491,9 @@ GemmProb make_nt(const float* A, int lda, const float* B, int ldb, float* C, int
 }
 
 GemmProb make_tn(const float* A, int lda, const float* B, int ldb, float* part, int ldc, int M, int N, int K,
-                 int splitk, int k_chunk) {
+                 int splitk, int k_chunk, int bn = BN) {
   GemmProb P = make_nt(A, lda, B, ldb, part, ldc, M, N, K);
+  P.tiles_n = cdiv(N, bn);
   P.splitk = splitk;
   P.k_chunk = k_chunk;
   P.nblk = P.tiles_m * P.tiles_n * splitk;
@@ -552,7 +577,8 @@ pdadmm_status build_tables(pdadmm_ctx* c) {
       }
     }
     // gradient of phi in W_l: G = nu * R^T p  (contraction over the nodes, split in chunks)
-    GemmProb Wg = make_tn(b.R, b.ld_out, b.p, b.ld_in, b.Gpart, b.ld_in, b.n_out, b.n_in, N, b.splitk, b.k_chunk);
+    GemmProb Wg = make_tn(b.R, b.ld_out, b.p, b.ld_in, b.Gpart, b.ld_in, b.n_out, b.n_in, N, b.splitk, b.k_chunk,
+                          c->tn_bn);
     Wg.layer = i;
     const bool as_idx = Q && i >= 1;
     if (as_idx) as_indices(Wg, b);
@@ -641,7 +667,7 @@ pdadmm_status build_tables(pdadmm_ctx* c) {
     c->panel = std::max(1, std::min(8, cdiv(typical, BN)));
     // W-gradient products: all output tiles of one node chunk read the same two operand panels, so the
     // whole chunk goes to one die (its tiles run together and share the panels through that die's L2)
-    c->panel_tn = std::max(1, std::min(64, cdiv(typical, BM) * cdiv(typical, BN)));
+    c->panel_tn = std::max(1, std::min(64, cdiv(typical, BM) * cdiv(typical, c->tn_bn)));
 
   }
   pdadmm_status s;
@@ -700,6 +726,14 @@ void launch_gemm(pdadmm_ctx* c, const Group<GemmProb>& g, int predicated) {
   const int panel = KC ? c->panel : c->panel_tn;
   for (size_t k = 0; k < g.maps.size(); ++k) {
     if (g.maps[k].total <= 0) continue;
+    if constexpr (!KC && !P8) {
+      if (c->tn_bn == TileWide::BN) {   // the descriptors of this context count their tiles 256 columns wide
+        hipLaunchKernelGGL((gemm_kernel<TileWide, KC, Epi, VECC, P8>), dim3(xcd_padded(g.maps[k].total, panel)),
+                           dim3(256), 0, c->stream, (const GemmProb*)(g.dev + g.start[k]), g.maps[k],
+                           (const LayerScal*)c->scal, predicated, panel);
+        continue;
+      }
+    }
     hipLaunchKernelGGL((gemm_kernel<Tile, KC, Epi, VECC, P8>), dim3(xcd_padded(g.maps[k].total, panel)), dim3(256), 0,
                        c->stream, (const GemmProb*)(g.dev + g.start[k]), g.maps[k], (const LayerScal*)c->scal,
                        predicated, panel);
