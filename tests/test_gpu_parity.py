@@ -169,6 +169,10 @@ CASES = {
     "paper-grid": lambda: dataclasses.replace(scaled_workload("C5", 800, hidden=60, n_layers=4, feat_dim=10),
                                               quant=(-1.0, 20.0, 22)),      # Delta = {-1, 0, 1, ..., 20} (Section 5.1)
     "ragged": lambda: dataclasses.replace(scaled_workload("C2", 1037, hidden=131, n_layers=3, feat_dim=7), n_classes=11),
+    # hidden widths just under 256 and no multiples of 4, odd node count: the W-gradient products take their
+    # 128 x 256 tile here (as at full size), through the guarded loader and with ragged tiles on every side
+    "ragged-wide": lambda: dataclasses.replace(scaled_workload("C2", 1037, hidden=253, n_layers=3, feat_dim=63),
+                                               n_classes=5),
     "leaky-small": lambda: dataclasses.replace(scaled_workload("C2", 1100, hidden=90, n_layers=4, feat_dim=14), slope=0.05),
     # least-squares risk: closed-form z_L in place of FISTA
     "ls-small": lambda: dataclasses.replace(scaled_workload("C2", 900, hidden=70, n_layers=3, feat_dim=9), risk="ls"),
