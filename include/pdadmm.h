@@ -189,7 +189,8 @@ size_t pdadmm_workspace_bytes(const pdadmm_config* cfg);
  * p_1 = X_aug; z_l = W_l p_l + b_l; q_l = f(z_l); p_{l+1} = q_l (projected onto Delta for -Q; with
  * quantize = 2 q_l is projected as well);
  * u_l = 0; tau_l = tau0, theta_l = theta0.
- *  workspace: DEVICE, >= pdadmm_workspace_bytes(cfg), 256-byte aligned, owned by the caller and kept
+ *  workspace: DEVICE, >= pdadmm_workspace_bytes(cfg), 256-byte aligned (4 KiB for the best rate of the streaming
+ *             kernels: every array is placed at a multiple of 4 KiB from its start), owned by the caller and kept
  *             alive until pdadmm_destroy. X_aug [N, n_0], labels [N] int32 in [0, n_L),
  *             train_mask [N] uint8 or NULL (= every node labelled), W0[l-1] [n_l, n_{l-1}],
  *             b0[l-1] [n_l]: all DEVICE, copied during the call (the caller may free them afterwards).
@@ -300,7 +301,8 @@ pdadmm_status pdadmm_plan_info(pdadmm_ctx* ctx, int32_t* fused_updates, int32_t*
  * records). Classes: 0 p-gradient product (W^T r, fused gradient), 1 step-direction products
  * (W g / W d and G p), 2 W-gradient product (r p^T, split over nodes), 3 its partial-sum reduce,
  * 4 step-size selection, 5 p-step, 6 W-step, 7 residual update + column sums, 8 b-step,
- * 9 fused z/q/u update, 10 FISTA for z_L, 11 -Q trial projection, 12 -Q apply, 13 residual refresh.
+ * 9 fused z/q/u update, 10 z_L-update (FISTA, or the closed form of the least-squares risk), 11 -Q trial
+ * projection, 12 -Q residual update r += W d after the search, 13 residual refresh.
  * pdadmm_timing_read synchronises, adds up the elapsed milliseconds and the number of launches per
  * class since the last read into HOST arrays of n_classes >= 14 entries, and clears the records.
  */
