@@ -57,7 +57,7 @@ def elementwise_bytes_per_iteration(dims, n_nodes, quant, fused, trials_per_iter
                     over [N, n_{l-1}] and 3 over [N, n_l], l >= 2;
       resid_colsum  r -= Gp/theta with column sums, 3 passes over [N, n_l], all l (bit 1 clear);
       quant_trial   -Q: per backtracking trial of a layer, reads p_l (p_bytes) and g, writes d (4 B) and the
-                    candidate index (1 B) over [N, n_{l-1}]; `trials_per_iter[l-1]` = measured trials per
+                    candidate index (1 B, 2 B above 256 levels) over [N, n_{l-1}]; `trials_per_iter[l-1]` = measured trials per
                     iteration of layer l;
       quant_apply   -Q, per layer and iteration: what the library does on acceptance (p_l <- Delta[idx]:
                     1 B read + 4 B written per element while p_l is kept as fp32, nothing once p_l is kept as
@@ -72,7 +72,8 @@ def elementwise_bytes_per_iteration(dims, n_nodes, quant, fused, trials_per_iter
     if not fused & 1 and not quant:
         out["p_step"] = sum(12 * e * (dims[i] + dims[i + 1]) for i in range(1, L))
     if quant:
-        out["quant_trial"] = sum(trials_per_iter[i] * (p_bytes + 4 + 4 + 1) * e * dims[i] for i in range(1, L))
+        idx_bytes = p_bytes if p_bytes < 4 else 1        # width of a stored index (2 above 256 levels)
+        out["quant_trial"] = sum(trials_per_iter[i] * (p_bytes + 4 + 4 + idx_bytes) * e * dims[i] for i in range(1, L))
         apply_p = (1 + 4) if p_bytes == 4 else 0
         out["quant_apply"] = sum(apply_p * e * dims[i] + 12 * e * dims[i + 1] for i in range(1, L))
     return out

@@ -48,7 +48,7 @@ typedef struct {
   int32_t quantize;        /* 0: pdADMM-G; 1: pdADMM-G-Q, p_l (l >= 2) restricted to Delta; 2: the variant of
                               Appendix B that also projects every updated q_l onto Delta */
   float q_lo, q_hi;        /* Delta = { q_lo + i*(q_hi-q_lo)/(q_levels-1) }, i = 0..q_levels-1 */
-  int32_t q_levels;        /* 2..256 */
+  int32_t q_levels;        /* 2..65536; up to 256 the library keeps p_l as one byte per element, above as two */
   int32_t fista_iters;     /* fixed number of FISTA steps for z_L (Appendix A); e.g. 20 */
   float bt_eta;            /* backtracking growth factor (> 1), e.g. 2. Every p- and W-update starts at the
                               previous tau (theta) divided by bt_eta and multiplies by bt_eta until the
@@ -95,7 +95,7 @@ enum {
   PDADMM_VAR_U = 5,      /* u_l, l = 1..L-1, [N, n_l] */
   PDADMM_VAR_TAU = 6,    /* tau_l, l = 2..L: one HOST double */
   PDADMM_VAR_THETA = 7,  /* theta_l, l = 1..L: one HOST double */
-  PDADMM_VAR_PIDX = 8,   /* get only, -Q: indices of p_l in Delta, uint8 [N, n_{l-1}], l = 2..L (this is how the library
+  PDADMM_VAR_PIDX = 8,   /* get only, -Q: indices of p_l in Delta, uint8 (uint16 if q_levels > 256) [N, n_{l-1}], l = 2..L (this is how the library
                             keeps p_l in -Q; PDADMM_VAR_P forms the values Delta[index] on the way out and takes
                             the indices of the nearest members on the way in) */
   /* (diagnostics) read-only internals */
@@ -134,13 +134,14 @@ pdadmm_status pdadmm_augment(int32_t n, int64_t nnz, const int32_t* rowptr, cons
 
 /*
  * Projection onto the uniform set Delta (Section 3.3, Appendix B): elementwise
- * argmin_{delta in Delta} |delta - v|. DEVICE in v[count]; DEVICE out idx[count] (uint8) and/or
+ * argmin_{delta in Delta} |delta - v|. DEVICE in v[count]; DEVICE out idx[count] (uint8; uint16 if levels > 256) and/or
  * val[count] (either may be NULL). step = (hi-lo)/(levels-1) in fp32; t = (v-lo)/step;
  * idx = clamp(round-half-even(t), 0, levels-1); delta = lo + idx*step (product, then sum, each
- * rounded to fp32). NaN maps to index 0. levels in 2..256. Asynchronous on `stream`.
+ * rounded to fp32). NaN maps to index 0. levels in 2..65536 (the paper's 8- and 16-bit cases,
+ * Section 5.5, are 256 and 65536). Asynchronous on `stream`.
  */
 pdadmm_status pdadmm_quantize(const float* v, int64_t count, float lo, float hi, int32_t levels,
-                              uint8_t* idx, float* val, void* stream);
+                              void* idx, float* val, void* stream);
 
 /* ------------------------------------------------------------------------------------------------
  * DIAGNOSTICS. The entry points and variable kinds marked "diagnostics" below (pdadmm_gemm_nt/_tn,
@@ -289,8 +290,8 @@ pdadmm_status pdadmm_stats(pdadmm_ctx* ctx, double* tau, double* theta, int32_t*
  * A clear bit means separate streaming kernels apply that update. wgrad_split (L entries): number of
  * node-range chunks the r p^T product of each layer is split into. wtrial_split: number of chunks the
  * contraction of the G p products is split into (1 = not split). p_bytes: bytes per element in which p_l
- * (l >= 2) is resident: 4 (fp32) for pdADMM-G, 1 for -Q, where p_l is a member of Delta and only its 8-bit index is
- * kept (Appendix B, last paragraph; the values are formed where they are consumed: in the operand loads of the
+ * (l >= 2) is resident: 4 (fp32) for pdADMM-G; 1 for -Q (2 if q_levels > 256), where p_l is a member of Delta and
+ * only its index is kept (Appendix B, last paragraph; the values are formed where they are consumed: in the operand loads of the
  * products and in the streaming kernels). Does not synchronise. */
 pdadmm_status pdadmm_plan_info(pdadmm_ctx* ctx, int32_t* fused_updates, int32_t* wgrad_split, int32_t* wtrial_split,
                                int32_t* p_bytes);

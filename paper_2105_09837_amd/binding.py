@@ -226,7 +226,7 @@ def pdadmm_quantize(v, lo: float, hi: float, levels: int, want_idx=True, want_va
     import torch
     lib = load_library()
     _dev_f32(v, "pdadmm_quantize")
-    idx = torch.empty(v.shape, dtype=torch.uint8, device=v.device) if want_idx else None
+    idx = torch.empty(v.shape, dtype=torch.uint8 if levels <= 256 else torch.uint16, device=v.device) if want_idx else None
     val = torch.empty_like(v) if want_val else None
     _check(lib.pdadmm_quantize(_ptr(v), v.numel(), lo, hi, levels, _ptr(idx), _ptr(val), _stream_ptr(stream)),
            "pdadmm_quantize")
@@ -370,10 +370,11 @@ def pdadmm_get_var(ctx: Context, kind: int, layer: int, to_host: bool = True):
         _check(lib.pdadmm_get_var(ctx.handle, kind, layer, C.addressof(v)), "pdadmm_get_var", ctx)
         return (int(v[0]), int(v[1]))
     shape = _var_shape(ctx, kind, layer)
+    wide = kind == VAR.PIDX and ctx.cfg.q_levels > 256      # indices of two bytes
     if to_host:
-        out = np.empty(shape, dtype=np.uint8 if kind == VAR.PIDX else np.float32)
+        out = np.empty(shape, dtype=(np.uint16 if wide else np.uint8) if kind == VAR.PIDX else np.float32)
     else:
-        out = torch.empty(shape, dtype=torch.uint8 if kind == VAR.PIDX else torch.float32,
+        out = torch.empty(shape, dtype=(torch.uint16 if wide else torch.uint8) if kind == VAR.PIDX else torch.float32,
                           device=ctx.workspace.device)
     _check(lib.pdadmm_get_var(ctx.handle, kind, layer, _ptr(out)), "pdadmm_get_var", ctx)
     return out

@@ -115,6 +115,7 @@ __device__ __forceinline__ float act_fn(float z, float slope) { return z > 0.0f 
 struct QuantGrid {
   float lo, step;
   int levels;
+  int ib;   // bytes per stored index: 1 for up to 256 levels, 2 for up to 65536
 };
 
 // Single fp32 operations that the compiler may not fuse with their neighbours into a fused
@@ -158,6 +159,40 @@ __device__ __forceinline__ f32x4 dequant4(uint32_t packed, const QuantGrid g) {
   v.w = quant_value((int)(packed >> 24), g);
   return v;
 }
+// The same for 16-bit indices (grids of more than 256 levels): element j in bits 16 (j % 2) .. of word j / 2.
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ f32x4 dequant4(u32x2 packed, const QuantGrid g) {
+  f32x4 v;
+  v.x = quant_value((int)(packed.x & 0xffffu), g);
+  v.y = quant_value((int)(packed.x >> 16), g);
+  v.z = quant_value((int)(packed.y & 0xffffu), g);
+  v.w = quant_value((int)(packed.y >> 16), g);
+  return v;
+}
 typedef const uint8_t PD_GLOBAL* gcu8;
+// Four consecutive indices as they lie in memory, by index width in bytes.
+template <int IB> struct PackedIdx { typedef uint32_t type; };
+template <> struct PackedIdx<2> { typedef u32x2 type; };
+
+// Group i4 (elements 4 i4 .. 4 i4 + 3) of an index plane, as values / from indices; the width comes with the grid.
+// The plane is 8-byte aligned (the library's planes start on 256-byte boundaries).
+// (IB = 0: width read from the grid at run time; the streaming kernels of the iteration are compiled per width)
+template <int IB = 0>
+__device__ __forceinline__ f32x4 load_members4(const uint8_t* plane, size_t i4, const QuantGrid g) {
+  if (IB == 2 || (IB == 0 && g.ib == 2))
+    return dequant4(__builtin_nontemporal_load(reinterpret_cast<const u32x2*>(plane) + i4), g);
+  return dequant4(__builtin_nontemporal_load(reinterpret_cast<const uint32_t*>(plane) + i4), g);
+}
+__device__ __forceinline__ void store_indices4(uint8_t* plane, size_t i4, int ib, int i0, int i1, int i2, int i3) {
+  if (ib == 2) {
+    u32x2 w;
+    w.x = (uint32_t)i0 | ((uint32_t)i1 << 16);
+    w.y = (uint32_t)i2 | ((uint32_t)i3 << 16);
+    reinterpret_cast<u32x2*>(plane)[i4] = w;
+  } else {
+    reinterpret_cast<uint32_t*>(plane)[i4] =
+        (uint32_t)i0 | ((uint32_t)i1 << 8) | ((uint32_t)i2 << 16) | ((uint32_t)i3 << 24);
+  }
+}
 
 }  // namespace pdadmm

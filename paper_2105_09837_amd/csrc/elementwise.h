@@ -314,6 +314,8 @@ __device__ __forceinline__ f32x4 zqu_load(const f32x4* p) { return __builtin_non
 __device__ __forceinline__ void zqu_store(f32x4* p, f32x4 v) { __builtin_nontemporal_store(v, p); }
 
 // pgrid: Delta when p_{l+1} is kept as 8-bit indices (-Q; levels = 0 otherwise); qgrid: Delta when q is projected too.
+// IB: bytes per index of p_{l+1} (1 or 2; ignored when p_{l+1} is fp32).
+template <int IB>
 __global__ __launch_bounds__(kZquThreads) void zqu_kernel(const RowSeg* __restrict__ segs, const BlockMap map,
                                                   const LayerScal* __restrict__ scal, float rho, float nu,
                                                   float slope, const QuantGrid pgrid, const QuantGrid qgrid) {
@@ -338,7 +340,7 @@ __global__ __launch_bounds__(kZquThreads) void zqu_kernel(const RowSeg* __restri
       zo[k] = zqu_load(reinterpret_cast<const f32x4*>(S.z) + i);
       qo[k] = zqu_load(reinterpret_cast<const f32x4*>(S.q) + i);
       if (p8) {
-        pn[k] = dequant4(__builtin_nontemporal_load(reinterpret_cast<const uint32_t*>(p8) + i), pgrid);
+        pn[k] = load_members4<IB>(p8, i, pgrid);
         if (S.ncols != S.ld) {        // index 0 in a pad column stands for no value
           const int col0 = (int)(i % (size_t)ld4) * 4;
 #pragma unroll
@@ -496,6 +498,7 @@ struct QuantSeg {
 constexpr int kQuantUnroll = 2;
 constexpr int kQtThreads = 256;
 
+template <int IB>
 __global__ __launch_bounds__(kQtThreads) void quant_trial_kernel(const QuantSeg* __restrict__ segs, const BlockMap map,
                                                           const LayerScal* __restrict__ scal, QuantGrid grid) {
   __shared__ double red[4];
@@ -505,15 +508,15 @@ __global__ __launch_bounds__(kQtThreads) void quant_trial_kernel(const QuantSeg*
   if (!scal[S.layer].active) return;
   const float t = scal[S.layer].trial_t;
   const int cur = scal[S.layer].cur;
-  const uint32_t* pin = reinterpret_cast<const uint32_t*>(S.p8 + (size_t)cur * S.p8_plane);
-  uint32_t* pout = reinterpret_cast<uint32_t*>(S.p8 + (size_t)(cur ^ 1) * S.p8_plane);
+  const uint8_t* pin = S.p8 + (size_t)cur * S.p8_plane;
+  uint8_t* pout = S.p8 + (size_t)(cur ^ 1) * S.p8_plane;
   const size_t base = (size_t)local * (kQtThreads * kQuantUnroll) + threadIdx.x;
   f32x4 pv[kQuantUnroll], gv[kQuantUnroll];
 #pragma unroll
   for (int j = 0; j < kQuantUnroll; ++j) {
     const size_t i = base + (size_t)j * kQtThreads;
     if (i < S.n4) {
-      pv[j] = dequant4(__builtin_nontemporal_load(pin + i), grid);
+      pv[j] = load_members4<IB>(pin, i, grid);
       gv[j] = stream_load(reinterpret_cast<const f32x4*>(S.g) + i);
     }
   }
@@ -524,13 +527,13 @@ __global__ __launch_bounds__(kQtThreads) void quant_trial_kernel(const QuantSeg*
     if (i >= S.n4) continue;
     const int col0 = (int)((i * 4) % (size_t)S.ld);
     f32x4 dv;
-    uchar4 iv;
+    struct { int x, y, z, w; } iv;
 #define PDADMM_QT(c, k)                                                       \
   {                                                                           \
     if (col0 + k < S.ncols) {                                                 \
       const float v = sub_rn(pv[j].c, div_rn(gv[j].c, t));                    \
       const int id = quant_index(v, grid);                                    \
-      iv.c = (unsigned char)id;                                               \
+      iv.c = id;                                                              \
       dv.c = sub_rn(quant_value(id, grid), pv[j].c);                          \
       ds += (double)dv.c * (double)dv.c;                                      \
     } else {                                                                  \
@@ -541,7 +544,7 @@ __global__ __launch_bounds__(kQtThreads) void quant_trial_kernel(const QuantSeg*
     PDADMM_QT(x, 0) PDADMM_QT(y, 1) PDADMM_QT(z, 2) PDADMM_QT(w, 3)
 #undef PDADMM_QT
     reinterpret_cast<f32x4*>(S.d)[i] = dv;       // re-read by the product W d that follows
-    pout[i] = (uint32_t)iv.x | ((uint32_t)iv.y << 8) | ((uint32_t)iv.z << 16) | ((uint32_t)iv.w << 24);
+    store_indices4(pout, i, IB, iv.x, iv.y, iv.z, iv.w);
   }
   const double tot = kQtThreads == 64 ? wave_sum(ds) : block_sum_256(ds, red);
   if (threadIdx.x == 0) S.dpart[local] = tot;
@@ -618,7 +621,7 @@ __global__ __launch_bounds__(256) void dequantize_kernel(const uint8_t* __restri
                                                          QuantGrid grid, float* __restrict__ val) {
   const size_t stride = (size_t)gridDim.x * 256;
   for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n4; i += stride) {
-    f32x4 v = dequant4(reinterpret_cast<const uint32_t*>(idx)[i], grid);
+    f32x4 v = load_members4(idx, i, grid);
     const int col0 = (int)((i * 4) % (size_t)ld);
 #pragma unroll
     for (int c = 0; c < 4; ++c)
@@ -639,7 +642,7 @@ __global__ __launch_bounds__(256) void quantize_kernel(const float* __restrict__
     const int i1 = col0 + 1 < ncols ? quant_index(x.y, grid) : 0;
     const int i2 = col0 + 2 < ncols ? quant_index(x.z, grid) : 0;
     const int i3 = col0 + 3 < ncols ? quant_index(x.w, grid) : 0;
-    if (idx) reinterpret_cast<uchar4*>(idx)[i] = make_uchar4(i0, i1, i2, i3);
+    if (idx) store_indices4(idx, i, grid.ib, i0, i1, i2, i3);
     if (val) {
       float4 o;
       o.x = col0 + 0 < ncols ? quant_value(i0, grid) : 0.0f;
@@ -656,7 +659,10 @@ __global__ __launch_bounds__(256) void quantize_scalar_kernel(const float* __res
   const size_t stride = (size_t)gridDim.x * 256;
   for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += stride) {
     const int id = quant_index(v[i], grid);
-    if (idx) idx[i] = (uint8_t)id;
+    if (idx) {
+      if (grid.ib == 2) reinterpret_cast<uint16_t*>(idx)[i] = (uint16_t)id;
+      else idx[i] = (uint8_t)id;
+    }
     if (val) val[i] = quant_value(id, grid);
   }
 }
@@ -694,7 +700,7 @@ __global__ __launch_bounds__(256) void pair_reduce_kernel(const PairSeg* __restr
     const float4 u = reinterpret_cast<const float4*>(S.u)[i];
     float4 p;
     if (p8) {
-      const f32x4 v = dequant4(reinterpret_cast<const uint32_t*>(p8)[i], pgrid);
+      const f32x4 v = load_members4(p8, i, pgrid);
       const int col0 = (int)((i * 4) % (size_t)S.ld);
       p.x = col0 + 0 < S.ncols ? v.x : 0.0f;
       p.y = col0 + 1 < S.ncols ? v.y : 0.0f;

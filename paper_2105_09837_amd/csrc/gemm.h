@@ -115,15 +115,19 @@ struct EpiPGradT {
 typedef EpiPGradT<false> EpiPGrad;
 typedef EpiPGradT<true> EpiPGradUpd;
 
-// The same gradient in -Q mode, where p_l is read as 8-bit indices into Delta (P.p8) and becomes a value here.
-struct EpiPGradQ {
+// The same gradient in -Q mode, where p_l is read as indices into Delta (P.p8, IB bytes each) and becomes a
+// value here.
+template <int IB>
+struct EpiPGradQT {
   static constexpr int NS = 1, kBatch = 4;
   static constexpr bool kVec = true, kExtra = false, kColsum = false;
   static constexpr int kScale = 0;
   struct In { float u, p, q; };
-  struct In4 { f32x4 u, q; uint32_t p; };
+  typedef typename PackedIdx<IB>::type Packed;
+  struct In4 { f32x4 u, q; Packed p; };
   __device__ static __forceinline__ In load(const GemmProb& P, size_t i, int) {
-    return In{((gcf)P.e0)[i], quant_value((int)((gcu8)P.p8)[i], P.grid), ((gcf)P.e2)[i]};
+    const int id = IB == 2 ? (int)((const uint16_t PD_GLOBAL*)P.p8)[i] : (int)((gcu8)P.p8)[i];
+    return In{((gcf)P.e0)[i], quant_value(id, P.grid), ((gcf)P.e2)[i]};
   }
   __device__ static __forceinline__ void apply(const GemmProb& P, float* C, size_t i, int, float acc, const In& in,
                                                double& s0, double&) {
@@ -133,7 +137,7 @@ struct EpiPGradQ {
   }
   __device__ static __forceinline__ In4 load4(const GemmProb& P, size_t i) {
     return In4{*reinterpret_cast<gcf4>((gcf)P.e0 + i), *reinterpret_cast<gcf4>((gcf)P.e2 + i),
-               *reinterpret_cast<const uint32_t PD_GLOBAL*>((gcu8)P.p8 + i)};
+               *reinterpret_cast<const Packed PD_GLOBAL*>((gcu8)P.p8 + i * IB)};
   }
   __device__ static __forceinline__ f32x4 apply4(const GemmProb& P, f32x4 acc, const In4& in, float, f32x4&) {
     return P.alpha * acc + in.u + P.beta * (dequant4(in.p, P.grid) - in.q);
@@ -201,8 +205,10 @@ struct EpiForward {   // z = acc + b[col]; q = f(z); p_next = f(z) (projected on
       const int id = P.grid.levels > 0 ? quant_index(a, P.grid) : 0;
       const float aq = P.grid.levels > 0 ? quant_value(id, P.grid) : a;
       ((float PD_GLOBAL*)P.o1)[i] = P.beta != 0.0f ? aq : a;    // beta != 0: q is kept on the grid as well
-      if (P.o8) ((uint8_t PD_GLOBAL*)P.o8)[i] = (uint8_t)id;    // -Q: p_{l+1} is kept as indices
-      else ((float PD_GLOBAL*)P.o2)[i] = aq;
+      if (P.o8) {                                               // -Q: p_{l+1} is kept as indices
+        if (P.grid.ib == 2) ((uint16_t PD_GLOBAL*)P.o8)[i] = (uint16_t)id;
+        else ((uint8_t PD_GLOBAL*)P.o8)[i] = (uint8_t)id;
+      } else ((float PD_GLOBAL*)P.o2)[i] = aq;
     }
   }
 };
@@ -330,14 +336,15 @@ __device__ __forceinline__ void store_operand(float* lds, const f32x4 (&reg)[NV]
   }
 }
 
-// The same two steps for an operand that is stored as 8-bit indices into Delta (p_l in -Q mode; rows of ld
-// bytes, ld a multiple of 4, base 4-byte aligned: the library's own arrays). A thread fetches the four
-// indices of one group as one 32-bit word from an address clamped into the array (whatever a clamped index
-// fetches only reaches output rows/columns that are never stored) and turns them into values when the tile
-// is written to LDS, where entries whose k lies beyond kend become zero.
-template <bool KCONTIG, int ROWS, int BK, int NV>
-__device__ __forceinline__ void load_operand_u8(uint32_t (&reg)[NV], gcu8 base, int ld, int m0, int mlim, int kb,
-                                                int kend, int tid) {
+// The same two steps for an operand that is stored as indices into Delta of IB bytes each (p_l in -Q mode; rows
+// of ld indices, ld a multiple of 4, base 8-byte aligned: the library's own arrays). A thread fetches the four
+// indices of one group as one 32- or 64-bit word from an address clamped into the array (whatever a clamped
+// index fetches only reaches output rows/columns that are never stored) and turns them into values when the
+// tile is written to LDS, where entries whose k lies beyond kend become zero.
+template <bool KCONTIG, int ROWS, int BK, int NV, int IB>
+__device__ __forceinline__ void load_operand_u8(typename PackedIdx<IB>::type (&reg)[NV], gcu8 base, int ld, int m0,
+                                                int mlim, int kb, int kend, int tid) {
+  typedef typename PackedIdx<IB>::type Packed;
   if (KCONTIG) {
     constexpr int KQ = BK / 4;
     constexpr int RSTEP = 256 / KQ;
@@ -346,7 +353,7 @@ __device__ __forceinline__ void load_operand_u8(uint32_t (&reg)[NV], gcu8 base, 
 #pragma unroll
     for (int h = 0; h < NV; ++h) {
       const int mc = min(m0 + r + RSTEP * h, mlim - 1);
-      reg[h] = *reinterpret_cast<const uint32_t PD_GLOBAL*>(base + (size_t)mc * ld + kc);
+      reg[h] = *reinterpret_cast<const Packed PD_GLOBAL*>(base + ((size_t)mc * ld + kc) * IB);
     }
   } else {
     constexpr int MQ = ROWS / 4;
@@ -356,13 +363,13 @@ __device__ __forceinline__ void load_operand_u8(uint32_t (&reg)[NV], gcu8 base, 
 #pragma unroll
     for (int h = 0; h < NV; ++h) {
       const int kc = min(kb + kr + KSTEP * h, kend - 1);
-      reg[h] = *reinterpret_cast<const uint32_t PD_GLOBAL*>(base + (size_t)kc * ld + mc);
+      reg[h] = *reinterpret_cast<const Packed PD_GLOBAL*>(base + ((size_t)kc * ld + mc) * IB);
     }
   }
 }
 
-template <bool KCONTIG, int ROWS, int BK, int LD, int NV>
-__device__ __forceinline__ void store_operand_u8(float* lds, const uint32_t (&reg)[NV], int kb, int kend, int tid,
+template <bool KCONTIG, int ROWS, int BK, int LD, int NV, class Packed>
+__device__ __forceinline__ void store_operand_u8(float* lds, const Packed (&reg)[NV], int kb, int kend, int tid,
                                                  const QuantGrid grid) {
   if (KCONTIG) {
     constexpr int KQ = BK / 4;
@@ -394,16 +401,16 @@ __device__ __forceinline__ void store_operand_u8(float* lds, const uint32_t (&re
 
 constexpr int kVecBatch = 4;   // 16-byte column groups per lane whose inputs are fetched together
 
-template <bool U8> struct OperandReg { typedef f32x4 type; };
-template <> struct OperandReg<true> { typedef uint32_t type; };
+template <int IB> struct OperandReg { typedef typename PackedIdx<IB>::type type; };   // staging registers of an operand
+template <> struct OperandReg<0> { typedef f32x4 type; };                              // (0: fp32 values)
 
 template <bool B> struct BoolTag { static constexpr bool value = B; };
 
 // VECC: the output and the epilogue's inputs are [*, ld] arrays with ld % 4 == 0 and 16-byte aligned
 // bases (true for the library's own buffers), which allows the row-contiguous epilogue below.
-// P8: the operand that carries p_l (A in the k-contiguous layout, B in the other) is P.p8, 8-bit indices into
-// P.grid, instead of fp32 values.
-template <class Cfg, bool KCONTIG, class Epi, bool VECC, bool P8 = false>
+// P8 = 1 or 2: the operand that carries p_l (A in the k-contiguous layout, B in the other) is P.p8, indices into
+// P.grid of that many bytes each, instead of fp32 values.
+template <class Cfg, bool KCONTIG, class Epi, bool VECC, int P8 = 0>
 __device__ __forceinline__ void gemm_body(const GemmProb& P, const int local, const float escale) {
   constexpr int BM = Cfg::BM, BN = Cfg::BN, BK = Cfg::BK, TM = Cfg::TM, TN = Cfg::TN;
   constexpr int LDA = Cfg::LDA, LDB = Cfg::LDB;
@@ -433,7 +440,7 @@ __device__ __forceinline__ void gemm_body(const GemmProb& P, const int local, co
   const gcf B = (gcf)P.B;
   // the branch-free loader needs 16-byte loads to be legal and, for the m-contiguous layout,
   // whole float4 groups inside the matrix
-  constexpr bool A8 = P8 && KCONTIG, B8 = P8 && !KCONTIG;
+  constexpr int A8 = KCONTIG ? P8 : 0, B8 = KCONTIG ? 0 : P8;
   const bool fast = (A8 || P.vecA) && (B8 || P.vecB) &&
                     (KCONTIG || (P.M % 4 == 0 && P.M >= 4 && (B8 || (P.N % 4 == 0 && P.N >= 4))));
 
@@ -489,16 +496,16 @@ __device__ __forceinline__ void gemm_body(const GemmProb& P, const int local, co
     RegB rb0[NVB], rb1[NVB];
     auto load_tile = [&](int kt, RegA (&ra)[NVA], RegB (&rb)[NVB]) {
       const int kb = kbeg + kt * BK;
-      if constexpr (A8) load_operand_u8<KCONTIG, BM, BK, NVA>(ra, (gcu8)P.p8, P.lda, m0, P.M, kb, kend, tid);
+      if constexpr (A8 != 0) load_operand_u8<KCONTIG, BM, BK, NVA, A8>(ra, (gcu8)P.p8, P.lda, m0, P.M, kb, kend, tid);
       else load_operand<KCONTIG, FAST, BM, BK, NVA>(ra, A, P.lda, m0, P.M, kb, kend, tid);
-      if constexpr (B8) load_operand_u8<KCONTIG, BN, BK, NVB>(rb, (gcu8)P.p8, P.ldb, n0, P.N, kb, kend, tid);
+      if constexpr (B8 != 0) load_operand_u8<KCONTIG, BN, BK, NVB, B8>(rb, (gcu8)P.p8, P.ldb, n0, P.N, kb, kend, tid);
       else load_operand<KCONTIG, FAST, BN, BK, NVB>(rb, B, P.ldb, n0, P.N, kb, kend, tid);
     };
     auto store_tile = [&](int kt, int buf, const RegA (&ra)[NVA], const RegB (&rb)[NVB]) {
       const int kb = kbeg + kt * BK;
-      if constexpr (A8) store_operand_u8<KCONTIG, BM, BK, LDA, NVA>(As + buf * BUFA, ra, kb, kend, tid, P.grid);
+      if constexpr (A8 != 0) store_operand_u8<KCONTIG, BM, BK, LDA, NVA>(As + buf * BUFA, ra, kb, kend, tid, P.grid);
       else store_operand<KCONTIG, FAST, BM, BK, LDA, NVA>(As + buf * BUFA, ra, kb, kend, tid);
-      if constexpr (B8) store_operand_u8<KCONTIG, BN, BK, LDB, NVB>(Bs + buf * BUFB, rb, kb, kend, tid, P.grid);
+      if constexpr (B8 != 0) store_operand_u8<KCONTIG, BN, BK, LDB, NVB>(Bs + buf * BUFB, rb, kb, kend, tid, P.grid);
       else store_operand<KCONTIG, FAST, BN, BK, LDB, NVB>(Bs + buf * BUFB, rb, kb, kend, tid);
     };
     load_tile(0, ra0, rb0);
@@ -655,7 +662,7 @@ __device__ __forceinline__ void gemm_body(const GemmProb& P, const int local, co
 // The second launch bound asks for Cfg::MINB waves per SIMD (for the 128x128 tile 3 blocks per compute unit, 768 on
 // the chip, which the launch plans count on): the compiler then keeps accumulators and staging registers within
 // 168 in all.
-template <class Cfg, bool KCONTIG, class Epi, bool VECC = false, bool P8 = false>
+template <class Cfg, bool KCONTIG, class Epi, bool VECC = false, int P8 = 0>
 __global__ __launch_bounds__(256, Cfg::MINB) void gemm_kernel(const GemmProb* __restrict__ probs, const BlockMap map,
                                                    const LayerScal* __restrict__ scal, int predicated,
                                                    int panel) {
@@ -674,7 +681,7 @@ __global__ __launch_bounds__(256, Cfg::MINB) void gemm_kernel(const GemmProb* __
 
 // Single problem with the descriptor passed by value (no table in device memory needed).
 // (P.p8, if used, must already point at the plane that holds p_l.)
-template <class Cfg, bool KCONTIG, class Epi, bool P8 = false>
+template <class Cfg, bool KCONTIG, class Epi, int P8 = 0>
 __global__ __launch_bounds__(256) void gemm_one_kernel(const GemmProb P, int panel) {
   const int lb = xcd_remap(blockIdx.x, panel);
   if (lb >= P.nblk) return;

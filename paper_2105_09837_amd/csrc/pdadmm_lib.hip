@@ -83,9 +83,10 @@ struct LayerBufs {
   int wt_split, wt_chunk;   // number of such chunks (1 = the product is not split) and their length
   float* p;                 // input of the layer, [N, ld_in] fp32 (null for l >= 2 in -Q: p_l is kept as indices)
   float *g, *d;             // l >= 2: gradient of phi in p, -Q trial direction
-  uint8_t* pidx;            // l >= 2, -Q: two planes of 8-bit indices into Delta, [2][idx_plane]; LayerScal::cur tells
-                            // which one holds p_l, the other takes the candidates of the backtracking trials
-  size_t idx_plane;         // bytes per plane (N * ld_in rounded up to 256)
+  uint8_t* pidx;            // l >= 2, -Q: two planes of indices into Delta (1 byte each, 2 for grids of more than
+                            // 256 levels), [2][idx_plane]; LayerScal::cur tells which one holds p_l, the other
+                            // takes the candidates of the backtracking trials
+  size_t idx_plane;         // bytes per plane (N * ld_in indices rounded up to 256 bytes)
   float *q, *u;             // l < L
   double *part_a, *part_b, *part_c, *colpart, *pairpart;
   int splitk, k_chunk;
@@ -302,7 +303,7 @@ bool config_ok(const pdadmm_config* c, std::string* why) {
   if (!(c->rho > 0.f) || !(c->nu > 0.f)) return bad("rho and nu must be > 0");
   if (c->quantize < 0 || c->quantize > 2) return bad("quantize must be 0, 1 or 2");
   if (c->quantize) {
-    if (c->q_levels < 2 || c->q_levels > 256) return bad("q_levels must be in 2..256");
+    if (c->q_levels < 2 || c->q_levels > 65536) return bad("q_levels must be in 2..65536");
     if (!(c->q_hi > c->q_lo)) return bad("q_hi must exceed q_lo");
   }
   if (c->fista_iters < 0) return bad("fista_iters < 0");
@@ -322,6 +323,7 @@ QuantGrid make_grid(float lo, float hi, int levels) {
   g.lo = lo;
   g.step = (hi - lo) / (float)(levels - 1);
   g.levels = levels;
+  g.ib = levels > 256 ? 2 : 1;
   return g;
 }
 
@@ -416,7 +418,7 @@ size_t plan(pdadmm_ctx* c, void* base) {
       b.g = cv.take<float>(in_sz);
       if (Q) {
         b.d = cv.take<float>(in_sz);
-        b.idx_plane = (in_sz + 255) & ~size_t(255);
+        b.idx_plane = (in_sz * (c->cfg.q_levels > 256 ? 2 : 1) + 255) & ~size_t(255);
         b.pidx = cv.take<uint8_t>(2 * b.idx_plane);
       }
     }
@@ -631,7 +633,7 @@ pdadmm_status build_tables(pdadmm_ctx* c) {
     Fw.e0 = b.b;
     if (i < L - 1) { Fw.o1 = b.q; Fw.o2 = c->lay[i + 1].p; Fw.o8 = Q ? c->lay[i + 1].pidx : nullptr; }
     if (as_idx) as_indices(Fw, b);             // plane 0 holds p_l at the start (LayerScal::cur = 0)
-    Fw.grid = Q ? c->grid : QuantGrid{0.f, 0.f, 0};
+    Fw.grid = Q ? c->grid : QuantGrid{0.f, 0.f, 0, 1};
     Fw.beta = c->cfg.quantize == 2 ? 1.0f : 0.0f;
     Fw.slope = c->cfg.leaky_slope;
     Fw.blk0 = 0;
@@ -720,8 +722,8 @@ void launch_group(pdadmm_ctx* c, const Group<T>& g, K kernel, Args... args) {
 
 // VECC = true: every problem of the group writes (and reads its epilogue inputs from) workspace arrays,
 // which are 16-byte aligned with leading dimensions that are multiples of 4.
-// P8: the operand that carries p_l is read as 8-bit indices (the `..._q` groups of a -Q context).
-template <bool KC, class Epi, bool VECC = false, bool P8 = false>
+// P8 = 1, 2: the operand that carries p_l is read as indices of that many bytes (the `..._q` groups of a -Q context).
+template <bool KC, class Epi, bool VECC = false, int P8 = 0>
 void launch_gemm(pdadmm_ctx* c, const Group<GemmProb>& g, int predicated) {
   const int panel = KC ? c->panel : c->panel_tn;
   for (size_t k = 0; k < g.maps.size(); ++k) {
@@ -743,8 +745,11 @@ void launch_gemm(pdadmm_ctx* c, const Group<GemmProb>& g, int predicated) {
 // A product over all layers: the group that reads p_l as fp32 and, in -Q, the group that reads it as indices.
 template <bool KC, class Epi, bool VECC>
 void launch_gemm_all(pdadmm_ctx* c, const Group<GemmProb>& f, const Group<GemmProb>& q) {
-  launch_gemm<KC, Epi, VECC, false>(c, f, 0);
-  if (q.count > 0) launch_gemm<KC, Epi, VECC, true>(c, q, 0);
+  launch_gemm<KC, Epi, VECC, 0>(c, f, 0);
+  if (q.count > 0) {
+    if (c->grid.ib == 2) launch_gemm<KC, Epi, VECC, 2>(c, q, 0);
+    else launch_gemm<KC, Epi, VECC, 1>(c, q, 0);
+  }
 }
 
 pdadmm_status refresh_residual(pdadmm_ctx* c) {
@@ -762,7 +767,8 @@ pdadmm_status phase_p(pdadmm_ctx* c) {
   if (L < 2) return PDADMM_OK;
   const pdadmm_config& g = c->cfg;
   if (c->spec_p) { TIMED(c, kClsGemmPGrad); launch_gemm<true, EpiPGradUpd, true>(c, c->g_pgrad, 0); }
-  else if (g.quantize) { TIMED(c, kClsGemmPGrad); launch_gemm<true, EpiPGradQ, true>(c, c->g_pgrad, 0); }
+  else if (g.quantize && c->grid.ib == 2) { TIMED(c, kClsGemmPGrad); launch_gemm<true, EpiPGradQT<2>, true>(c, c->g_pgrad, 0); }
+  else if (g.quantize) { TIMED(c, kClsGemmPGrad); launch_gemm<true, EpiPGradQT<1>, true>(c, c->g_pgrad, 0); }
   else { TIMED(c, kClsGemmPGrad); launch_gemm<true, EpiPGrad, true>(c, c->g_pgrad, 0); }
   LAUNCH_CHECK(c, "gemm pgrad");
   if (!g.quantize) {
@@ -793,7 +799,8 @@ pdadmm_status phase_p(pdadmm_ctx* c) {
   constexpr int kRoundsPerRead = 2;
   for (int round = 0; round <= g.bt_max_trials; round += kRoundsPerRead) {
     for (int r = 0; r < kRoundsPerRead; ++r) {
-      { TIMED(c, kClsQuantTrial); launch_group_threads<kQtThreads>(c, c->g_quant, quant_trial_kernel, (const LayerScal*)c->scal, c->grid); }
+      if (c->grid.ib == 2) { TIMED(c, kClsQuantTrial); launch_group_threads<kQtThreads>(c, c->g_quant, quant_trial_kernel<2>, (const LayerScal*)c->scal, c->grid); }
+      else { TIMED(c, kClsQuantTrial); launch_group_threads<kQtThreads>(c, c->g_quant, quant_trial_kernel<1>, (const LayerScal*)c->scal, c->grid); }
       LAUNCH_CHECK(c, "quant trial");
       { TIMED(c, kClsGemmTrial); launch_gemm<true, EpiStoreNorm, true>(c, c->g_ptrial, 1); }
       LAUNCH_CHECK(c, "gemm qtrial");
@@ -932,9 +939,10 @@ pdadmm_status phase_bzqu(pdadmm_ctx* c) {
     if (s != PDADMM_OK) return s;
   }
   if (L > 1) {
-    { TIMED(c, kClsZqu); launch_group_threads<kZquThreads>(c, c->g_rows_hidden, zqu_kernel, (const LayerScal*)c->scal, g.rho, g.nu, g.leaky_slope,
-                                      g.quantize ? c->grid : QuantGrid{0.f, 0.f, 0},
-                                      g.quantize == 2 ? c->grid : QuantGrid{0.f, 0.f, 0}); }
+    const QuantGrid none{0.f, 0.f, 0, 1};
+    const QuantGrid pg = g.quantize ? c->grid : none, qg = g.quantize == 2 ? c->grid : none;
+    if (pg.ib == 2) { TIMED(c, kClsZqu); launch_group_threads<kZquThreads>(c, c->g_rows_hidden, zqu_kernel<2>, (const LayerScal*)c->scal, g.rho, g.nu, g.leaky_slope, pg, qg); }
+    else { TIMED(c, kClsZqu); launch_group_threads<kZquThreads>(c, c->g_rows_hidden, zqu_kernel<1>, (const LayerScal*)c->scal, g.rho, g.nu, g.leaky_slope, pg, qg); }
     LAUNCH_CHECK(c, "zqu");
   }
   if (side && L > 1) return side.join();
@@ -1007,7 +1015,7 @@ pdadmm_status locate(pdadmm_ctx* c, int kind, int layer, bool writing, VarRef* v
       return PDADMM_OK;
     case PDADMM_VAR_PIDX:
       if (writing || !c->cfg.quantize || layer < 2) return fail(c, PDADMM_EINVAL, "PIDX: get only, -Q, l >= 2");
-      *v = {b.pidx, c->N, b.n_in, b.ld_in, 1};      // plane 0; the caller adds the current plane
+      *v = {b.pidx, c->N, b.n_in, b.ld_in, (size_t)c->grid.ib};      // plane 0; the caller adds the current plane
       return PDADMM_OK;
     case PDADMM_VAR_RESID:
       if (writing) return fail(c, PDADMM_EINVAL, "read-only variable");
@@ -1099,15 +1107,16 @@ pdadmm_status pdadmm_augment(int32_t n, int64_t nnz, const int32_t* rowptr, cons
   return PDADMM_OK;
 }
 
-pdadmm_status pdadmm_quantize(const float* v, int64_t count, float lo, float hi, int32_t levels, uint8_t* idx,
+pdadmm_status pdadmm_quantize(const float* v, int64_t count, float lo, float hi, int32_t levels, void* idx_out,
                               float* val, void* stream) {
-  if (count < 0 || levels < 2 || levels > 256 || !(hi > lo)) return PDADMM_EINVAL;
+  if (count < 0 || levels < 2 || levels > 65536 || !(hi > lo)) return PDADMM_EINVAL;
   if (count == 0) return PDADMM_OK;
+  uint8_t* idx = static_cast<uint8_t*>(idx_out);
   if (!v || (!idx && !val)) return PDADMM_EINVAL;
   hipStream_t st = static_cast<hipStream_t>(stream);
   const QuantGrid g = make_grid(lo, hi, levels);
   const bool vec = count % 4 == 0 && aligned16(v) && (!val || aligned16(val)) &&
-                   (!idx || (reinterpret_cast<uintptr_t>(idx) & 3) == 0);
+                   (!idx || (reinterpret_cast<uintptr_t>(idx) & 7) == 0);
   if (vec) {
     const size_t n4 = (size_t)count / 4;
     // ld = a multiple of 4 large enough that no column is masked
@@ -1277,11 +1286,14 @@ pdadmm_status init_common(pdadmm_ctx** out, const pdadmm_config* cfg, void* work
   // (-Q: the epilogue of layer l writes p_{l+1} as indices, which the product of layer l+1 then reads)
   for (int i = 0; i < L; ++i) {
     const GemmProb& F = c->fwd[i];
-    if (F.p8)
-      hipLaunchKernelGGL((gemm_one_kernel<Tile, true, EpiForward, true>), dim3(xcd_padded(F.nblk, c->panel)), dim3(256),
+    if (F.p8 && c->grid.ib == 2)
+      hipLaunchKernelGGL((gemm_one_kernel<Tile, true, EpiForward, 2>), dim3(xcd_padded(F.nblk, c->panel)), dim3(256),
+                         0, c->stream, F, c->panel);
+    else if (F.p8)
+      hipLaunchKernelGGL((gemm_one_kernel<Tile, true, EpiForward, 1>), dim3(xcd_padded(F.nblk, c->panel)), dim3(256),
                          0, c->stream, F, c->panel);
     else
-      hipLaunchKernelGGL((gemm_one_kernel<Tile, true, EpiForward, false>), dim3(xcd_padded(F.nblk, c->panel)), dim3(256),
+      hipLaunchKernelGGL((gemm_one_kernel<Tile, true, EpiForward, 0>), dim3(xcd_padded(F.nblk, c->panel)), dim3(256),
                          0, c->stream, F, c->panel);
     LAUNCH_CHECK(c, "gemm forward");
   }
@@ -1511,7 +1523,7 @@ static pdadmm_status pair_sums(pdadmm_ctx* c, std::vector<double>* act, std::vec
   dq->assign(L, 0.0);
   if (L < 2) return PDADMM_OK;
   launch_group(c, c->g_pair, pair_reduce_kernel, (const LayerScal*)c->scal, c->cfg.leaky_slope,
-               c->cfg.quantize ? c->grid : QuantGrid{0.f, 0.f, 0});
+               c->cfg.quantize ? c->grid : QuantGrid{0.f, 0.f, 0, 1});
   LAUNCH_CHECK(c, "pair reduce");
   std::vector<double> h;
   for (int i = 0; i < L - 1; ++i) {
@@ -1613,7 +1625,7 @@ pdadmm_status pdadmm_stats(pdadmm_ctx* c, double* tau, double* theta, int32_t* p
 pdadmm_status pdadmm_plan_info(pdadmm_ctx* c, int32_t* fused_updates, int32_t* wgrad_split, int32_t* wtrial_split,
                                int32_t* p_bytes) {
   if (!c) return PDADMM_EINVAL;
-  if (p_bytes) *p_bytes = c->cfg.quantize ? 1 : 4;
+  if (p_bytes) *p_bytes = c->cfg.quantize ? c->grid.ib : 4;
   if (fused_updates) *fused_updates = (c->spec_p ? 1 : 0) | (c->spec_w ? 2 : 0);
   if (wgrad_split)
     for (int i = 0; i < c->L; ++i) wgrad_split[i] = c->lay[i].splitk;

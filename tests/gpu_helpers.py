@@ -137,6 +137,14 @@ def compare_state(ctx, st, tol, what="", before=None):
 EPS32 = float(np.finfo(np.float32).eps)
 
 
+def flip_allowance(st, total, base=2e-5, floor=2):
+    """How many of `total` projected elements may land on the other side of a midpoint of Delta: the share of
+    values that lie within fp32 rounding of a midpoint grows in proportion to the number of midpoints per unit
+    length, i.e. with the number of levels; `base` is the share allowed at 256 levels (every differing index is
+    checked on its own by quant_flips / q_flips, this only bounds how many there may be)."""
+    return max(floor, base * total * max(1.0, (st.grid.levels - 1) / 255.0))
+
+
 def quant_flips(P_, ctx, before, st, what="", layers=None, layer_of=None, adopt=True):
     """-Q: indices of every p_l (l >= 2) against the oracle's. They must be equal except where the value
     that is projected, v = p - grad/tau (Appendix B), lies within rounding of the midpoint between two

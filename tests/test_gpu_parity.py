@@ -119,6 +119,29 @@ def test_quantizer_bit_exact(env, grid, count):
     assert np.array_equal(val.cpu().numpy().view(np.uint32), val_ref.view(np.uint32))
 
 
+def test_quantizer_bit_exact_beyond_256_levels(env):
+    """Grids whose indices take two bytes: every member, every midpoint and its two fp32 neighbours."""
+    torch, P, H = env
+    for grid in ((-1.0, 1.0, 65536), (-3.0, 5.0, 1000), (0.0, 1.0, 257)):
+        g = O.Grid(*grid)
+        mem = g.members()
+        mids = ((mem[:-1].astype(F64) + mem[1:].astype(F64)) / 2).astype(F32)
+        adv = np.concatenate([mem, mids, np.nextafter(mids, F32(np.inf)), np.nextafter(mids, F32(-np.inf)),
+                              np.array([np.inf, -np.inf, np.nan, 0.0, -0.0, 1e30, -1e30], dtype=F32)])
+        span = g.hi - g.lo
+        rnd = np.random.default_rng(grid[2]).uniform(g.lo - 0.3 * span, g.hi + 0.3 * span, size=10001).astype(F32)
+        full = np.concatenate([adv, rnd])
+        full = full[:full.size // 4 * 4]
+        for v in (full, full[:-1]):          # a multiple of 4 (16-byte accesses) and not (element by element)
+            _say(f"quantize grid={grid} count={v.size}")
+            idx_ref, val_ref = O.quantize(v, g)
+            idx, val = P.pdadmm_quantize(torch.from_numpy(v).cuda(), *grid)
+            torch.cuda.synchronize()
+            assert idx.dtype == torch.uint16
+            assert np.array_equal(idx.cpu().numpy().astype(np.int32), idx_ref)
+            assert np.array_equal(val.cpu().numpy().view(np.uint32), val_ref.view(np.uint32))
+
+
 # ------------------------------------------------------------------------------ starting point
 @pytest.mark.parametrize("name", ["C1", "C5"])
 def test_forward_init_matches_oracle(env, name):
@@ -166,6 +189,12 @@ CASES = {
     "mid": lambda: scaled_workload("C2", 3300, hidden=260, n_layers=8, feat_dim=10),
     # -Q at the same size: r -= Gp/theta and the column sums ride in the product epilogue there too
     "mid-Q": lambda: scaled_workload("C5", 3300, hidden=260, n_layers=6, feat_dim=10),
+    # Delta of 65536 levels (the paper's 16-bit case, Section 5.5): p_l resident as 16-bit indices; with q on the
+    # grid as well and widths that are no multiples of 4
+    "C5-16bit": lambda: dataclasses.replace(scaled_workload("C5", 1100, hidden=132, n_layers=4, feat_dim=12),
+                                            quant=(-1.0, 1.0, 65536)),
+    "C5pq16-ragged": lambda: dataclasses.replace(scaled_workload("C5", 700, hidden=37, n_layers=4, feat_dim=7),
+                                                 quant=(-1.0, 1.0, 65536), quant_q=True, n_classes=5),
     "paper-grid": lambda: dataclasses.replace(scaled_workload("C5", 800, hidden=60, n_layers=4, feat_dim=10),
                                               quant=(-1.0, 20.0, 22)),      # Delta = {-1, 0, 1, ..., 20} (Section 5.1)
     "ragged": lambda: dataclasses.replace(scaled_workload("C2", 1037, hidden=131, n_layers=3, feat_dim=7), n_classes=11),
@@ -250,11 +279,11 @@ def test_one_iteration_phase_by_phase(env, case, schedule):
             bad, total, worst_mid = H.quant_flips(P, ctx, start, st, what=case)
             _say(f"  -Q indices differing from the oracle's after the p-update: {bad} of {total}, all at midpoints of "
                  f"Delta (worst distance / slack {worst_mid:.2f})")
-            assert bad <= max(2, 2e-5 * total)
+            assert bad <= H.flip_allowance(st, total)
             for l in range(2, st.L + 1):
                 assert P.pdadmm_get_var(ctx, P.VAR.PROBE, l) == (st.p_wait[l - 1], st.p_skip[l - 1])
         if st.quantize_q and phase == P.PHASE.BZQU:
-            assert H.q_flips(P, ctx, before, st, what=case) <= 2
+            assert H.q_flips(P, ctx, before, st, what=case) <= H.flip_allowance(st, total)
         ok, worst, rep = H.compare_state(ctx, st, TOL_STATE, what=f"{case}/{nm}", before=before)
         assert ok, rep
         _check_step_sizes(H, ctx, st)
@@ -313,13 +342,13 @@ def _one_step_against_oracle(P, H, ctx, st, what):
     P.pdadmm_sync(ctx)
     H.oracle_phase(st, P.PHASE.P)
     bad, total, worst_mid = H.quant_flips(P, ctx, start, st, what=what)
-    assert bad <= max(3, 3e-5 * total), (what, bad, total)
+    assert bad <= H.flip_allowance(st, total, 3e-5, 3), (what, bad, total)
     H.oracle_phase(st, P.PHASE.W)
     before = st.copy()
     H.oracle_phase(st, P.PHASE.BZQU)
     if st.quantize_q:                     # the projected q-update has midpoint cases of its own
         bad_q = H.q_flips(P, ctx, before, st, what=what)
-        assert bad_q <= max(3, 3e-5 * total), (what, bad_q)
+        assert bad_q <= H.flip_allowance(st, total, 3e-5, 3), (what, bad_q)
         bad += bad_q
     _check_step_sizes(H, ctx, st)
     for l in range(2, st.L + 1):
@@ -336,7 +365,7 @@ def _one_step_against_oracle(P, H, ctx, st, what):
 
 # (case, schedule, iterations): 20 iterations on the small cases; the larger one (the plan that folds r -= Gp/theta
 # into the product epilogue) takes the oracle seconds per iteration and runs 6
-Q_STEP_CASES = [(c, s, 6 if c == "mid-Q" else 20) for c in ("C5-small", "C5pq-small", "C5pq-ragged", "paper-grid", "mid-Q")
+Q_STEP_CASES = [(c, s, 6 if c == "mid-Q" else 20) for c in ("C5-small", "C5pq-small", "C5pq-ragged", "paper-grid", "mid-Q", "C5-16bit", "C5pq16-ragged")
                 for s in ("backoff", "plain")]
 
 
@@ -372,7 +401,8 @@ def test_quantized_trajectory_step_by_step_along_the_oracle_run(env, case, sched
     _say(f"  stepwise -Q run ({schedule}): {total_bad} one-level index differences at midpoints in {iters} iterations")
 
 
-@pytest.mark.parametrize("case,schedule,iters", [("C5-small", "backoff", 20), ("C5-small", "plain", 20), ("mid-Q", "backoff", 6)])
+@pytest.mark.parametrize("case,schedule,iters", [("C5-small", "backoff", 20), ("C5-small", "plain", 20), ("mid-Q", "backoff", 6),
+                                                 ("C5-16bit", "backoff", 20)])
 def test_quantized_free_run_is_a_chain_of_oracle_steps(env, case, schedule, iters):
     """pdADMM-G-Q, free-running over `iters` iterations. The projection onto Delta is discontinuous: where the
     projected value sits within rounding of a midpoint, fp32 and fp64 products land on different members,

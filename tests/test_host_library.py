@@ -87,8 +87,12 @@ def test_workspace_size_and_config_validation(lib):
     assert nbytes > 3 * state and nbytes < 12 * state
     import dataclasses
     for bad in (dict(rho=0.0), dict(nu=-1.0), dict(n_nodes=0), dict(bt_eta=1.0), dict(dims=[5, 0, 3]),
-                dict(quantize=1, q_levels=1), dict(quantize=1, q_levels=300), dict(quantize=1, q_lo=1.0, q_hi=1.0),
+                dict(quantize=1, q_levels=1), dict(quantize=1, q_levels=65537), dict(quantize=1, q_lo=1.0, q_hi=1.0),
                 dict(quantize=3), dict(quantize=-1), dict(bt_max_trials=0), dict(tau0=0.0)):
         assert P.pdadmm_workspace_bytes(dataclasses.replace(good, **bad)) == 0, bad
+    # p_l resident as indices: one byte each up to 256 levels, two above (two planes per layer)
+    elems = 2 * w.n_nodes * sum(w.dims[1:-1])
+    b8, b16 = (P.pdadmm_workspace_bytes(dataclasses.replace(good, quantize=1, q_levels=lv)) for lv in (256, 257))
+    assert abs((b16 - b8) - elems) <= 1e-3 * elems
     q = dataclasses.replace(good, quantize=1)
     assert P.pdadmm_workspace_bytes(q) > nbytes

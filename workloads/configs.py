@@ -55,6 +55,8 @@ WORKLOADS = {
 }
 # C5 with p and q both on the grid (the variant at the end of Appendix B)
 WORKLOADS["C5pq"] = replace(WORKLOADS["C5"], name="C5pq", quant_q=True)
+# C5 on a grid of 65536 levels (the 16-bit case of Section 5.5)
+WORKLOADS["C5x16"] = replace(WORKLOADS["C5"], name="C5x16", quant=(-1.0, 1.0, 65536))
 
 
 def get_workload(name: str) -> Workload:
