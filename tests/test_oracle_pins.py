@@ -407,6 +407,33 @@ def test_quantizer_is_nearest_member(grid):
     assert O.quantize(np.array([np.nan], dtype=F32), grid)[0][0] == 0
 
 
+@pytest.mark.parametrize("grid", [O.Grid(-1.0, 1.0, 65536), O.Grid(-3.0, 5.0, 1000)])
+def test_quantizer_is_nearest_member_on_fine_grids(grid):
+    # the 16-bit case of Section 5.5 (65536 levels): nearest member by bisection into the sorted members
+    # and a comparison of the two neighbours in fp64
+    rng = np.random.default_rng(12)
+    mem = grid.members()
+    assert mem.dtype == F32 and mem.size == grid.levels and np.all(np.diff(mem) > 0)
+    span = grid.hi - grid.lo
+    mids = ((mem[:-1].astype(F64) + mem[1:].astype(F64)) / 2).astype(F32)
+    v = np.concatenate([rng.uniform(grid.lo - 0.3 * span, grid.hi + 0.3 * span, size=50000).astype(F32), mem, mids,
+                        np.nextafter(mids, F32(np.inf)), np.nextafter(mids, F32(-np.inf))])
+    idx, val = O.quantize(v, grid)
+    assert idx.min() >= 0 and idx.max() < grid.levels
+    assert np.array_equal(val.view(np.uint32), mem[idx].view(np.uint32))
+    m64, v64 = mem.astype(F64), v.astype(F64)
+    hi = np.clip(np.searchsorted(m64, v64), 1, grid.levels - 1)
+    lo = hi - 1
+    brute = np.where(np.abs(m64[lo] - v64) <= np.abs(m64[hi] - v64), lo, hi)
+    dist_got, dist_best = np.abs(m64[idx] - v64), np.abs(m64[brute] - v64)
+    assert np.all(dist_got <= dist_best + 4 * np.finfo(F32).eps * np.maximum(1.0, np.abs(v64)))
+    # equal indices wherever the decision is not within fp32 rounding of a midpoint (t = (v - lo)/step is formed in
+    # fp32: at t near 65535 one ulp of t is 0.004 of a step, and so is one ulp of v - lo near 2)
+    away = np.abs(np.abs(m64[lo] - v64) - np.abs(m64[hi] - v64)) > 0.05 * float(grid.step32)
+    assert away[:50000].mean() > 0.9          # (the random values; the rest sit on members and midpoints)
+    assert np.array_equal(idx[away], brute[away])
+
+
 def test_quantized_run_keeps_p_in_delta():
     w = small("C5", n=90, hidden=10, n_layers=4, feat_dim=4)
     st = oracle_state(w)
