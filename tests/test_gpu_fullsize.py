@@ -219,7 +219,8 @@ def _window_state(w, layer, win, X_aug, y):
 # state is the same sequence of trials; they differ in the bookkeeping afterwards, which the small cases check in
 # both modes); from (2, 1) the back-off schedule skips the probe and starts at tau itself.
 WINDOWS = [("C4", 1, None), ("C4", 26, None), ("C4", 50, None), ("C3", 1, None), ("C3", 5, None), ("C3", 10, None),
-           ("C5", 2, (0, 0)), ("C5", 16, (2, 1))]
+           ("C5", 2, (0, 0)), ("C5", 16, (2, 1)),
+           ("C5x16", 9, (0, 0))]        # Delta of 65536 levels: p_l resident as 16-bit indices
 
 
 @pytest.mark.parametrize("name,layer,probe", WINDOWS)
