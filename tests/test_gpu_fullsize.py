@@ -136,6 +136,12 @@ def test_full_size_trajectory_against_stored_oracle_run(env, say, name, live_fir
         if diverged_at is None and w.quant is not None and not same_steps:
             diverged_at = k
             say(f"{name}: a step size differs from iteration {k} on: two valid runs of the algorithm from here")
+            for l in range(2, L + 1):
+                if float(tau[l - 1]) != g["tau"][l - 2]:
+                    say(f"{name}:   tau_{l}: HIP path {float(tau[l - 1])}, stored run {g['tau'][l - 2]}")
+            for l in range(1, L + 1):
+                if float(theta[l - 1]) != g["theta"][l - 1]:
+                    say(f"{name}:   theta_{l}: HIP path {float(theta[l - 1])}, stored run {g['theta'][l - 1]}")
         if diverged_at is None:
             assert same_steps, (k, "tau/theta", list(tau), g["tau"], list(theta), g["theta"])
             for key, e in errs.items():
